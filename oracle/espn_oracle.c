@@ -1,0 +1,167 @@
+/*
+ * CPU oracle for the late-interaction re-ranking path: candidate gather through
+ * CSR offsets, MaxSim score (Eq. 1, Sec. 2.1), ranked top-k (Sec. 2.1: the
+ * re-ranking stage sorts candidates by score).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the slow, plain definition the GPU path
+ * is checked against; only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it.  It shares no code with the HIP library.
+ *
+ * Everything is evaluated in IEEE double on the 16-bit inputs widened exactly
+ * (Sec. 3.1 fixes the stored vectors at 16 bits; nothing else is rounded).
+ * Loops run in index order; there is no blocking or reordering, so each
+ * function can be read against Eq. 1 by eye.  The only concurrency is an
+ * OpenMP "parallel for" over queries, which does not change any result.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Widen one IEEE-754 binary16 bit pattern to double, exactly.
+ * sign(1) exponent(5, bias 15) fraction(10). */
+double espn_oracle_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1f;
+    int frac = h & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -24);              /* zero and subnormals: frac * 2^-10 * 2^-14 */
+    } else if (expo == 31) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(1024 + frac), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+    }
+    return sign ? -v : v;
+}
+
+/*
+ * Eq. 1 for one (query, document) pair.
+ *   q    : Q rows of d binary16 values (the query embedding matrix E_q)
+ *   doc  : t rows of d binary16 values (the document embedding matrix E_d)
+ * Returns sum over query rows i of max over document rows j of <q_i, doc_j>.
+ * A document with no rows has an empty max, taken as -infinity.
+ */
+double espn_oracle_maxsim_pair(const uint16_t *q, int32_t Q,
+                               const uint16_t *doc, int64_t t, int32_t d)
+{
+    double score = 0.0;
+    for (int32_t i = 0; i < Q; ++i) {
+        double best = -INFINITY;
+        for (int64_t j = 0; j < t; ++j) {
+            double dot = 0.0;
+            for (int32_t c = 0; c < d; ++c) {
+                dot += espn_oracle_half_to_double(q[(int64_t)i * d + c]) *
+                       espn_oracle_half_to_double(doc[j * d + c]);
+            }
+            if (dot > best) best = dot;
+        }
+        score += best;
+    }
+    return score;
+}
+
+/*
+ * Scores of every candidate of every query.
+ *   emb     : packed table, [total_tokens, d] binary16, row-major
+ *   offsets : [n_docs + 1] row offsets; document id owns rows offsets[id] .. offsets[id+1]-1
+ *   q       : [B, Q, d] binary16
+ *   cand    : [B, K] document ids
+ *   scores  : [B, K] out
+ * Returns 0, or -1 if a candidate id is outside [0, n_docs) (nothing is written for it).
+ */
+int espn_oracle_scores(const uint16_t *emb, const int64_t *offsets, int64_t n_docs, int32_t d,
+                       const uint16_t *q, const int64_t *cand,
+                       int32_t B, int32_t Q, int32_t K, double *scores, int32_t threads)
+{
+    int bad = 0;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t kk = 0; kk < K; ++kk) {
+            int64_t id = cand[(int64_t)b * K + kk];
+            if (id < 0 || id >= n_docs) { bad |= 1; continue; }
+            int64_t s = offsets[id], e = offsets[id + 1];
+            scores[(int64_t)b * K + kk] =
+                espn_oracle_maxsim_pair(q + (int64_t)b * Q * d, Q, emb + s * d, e - s, d);
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+typedef struct { double score; int64_t id; int32_t slot; } ranked_t;
+
+/* Ranking order: higher score first; equal scores: lower document id first;
+ * identical (score, id): lower candidate slot first (the two are indistinguishable
+ * in the output, the slot only makes the order total). */
+static int ranked_cmp(const void *pa, const void *pb)
+{
+    const ranked_t *a = (const ranked_t *)pa, *b = (const ranked_t *)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    if (a->id < b->id) return -1;
+    if (a->id > b->id) return 1;
+    return (a->slot > b->slot) - (a->slot < b->slot);
+}
+
+/*
+ * Ranked list: per query, sort all K candidates by the order above and emit the first k.
+ *   scores [B,K], cand [B,K]  ->  out_ids [B,k], out_scores [B,k]
+ * Scores must not be NaN.  Returns 0, or -1 if k is outside [0, K] or memory runs out.
+ */
+int espn_oracle_topk(const double *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k,
+                     int64_t *out_ids, double *out_scores)
+{
+    if (k < 0 || k > K) return -1;
+    ranked_t *r = (ranked_t *)malloc(sizeof(ranked_t) * (size_t)(K > 0 ? K : 1));
+    if (!r) return -1;
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t kk = 0; kk < K; ++kk) {
+            r[kk].score = scores[(int64_t)b * K + kk];
+            r[kk].id = cand[(int64_t)b * K + kk];
+            r[kk].slot = kk;
+        }
+        qsort(r, (size_t)K, sizeof(ranked_t), ranked_cmp);
+        for (int32_t j = 0; j < k; ++j) {
+            out_ids[(int64_t)b * k + j] = r[j].id;
+            out_scores[(int64_t)b * k + j] = r[j].score;
+        }
+    }
+    free(r);
+    return 0;
+}
+
+/* The whole path: scores, then ranked top-k.  all_scores ([B,K]) may be NULL. */
+int espn_oracle_rerank(const uint16_t *emb, const int64_t *offsets, int64_t n_docs, int32_t d,
+                       const uint16_t *q, const int64_t *cand,
+                       int32_t B, int32_t Q, int32_t K, int32_t k,
+                       int64_t *out_ids, double *out_scores, double *all_scores, int32_t threads)
+{
+    double *tmp = all_scores;
+    if (!tmp) {
+        tmp = (double *)malloc(sizeof(double) * (size_t)B * (size_t)K + 8);
+        if (!tmp) return -1;
+    }
+    int rc = espn_oracle_scores(emb, offsets, n_docs, d, q, cand, B, Q, K, tmp, threads);
+    if (rc == 0) rc = espn_oracle_topk(tmp, cand, B, K, k, out_ids, out_scores);
+    if (!all_scores) free(tmp);
+    return rc;
+}
+
+/* Number of threads the parallel loop over queries will use (for reporting). */
+int32_t espn_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
