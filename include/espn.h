@@ -1,0 +1,140 @@
+/*
+ * espn.h - C ABI of the MI355X (gfx950) re-ranking library.
+ *
+ * The library implements the re-ranking stage of multi-vector ("late interaction")
+ * retrieval: for each query, the candidate documents named by a first-stage retriever
+ * (Sec. 2.1; about a thousand per query, Sec. 4.4) are looked up in the token-embedding
+ * table through per-document offsets (Sec. 4: the table's metadata is a list of offsets),
+ * scored with the MaxSim operator (Eq. 1, Sec. 2.1) and ranked by score (Sec. 2.1).
+ *
+ * Conventions for every entry point
+ *   - Plain C types only.  Every pointer argument says whether it is a HOST or a DEVICE
+ *     pointer.  DEVICE pointers must belong to the device the table was loaded on.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the device's null stream).  Calls that
+ *     take a stream only enqueue work on it and return; they never synchronise and never
+ *     allocate or free device memory.
+ *   - The return value is an espn_status.  Argument errors are found on the host before
+ *     anything is enqueued.  Nothing throws or aborts across this boundary.
+ *     espn_last_error() gives a message for the calling thread's last failure.
+ *   - 16-bit embeddings are IEEE binary16 (Sec. 3.1: 16-bit vectors); products are accumulated
+ *     in binary32; scores are binary32.  Inputs must be finite: the rank of a NaN score is
+ *     unspecified.
+ */
+#ifndef ESPN_H
+#define ESPN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum espn_status {
+    ESPN_OK = 0,
+    ESPN_ERR_ARG = 1,          /* null pointer, negative size, bad enum value */
+    ESPN_ERR_SHAPE = 2,        /* sizes that contradict each other (k > K, workspace too small, ...) */
+    ESPN_ERR_OFFSETS = 3,      /* offsets do not start at 0 or decrease somewhere */
+    ESPN_ERR_ID_RANGE = 4,     /* a candidate id outside [0, n_docs) was met by a kernel */
+    ESPN_ERR_NOMEM = 5,        /* host or device allocation failed */
+    ESPN_ERR_HIP = 6,          /* a HIP runtime call failed; see espn_last_error() */
+    ESPN_ERR_UNSUPPORTED = 7,  /* a shape this build has no kernel for */
+    ESPN_ERR_BUSY = 8          /* a staging slot is still in use */
+} espn_status;
+
+typedef struct espn_table espn_table;   /* opaque; owned by the library */
+
+/* Where the packed embedding rows live. */
+enum { ESPN_RESIDENT_HBM = 0, ESPN_RESIDENT_HOST_PINNED = 1 };
+
+/* Static string for a status code. */
+const char *espn_status_string(int status);
+
+/* Message describing the calling thread's most recent failing call ("" if none). */
+const char *espn_last_error(void);
+
+/*
+ * Register an embedding table (Sec. 3.1 / Sec. 4: token vectors per document plus offsets).
+ *
+ *   emb          [total_rows, dim] binary16, row-major, packed: document i owns rows
+ *                offsets[i] .. offsets[i+1]-1.  DEVICE pointer if residency is
+ *                ESPN_RESIDENT_HBM; pinned HOST pointer (hipHostMalloc) if
+ *                ESPN_RESIDENT_HOST_PINNED.  BORROWED: never copied, never freed; the caller
+ *                keeps it alive and unchanged until espn_table_free.  Must be 16-byte aligned.
+ *   offsets_host [n_docs + 1] int64 HOST pointer, in rows; offsets[0] = 0, non-decreasing
+ *                (a document may be empty).  COPIED (to the device); may be freed after the call.
+ *   dim          vector length; a positive multiple of 8.  32 and 128 (the two the paper's
+ *                models use) run on the matrix-core kernel, other values on a slower generic one.
+ *   device       HIP device ordinal.
+ *   out          receives the handle.
+ *
+ * Synchronous (copies the offsets and waits).  Errors: ARG, OFFSETS, NOMEM, HIP.
+ */
+int espn_table_load(const void *emb, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
+                    int32_t residency, int32_t device, espn_table **out);
+
+/* Release a table handle (the offsets copy and the library's own buffers; never `emb`).
+ * Synchronises the device first.  NULL is allowed. */
+int espn_table_free(espn_table *table);
+
+/* Facts about a loaded table; any out pointer may be NULL. */
+int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_rows, int32_t *dim,
+                    int32_t *residency, int32_t *device);
+
+/*
+ * MaxSim scores of every candidate (Eq. 1):
+ *     scores[b,j] = sum over i < Q of  max over rows r of document cand[b,j] of  <q[b,i,:], emb[r,:]>
+ * The candidate gather (offset lookup + streaming the document's rows) is fused into the
+ * scoring kernel; no copy of the rows is made.
+ *
+ *   q       [B, Q, dim] binary16, DEVICE, 16-byte aligned.
+ *   cand    [B, K] int64 document ids, DEVICE.
+ *   scores  [B, K] binary32, DEVICE, written.
+ *   Q       1 .. 32 on the matrix-core kernel; the generic kernel takes any Q with
+ *           Q * dim * 2 bytes <= 64 KiB.
+ * An empty document scores -infinity (empty max).  An id outside [0, n_docs) scores
+ * -infinity and raises the table's error flag (see espn_table_check); nothing is read for it.
+ * B = 0 or K = 0 is a no-op.  Table must be HBM-resident.
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
+ */
+int espn_score(espn_table *table, const void *q, const int64_t *cand,
+               int32_t B, int32_t Q, int32_t K, float *scores, void *stream);
+
+/*
+ * Ranked top-k of scored candidates (Sec. 2.1: sort by score): per query the k best of K in the
+ * order (score descending, then document id ascending), best first.
+ *
+ *   scores      [B, K] binary32, DEVICE.        cand        [B, K] int64, DEVICE.
+ *   out_ids     [B, k] int64, DEVICE, written.  out_scores  [B, k] binary32, DEVICE, written.
+ *   0 <= k <= K.
+ * Errors: ARG, SHAPE, HIP.
+ */
+int espn_topk(const float *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k,
+              int64_t *out_ids, float *out_scores, void *stream);
+
+/* Bytes of DEVICE workspace espn_rerank needs for a batch of B queries with K candidates each. */
+size_t espn_workspace_bytes(int32_t B, int32_t K);
+
+/*
+ * The whole hot path for an HBM-resident table: gather + MaxSim + ranked top-k.
+ * Same as espn_score into the workspace followed by espn_topk, both on `stream`.
+ *
+ *   workspace        DEVICE, 256-byte aligned, at least espn_workspace_bytes(B, K) bytes; scratch
+ *                    owned by the caller, contents undefined afterwards (it holds all B*K scores).
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
+ */
+int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
+                int32_t B, int32_t Q, int32_t K, int32_t k,
+                int64_t *out_ids, float *out_scores,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Wait for `stream` and report errors kernels recorded for this table since the last check:
+ * returns ESPN_ERR_ID_RANGE if any candidate id was out of range, else ESPN_OK; clears the flag.
+ */
+int espn_table_check(espn_table *table, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESPN_H */

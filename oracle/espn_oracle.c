@@ -11,7 +11,8 @@
  * (Sec. 3.1 fixes the stored vectors at 16 bits; nothing else is rounded).
  * Loops run in index order; there is no blocking or reordering, so each
  * function can be read against Eq. 1 by eye.  The only concurrency is an
- * OpenMP "parallel for" over queries, which does not change any result.
+ * OpenMP "parallel for" over (query, candidate) pairs, each of which is computed
+ * by one thread on its own, so the thread count does not change any result.
  */
 #include <math.h>
 #include <stdint.h>
@@ -49,19 +50,25 @@ double espn_oracle_half_to_double(uint16_t h)
 double espn_oracle_maxsim_pair(const uint16_t *q, int32_t Q,
                                const uint16_t *doc, int64_t t, int32_t d)
 {
+    /* widen both matrices once (exact), then evaluate Eq. 1 as written */
+    double *qd = (double *)malloc(sizeof(double) * ((size_t)Q * d + 1));
+    double *dd = (double *)malloc(sizeof(double) * ((size_t)t * d + 1));
+    if (!qd || !dd) { free(qd); free(dd); return NAN; }
+    for (int64_t x = 0; x < (int64_t)Q * d; ++x) qd[x] = espn_oracle_half_to_double(q[x]);
+    for (int64_t x = 0; x < t * d; ++x) dd[x] = espn_oracle_half_to_double(doc[x]);
+
     double score = 0.0;
     for (int32_t i = 0; i < Q; ++i) {
         double best = -INFINITY;
         for (int64_t j = 0; j < t; ++j) {
             double dot = 0.0;
-            for (int32_t c = 0; c < d; ++c) {
-                dot += espn_oracle_half_to_double(q[(int64_t)i * d + c]) *
-                       espn_oracle_half_to_double(doc[j * d + c]);
-            }
+            for (int32_t c = 0; c < d; ++c) dot += qd[(int64_t)i * d + c] * dd[j * d + c];
             if (dot > best) best = dot;
         }
         score += best;
     }
+    free(qd);
+    free(dd);
     return score;
 }
 
@@ -84,7 +91,7 @@ int espn_oracle_scores(const uint16_t *emb, const int64_t *offsets, int64_t n_do
 #else
     (void)threads;
 #endif
-#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
+#pragma omp parallel for collapse(2) schedule(dynamic, 16) reduction(| : bad)
     for (int32_t b = 0; b < B; ++b) {
         for (int32_t kk = 0; kk < K; ++kk) {
             int64_t id = cand[(int64_t)b * K + kk];

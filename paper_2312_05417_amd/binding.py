@@ -1,0 +1,205 @@
+"""Thin Python binding of the C-ABI library (include/espn.h): same names, argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libespn.so.  There is no fallback: if the
+library has not been built, loading fails with an error that says how to build it.
+torch is used for device memory and streams only (data_ptr() and the current stream handle).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libespn.so")
+
+ESPN_OK = 0
+ESPN_ERR_ARG, ESPN_ERR_SHAPE, ESPN_ERR_OFFSETS, ESPN_ERR_ID_RANGE = 1, 2, 3, 4
+ESPN_ERR_NOMEM, ESPN_ERR_HIP, ESPN_ERR_UNSUPPORTED, ESPN_ERR_BUSY = 5, 6, 7, 8
+ESPN_RESIDENT_HBM, ESPN_RESIDENT_HOST_PINNED = 0, 1
+
+_c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+
+# name -> (restype, argtypes); one entry per declaration in include/espn.h
+SIGNATURES = {
+    "espn_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "espn_last_error": (ctypes.c_char_p, []),
+    "espn_table_load": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
+    "espn_table_free": (ctypes.c_int, [_c_p]),
+    "espn_table_info": (ctypes.c_int, [_c_p, ctypes.POINTER(_c_i64), ctypes.POINTER(_c_i64),
+                                       ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
+    "espn_score": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p]),
+    "espn_topk": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
+    "espn_workspace_bytes": (_c_sz, [_c_i32, _c_i32]),
+    "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "espn_table_check": (ctypes.c_int, [_c_p, _c_p]),
+}
+
+_lib = None
+
+
+class EspnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("espn status %d (%s): %s" % (status, status_string(status), message))
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2312_05417_amd.build` "
+                "(or __graft_entry__.build()); there is no non-HIP path" % LIB_PATH)
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)          # AttributeError if the symbol is not exported
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().espn_status_string(int(status)).decode()
+
+
+def last_error() -> str:
+    return lib().espn_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != ESPN_OK:
+        raise EspnError(status, last_error())
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dtype))
+    return t.data_ptr()
+
+
+class Table:
+    """Handle of a loaded table (espn_table_load / espn_table_free).  Keeps `emb` alive."""
+
+    def __init__(self, emb: torch.Tensor, offsets, dim: int | None = None, device: int | None = None):
+        import numpy as np
+        if emb.dtype != torch.float16 or emb.dim() != 2 or not emb.is_contiguous():
+            raise TypeError("emb must be a contiguous [rows, dim] float16 tensor")
+        off = np.ascontiguousarray(np.asarray(offsets, dtype=np.int64))
+        if off.ndim != 1 or off.shape[0] < 1:
+            raise TypeError("offsets must be a 1-d int64 array of n_docs + 1 entries")
+        if int(off[-1]) != emb.shape[0]:
+            raise ValueError("offsets[-1] = %d but emb has %d rows" % (int(off[-1]), emb.shape[0]))
+        if emb.is_cuda:
+            residency, dev = ESPN_RESIDENT_HBM, emb.device.index
+        elif emb.is_pinned():
+            residency, dev = ESPN_RESIDENT_HOST_PINNED, (torch.cuda.current_device() if device is None else device)
+        else:
+            raise TypeError("emb must live in device memory or in pinned host memory")
+        self.emb, self.n_docs, self.dim = emb, off.shape[0] - 1, emb.shape[1] if dim is None else dim
+        self.device = dev
+        self._h = _c_p()
+        _check(lib().espn_table_load(emb.data_ptr(), off.ctypes.data, self.n_docs, self.dim, residency, dev,
+                                     ctypes.byref(self._h)))
+
+    def free(self) -> None:
+        if self._h:
+            lib().espn_table_free(self._h)
+            self._h = _c_p()
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("table has been freed")
+        return self._h
+
+    def info(self) -> dict:
+        n, rows, dim, res, dev = _c_i64(), _c_i64(), _c_i32(), _c_i32(), _c_i32()
+        _check(lib().espn_table_info(self.handle, ctypes.byref(n), ctypes.byref(rows), ctypes.byref(dim),
+                                     ctypes.byref(res), ctypes.byref(dev)))
+        return {"n_docs": n.value, "total_rows": rows.value, "dim": dim.value, "residency": res.value,
+                "device": dev.value}
+
+
+def espn_table_load(emb: torch.Tensor, offsets, device: int | None = None) -> Table:
+    return Table(emb, offsets, device=device)
+
+
+def espn_table_free(table: Table) -> None:
+    table.free()
+
+
+def espn_workspace_bytes(B: int, K: int) -> int:
+    return int(lib().espn_workspace_bytes(B, K))
+
+
+def _batch_shape(q: torch.Tensor, cand: torch.Tensor):
+    if q.dim() != 3 or cand.dim() != 2 or q.shape[0] != cand.shape[0]:
+        raise ValueError("expected q [B,Q,dim] and cand [B,K]")
+    return q.shape[0], q.shape[1], cand.shape[1]
+
+
+def espn_score(table: Table, q: torch.Tensor, cand: torch.Tensor, scores: torch.Tensor | None = None,
+               stream=None) -> torch.Tensor:
+    B, Q, K = _batch_shape(q, cand)
+    if q.shape[2] != table.dim:
+        raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
+    if scores is None:
+        scores = torch.empty((B, K), dtype=torch.float32, device=q.device)
+    if tuple(scores.shape) != (B, K):
+        raise ValueError("scores must be [B,K]")
+    _check(lib().espn_score(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"), B, Q, K,
+                            _dev(scores, torch.float32, "scores"), _stream_ptr(stream)))
+    return scores
+
+
+def espn_topk(scores: torch.Tensor, cand: torch.Tensor, k: int, out_ids: torch.Tensor | None = None,
+              out_scores: torch.Tensor | None = None, stream=None):
+    if scores.dim() != 2 or scores.shape != cand.shape:
+        raise ValueError("scores and cand must both be [B,K]")
+    B, K = scores.shape
+    if out_ids is None:
+        out_ids = torch.empty((B, max(k, 0)), dtype=torch.int64, device=scores.device)
+    if out_scores is None:
+        out_scores = torch.empty((B, max(k, 0)), dtype=torch.float32, device=scores.device)
+    _check(lib().espn_topk(_dev(scores, torch.float32, "scores"), _dev(cand, torch.int64, "cand"), B, K, k,
+                           _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
+                           _stream_ptr(stream)))
+    return out_ids, out_scores
+
+
+def espn_rerank(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_ids: torch.Tensor | None = None,
+                out_scores: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None):
+    """Whole hot path.  Returns (out_ids [B,k] int64, out_scores [B,k] float32)."""
+    B, Q, K = _batch_shape(q, cand)
+    if q.shape[2] != table.dim:
+        raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
+    if out_ids is None:
+        out_ids = torch.empty((B, max(k, 0)), dtype=torch.int64, device=q.device)
+    if out_scores is None:
+        out_scores = torch.empty((B, max(k, 0)), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(espn_workspace_bytes(B, K), dtype=torch.uint8, device=q.device)
+    _check(lib().espn_rerank(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"), B, Q, K, k,
+                             _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
+                             _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_scores
+
+
+def espn_table_check(table: Table, stream=None) -> None:
+    """Waits for the stream; raises EspnError(ESPN_ERR_ID_RANGE) if a kernel met an id out of range."""
+    _check(lib().espn_table_check(table.handle, _stream_ptr(stream)))

@@ -1,0 +1,306 @@
+// C-ABI of the re-ranking library (declarations and contracts: include/espn.h).
+// Host side only validates arguments and enqueues kernels; every step of the path runs in the
+// kernels of maxsim_kernels.h / topk_kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/espn.h"
+#include "maxsim_kernels.h"
+#include "topk_kernels.h"
+
+#define ESPN_API extern "C" __attribute__((visibility("default")))
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+#define HIP_TRY(call)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (call);                                                            \
+        if (e_ != hipSuccess)                                                              \
+            return fail(e_ == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP,         \
+                        "%s failed: %s", #call, hipGetErrorString(e_));                    \
+    } while (0)
+
+// Restores the caller's current device on scope exit.
+struct DeviceScope {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceScope(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceScope()
+    {
+        int cur = -1;
+        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxGridY = 65535;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct espn_table {
+    const uint16_t *emb = nullptr;   // borrowed
+    int64_t *off_dev = nullptr;      // owned, [n_docs + 1]
+    unsigned *err_dev = nullptr;     // owned, one flag word
+    int64_t n_docs = 0;
+    int64_t total_rows = 0;
+    int32_t dim = 0;
+    int32_t residency = 0;
+    int32_t device = 0;
+};
+
+ESPN_API const char *espn_status_string(int status)
+{
+    switch (status) {
+        case ESPN_OK: return "ok";
+        case ESPN_ERR_ARG: return "bad argument";
+        case ESPN_ERR_SHAPE: return "inconsistent sizes";
+        case ESPN_ERR_OFFSETS: return "malformed offsets";
+        case ESPN_ERR_ID_RANGE: return "candidate id out of range";
+        case ESPN_ERR_NOMEM: return "out of memory";
+        case ESPN_ERR_HIP: return "HIP runtime error";
+        case ESPN_ERR_UNSUPPORTED: return "unsupported shape";
+        case ESPN_ERR_BUSY: return "staging slot busy";
+        default: return "unknown status";
+    }
+}
+
+ESPN_API const char *espn_last_error(void) { return g_err; }
+
+ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
+                             int32_t residency, int32_t device, espn_table **out)
+{
+    if (!out) return fail(ESPN_ERR_ARG, "out is NULL");
+    *out = nullptr;
+    if (!offsets_host) return fail(ESPN_ERR_ARG, "offsets_host is NULL");
+    if (n_docs < 0) return fail(ESPN_ERR_ARG, "n_docs = %lld is negative", (long long)n_docs);
+    if (dim <= 0 || dim % 8 != 0) return fail(ESPN_ERR_ARG, "dim = %d is not a positive multiple of 8", dim);
+    if (residency != ESPN_RESIDENT_HBM && residency != ESPN_RESIDENT_HOST_PINNED)
+        return fail(ESPN_ERR_ARG, "residency = %d is not a known value", residency);
+    if (offsets_host[0] != 0) return fail(ESPN_ERR_OFFSETS, "offsets[0] = %lld, expected 0", (long long)offsets_host[0]);
+    for (int64_t i = 0; i < n_docs; ++i)
+        if (offsets_host[i + 1] < offsets_host[i])
+            return fail(ESPN_ERR_OFFSETS, "offsets decrease at document %lld", (long long)i);
+    const int64_t total = offsets_host[n_docs];
+    if (total > 0 && !emb) return fail(ESPN_ERR_ARG, "emb is NULL");
+    if (!aligned16(emb)) return fail(ESPN_ERR_ARG, "emb is not 16-byte aligned");
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return fail(ESPN_ERR_ARG, "device %d of %d", device, ndev);
+
+    DeviceScope scope(device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", device);
+    espn_table *t = new (std::nothrow) espn_table;
+    if (!t) return fail(ESPN_ERR_NOMEM, "host allocation failed");
+    t->emb = static_cast<const uint16_t *>(emb);
+    t->n_docs = n_docs;
+    t->total_rows = total;
+    t->dim = dim;
+    t->residency = residency;
+    t->device = device;
+    const size_t off_bytes = sizeof(int64_t) * (size_t)(n_docs + 1);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&t->off_dev), off_bytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&t->err_dev), kAlign);
+    if (e == hipSuccess) e = hipMemcpy(t->off_dev, offsets_host, off_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(t->err_dev, 0, kAlign);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipFree(t->off_dev);
+        (void)hipFree(t->err_dev);
+        delete t;
+        return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "table set-up failed: %s",
+                    hipGetErrorString(e));
+    }
+    *out = t;
+    return ESPN_OK;
+}
+
+ESPN_API int espn_table_free(espn_table *table)
+{
+    if (!table) return ESPN_OK;
+    DeviceScope scope(table->device);
+    (void)hipDeviceSynchronize();
+    (void)hipFree(table->off_dev);
+    (void)hipFree(table->err_dev);
+    delete table;
+    return ESPN_OK;
+}
+
+ESPN_API int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_rows, int32_t *dim,
+                             int32_t *residency, int32_t *device)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (n_docs) *n_docs = table->n_docs;
+    if (total_rows) *total_rows = table->total_rows;
+    if (dim) *dim = table->dim;
+    if (residency) *residency = table->residency;
+    if (device) *device = table->device;
+    return ESPN_OK;
+}
+
+namespace {
+
+int check_batch(const espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (B < 0 || K < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d: negative size", B, K);
+    if (Q < 1) return fail(ESPN_ERR_ARG, "Q = %d: a query needs at least one row", Q);
+    if (B > kMaxGridY) return fail(ESPN_ERR_UNSUPPORTED, "B = %d exceeds %d queries per call", B, kMaxGridY);
+    if (B > 0 && K > 0 && (!q || !cand)) return fail(ESPN_ERR_ARG, "q or cand is NULL");
+    if (!aligned16(q)) return fail(ESPN_ERR_ARG, "q is not 16-byte aligned");
+    return ESPN_OK;
+}
+
+// Documents per wave in the matrix-core kernel: enough waves to fill 256 CUs several times over
+// on small batches, enough documents per wave to amortise the query-fragment load on large ones.
+int docs_per_wave(int64_t pairs)
+{
+    if (pairs >= (int64_t)1 << 20) return 32;
+    if (pairs >= (int64_t)1 << 17) return 16;
+    return 8;
+}
+
+template <int D>
+void launch_mfma(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
+                 hipStream_t st)
+{
+    using namespace espn;
+    const auto *qh = static_cast<const uint16_t *>(q);
+    const int dpw = docs_per_wave((int64_t)B * K);
+    const int waves = (K + dpw - 1) / dpw;
+    const dim3 grid((waves + 3) / 4, B), block(256);
+    if (dpw == 32)
+        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 32>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh, cand,
+                           B, Q, K, scores, t->err_dev);
+    else if (dpw == 16)
+        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 16>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh, cand,
+                           B, Q, K, scores, t->err_dev);
+    else
+        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 8>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh, cand,
+                           B, Q, K, scores, t->err_dev);
+}
+
+int enqueue_score(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
+                  hipStream_t st)
+{
+    using namespace espn;
+    if (t->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is not HBM-resident");
+    if (B == 0 || K == 0) return ESPN_OK;
+    if ((t->dim == 32 || t->dim == 128) && Q <= 32) {
+        if (t->dim == 32) launch_mfma<32>(t, q, cand, B, Q, K, scores, st);
+        else launch_mfma<128>(t, q, cand, B, Q, K, scores, st);
+    } else {
+        const size_t lds = (size_t)Q * t->dim * 2;
+        if (lds > 64 * 1024)
+            return fail(ESPN_ERR_UNSUPPORTED, "Q * dim * 2 = %zu bytes exceeds the 64 KiB the generic kernel holds", lds);
+        const dim3 grid((K + 3) / 4, B), block(256);
+        hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, t->emb, t->off_dev, t->n_docs, t->dim,
+                           static_cast<const uint16_t *>(q), cand, B, Q, K, scores, t->err_dev);
+    }
+    HIP_TRY(hipGetLastError());
+    return ESPN_OK;
+}
+
+int enqueue_topk(const float *scores, const int64_t *cand, int B, int K, int k, int64_t *out_ids, float *out_scores,
+                 hipStream_t st)
+{
+    using namespace espn;
+    if (B == 0 || k == 0) return ESPN_OK;
+    if (K <= 256 * 4)
+        hipLaunchKernelGGL((topk_rounds_kernel<4>), dim3(B), dim3(256), 0, st, scores, cand, K, k, out_ids, out_scores);
+    else
+        hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, K, k, out_ids, out_scores);
+    HIP_TRY(hipGetLastError());
+    return ESPN_OK;
+}
+
+}  // namespace
+
+ESPN_API int espn_score(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
+                        float *scores, void *stream)
+{
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if (B > 0 && K > 0 && !scores) return fail(ESPN_ERR_ARG, "scores is NULL");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    return enqueue_score(table, q, cand, B, Q, K, scores, static_cast<hipStream_t>(stream));
+}
+
+ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k, int64_t *out_ids,
+                       float *out_scores, void *stream)
+{
+    if (B < 0 || K < 0 || k < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d, k = %d: negative size", B, K, k);
+    if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
+    if (B > 0 && k > 0 && (!scores || !cand || !out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "NULL pointer");
+    return enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, static_cast<hipStream_t>(stream));
+}
+
+ESPN_API size_t espn_workspace_bytes(int32_t B, int32_t K)
+{
+    if (B <= 0 || K <= 0) return kAlign;
+    const size_t bytes = sizeof(float) * (size_t)B * (size_t)K;
+    return (bytes + kAlign - 1) / kAlign * kAlign;
+}
+
+ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
+                         int32_t k, int64_t *out_ids, float *out_scores, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if (k < 0) return fail(ESPN_ERR_ARG, "k = %d is negative", k);
+    if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
+    if (B > 0 && k > 0 && (!out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "output pointer is NULL");
+    if (B > 0 && K > 0) {
+        if (!workspace) return fail(ESPN_ERR_ARG, "workspace is NULL");
+        if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
+            return fail(ESPN_ERR_ARG, "workspace is not %zu-byte aligned", kAlign);
+        if (workspace_bytes < espn_workspace_bytes(B, K))
+            return fail(ESPN_ERR_SHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes,
+                        espn_workspace_bytes(B, K));
+    }
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *scores = static_cast<float *>(workspace);
+    if (int rc = enqueue_score(table, q, cand, B, Q, K, scores, st)) return rc;
+    return enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, st);
+}
+
+ESPN_API int espn_table_check(espn_table *table, void *stream)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned flags = 0;
+    HIP_TRY(hipMemcpyAsync(&flags, table->err_dev, sizeof(flags), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (flags) {
+        HIP_TRY(hipMemsetAsync(table->err_dev, 0, sizeof(unsigned), st));
+        HIP_TRY(hipStreamSynchronize(st));
+    }
+    if (flags & espn::ERR_ID_RANGE) return fail(ESPN_ERR_ID_RANGE, "a candidate id was outside [0, %lld)",
+                                                (long long)table->n_docs);
+    return ESPN_OK;
+}
