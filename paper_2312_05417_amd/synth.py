@@ -184,3 +184,21 @@ def candidates(w: Workload, seed: int = DEFAULT_SEED, batch: int = 0) -> np.ndar
         else:
             raise ValueError(w.cand_law)
     return out
+
+
+def subtable(emb: torch.Tensor, off: np.ndarray, cand: np.ndarray):
+    """The part of a table a candidate sample refers to, as a small table of its own:
+    (rows [T',dim] binary16 numpy on the host, offsets int64 [U+1], cand remapped into 0..U-1,
+    ids int64 [U] = the original id of each local document).  Local ids keep the order of the
+    original ids, so ranking ties resolve the same way.  `emb` may live on any device; only the
+    needed rows are copied."""
+    ids, local = np.unique(np.asarray(cand, dtype=np.int64), return_inverse=True)
+    counts = off[ids + 1] - off[ids]
+    loc_off = offsets_from_counts(counts)
+    total = int(loc_off[-1])
+    # row index list: for local doc u, rows off[ids[u]] + 0..counts[u]-1
+    start = np.repeat(off[ids] - loc_off[:-1], counts)
+    rows = start + np.arange(total, dtype=np.int64)
+    idx = torch.from_numpy(rows).to(emb.device)
+    sub = emb.index_select(0, idx).cpu().numpy() if total else np.zeros((0, emb.shape[1]), dtype=np.float16)
+    return sub, loc_off, local.reshape(np.asarray(cand).shape).astype(np.int64), ids
