@@ -185,19 +185,20 @@ void launch_mfma(const espn_table *t, const void *q, const int64_t *cand, int B,
                  hipStream_t st)
 {
     using namespace espn;
+    constexpr int P = (D == 32) ? 4 : 2;     // register pipeline depth in 16-row tiles
     const auto *qh = static_cast<const uint16_t *>(q);
     const int dpw = docs_per_wave((int64_t)B * K);
     const int waves = (K + dpw - 1) / dpw;
     const dim3 grid((waves + 3) / 4, B), block(256);
     if (dpw == 32)
-        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 32>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh, cand,
-                           B, Q, K, scores, t->err_dev);
+        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 32, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh,
+                           cand, B, Q, K, scores, t->err_dev);
     else if (dpw == 16)
-        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 16>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh, cand,
-                           B, Q, K, scores, t->err_dev);
+        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 16, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh,
+                           cand, B, Q, K, scores, t->err_dev);
     else
-        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 8>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh, cand,
-                           B, Q, K, scores, t->err_dev);
+        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 8, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh,
+                           cand, B, Q, K, scores, t->err_dev);
 }
 
 int enqueue_score(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
