@@ -171,34 +171,36 @@ int check_batch(const espn_table *table, const void *q, const int64_t *cand, int
     return ESPN_OK;
 }
 
-// Documents per wave in the matrix-core kernel: enough waves to fill 256 CUs several times over
-// on small batches, enough documents per wave to amortise the query-fragment load on large ones.
+// Documents per wave in the matrix-core kernel.  Small batches want many short waves (every wave is
+// resident at once and the kernel's tail is set by the longest wave); large batches want fewer
+// query-fragment loads.  Measured on MI355X: 4 is best at 64 K pairs, 8..32 are equal beyond 256 K.
 int docs_per_wave(int64_t pairs)
 {
     if (pairs >= (int64_t)1 << 20) return 32;
-    if (pairs >= (int64_t)1 << 17) return 16;
-    return 8;
+    if (pairs >= (int64_t)1 << 17) return 8;
+    return 4;
+}
+
+template <int D, int DOCS, int P>
+void launch_mfma_as(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
+                    hipStream_t st)
+{
+    const int waves = (K + DOCS - 1) / DOCS;
+    const dim3 grid((waves + 3) / 4, B), block(256);
+    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs,
+                       static_cast<const uint16_t *>(q), cand, B, Q, K, scores, t->err_dev);
 }
 
 template <int D>
 void launch_mfma(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
                  hipStream_t st)
 {
-    using namespace espn;
-    constexpr int P = (D == 32) ? 4 : 2;     // register pipeline depth in 16-row tiles
-    const auto *qh = static_cast<const uint16_t *>(q);
-    const int dpw = docs_per_wave((int64_t)B * K);
-    const int waves = (K + dpw - 1) / dpw;
-    const dim3 grid((waves + 3) / 4, B), block(256);
-    if (dpw == 32)
-        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 32, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh,
-                           cand, B, Q, K, scores, t->err_dev);
-    else if (dpw == 16)
-        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 16, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh,
-                           cand, B, Q, K, scores, t->err_dev);
-    else
-        hipLaunchKernelGGL((maxsim_mfma_kernel<D, 8, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs, qh,
-                           cand, B, Q, K, scores, t->err_dev);
+    constexpr int P = (D == 32) ? 4 : 3;     // register pipeline depth in 16-row tiles
+    switch (docs_per_wave((int64_t)B * K)) {
+        case 32: launch_mfma_as<D, 32, P>(t, q, cand, B, Q, K, scores, st); break;
+        case 8: launch_mfma_as<D, 8, P>(t, q, cand, B, Q, K, scores, st); break;
+        default: launch_mfma_as<D, 4, P>(t, q, cand, B, Q, K, scores, st); break;
+    }
 }
 
 int enqueue_score(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
@@ -228,7 +230,11 @@ int enqueue_topk(const float *scores, const int64_t *cand, int B, int K, int k, 
 {
     using namespace espn;
     if (B == 0 || k == 0) return ESPN_OK;
-    if (K <= 256 * 4)
+    if (k <= 64 && K <= 64 * 16)
+        hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, K, k, out_ids, out_scores);
+    else if (k <= 64 && K <= 64 * 32)
+        hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, K, k, out_ids, out_scores);
+    else if (K <= 256 * 4)
         hipLaunchKernelGGL((topk_rounds_kernel<4>), dim3(B), dim3(256), 0, st, scores, cand, K, k, out_ids, out_scores);
     else
         hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, K, k, out_ids, out_scores);

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace espn {
 
 struct Ranked {
@@ -106,6 +108,159 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
                     out_ids[(size_t)b * k + rest] = -1;
                     out_scores[(size_t)b * k + rest] = __builtin_nanf("");
                 }
+            break;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fast path: one wave per query, K <= 64*PER, k <= 64.
+//
+// Scores are mapped to unsigned keys that order like the floats (NaN and unused slots -> 0, never
+// picked).  Each lane holds PER keys in registers.  The k-th largest of the 64 per-lane maxima is a
+// lower bound theta for the k-th best key overall (at least k elements reach it), so every entry
+// that can appear in the ranked top-k, including all ties with the k-th, has key >= theta.  Those
+// few entries are compacted (ballot + mbcnt, in slot order), their ids are fetched, and each one
+// counts how many others rank before it; entries whose count is below k write themselves to that
+// position.  Only if more than 64 entries survive (massive exact ties) the survivors are ranked by
+// the k-round selection, from LDS.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned order_key(float s)
+{
+    if (!(s == s)) return 0u;
+    const unsigned u = __builtin_bit_cast(unsigned, s + 0.0f);   // -0 and +0 are the same score
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float key_to_score(unsigned key)
+{
+    const unsigned u = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
+    return __builtin_bit_cast(float, u);
+}
+
+// max over the wave, returned to every lane as a uniform value
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+    auto dpp = [](unsigned x, auto ctrl) {
+        return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, decltype(ctrl)::value, 0xF, 0xF, true);
+    };
+    v = max(v, dpp(v, std::integral_constant<int, 0xB1>{}));    // quad_perm [1,0,3,2]
+    v = max(v, dpp(v, std::integral_constant<int, 0x4E>{}));    // quad_perm [2,3,0,1]
+    v = max(v, dpp(v, std::integral_constant<int, 0x141>{}));   // row_half_mirror
+    v = max(v, dpp(v, std::integral_constant<int, 0x140>{}));   // row_mirror
+    const unsigned a = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
+    const unsigned b = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned c = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
+    const unsigned d = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    return max(max(a, b), max(c, d));
+}
+
+template <int PER>
+__global__ __launch_bounds__(64) void topk_wave_kernel(
+    const float *__restrict__ scores, const int64_t *__restrict__ cand, int K, int k,
+    int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
+{
+    __shared__ unsigned s_key[64 * PER];
+    __shared__ int s_slot[64 * PER];
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const float *sc = scores + (size_t)b * K;
+    const int64_t *ids = cand + (size_t)b * K;
+
+    unsigned key[PER];
+    unsigned local_max = 0;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+        const int slot = x * 64 + lane;
+        key[x] = slot < K ? order_key(sc[slot]) : 0u;
+        local_max = max(local_max, key[x]);
+    }
+
+    // theta = k-th largest of the per-lane maxima (1 if fewer than k lanes hold anything)
+    unsigned theta = 1u;
+    {
+        unsigned cur = local_max;
+        for (int round = 0; round < k; ++round) {
+            const unsigned m = wave_max_u32(cur);
+            if (m == 0u) { theta = 1u; break; }
+            theta = m;
+            const uint64_t holders = __ballot(cur == m);
+            if (lane == __builtin_ctzll(holders)) cur = 0u;
+        }
+    }
+
+    // compact the survivors in slot order
+    int total = 0;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+        const bool keep = key[x] >= theta;
+        const uint64_t mask = __ballot(keep);
+        if (keep) {
+            const int pos = total + __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                              __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+            s_key[pos] = key[x];
+            s_slot[pos] = x * 64 + lane;
+        }
+        total += __builtin_popcountll(mask);
+    }
+    __syncthreads();
+
+    if (total <= 64) {
+        // one survivor per lane: rank = number of survivors that come before it
+        const bool have = lane < total;
+        const unsigned my_key = have ? s_key[lane] : 0u;
+        const int my_slot = have ? s_slot[lane] : 0;
+        const int64_t my_id = have ? ids[my_slot] : 0;
+        int rank = 0;
+        for (int i = 0; i < total; ++i) {
+            const unsigned ki = (unsigned)__builtin_amdgcn_readlane((int)my_key, i);
+            const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(uint32_t)my_id, i);
+            const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)my_id >> 32), i);
+            const int64_t idi = (int64_t)(((uint64_t)hi << 32) | lo);
+            const bool before = ki > my_key || (ki == my_key && (idi < my_id || (idi == my_id && i < lane)));
+            rank += before ? 1 : 0;
+        }
+        if (have && rank < k) {
+            out_ids[(size_t)b * k + rank] = my_id;
+            out_scores[(size_t)b * k + rank] = key_to_score(my_key);
+        }
+        // fewer rankable entries than k (NaN scores): mark the rest
+        for (int rest = total + lane; rest < k; rest += 64) {
+            out_ids[(size_t)b * k + rest] = -1;
+            out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+        }
+        return;
+    }
+
+    // many exact ties: k rounds of selection over the survivors held in LDS
+    Ranked prev;
+    prev.slot = -1;
+    for (int round = 0; round < k; ++round) {
+        Ranked best;
+        best.slot = -1; best.score = 0.f; best.id = 0;
+        for (int i = lane; i < total; i += 64) {
+            Ranked e;
+            e.score = key_to_score(s_key[i]);
+            e.slot = s_slot[i];
+            e.id = ids[e.slot];
+            const bool after_prev = (round == 0) || ranks_before(prev, e);
+            if (after_prev && ranks_before(e, best)) best = e;
+        }
+#pragma unroll
+        for (int mask = 32; mask >= 1; mask >>= 1) {
+            const Ranked o = shfl_xor_ranked(best, mask);
+            if (ranks_before(o, best)) best = o;
+        }
+        if (lane == 0) {
+            out_ids[(size_t)b * k + round] = best.slot >= 0 ? best.id : (int64_t)-1;
+            out_scores[(size_t)b * k + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+        }
+        prev = best;
+        if (best.slot < 0) {
+            for (int rest = round + 1 + lane; rest < k; rest += 64) {
+                out_ids[(size_t)b * k + rest] = -1;
+                out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+            }
             break;
         }
     }
