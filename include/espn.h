@@ -94,7 +94,7 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
  *           Q * dim * 2 bytes <= 64 KiB.
  * An empty document scores -infinity (empty max).  An id outside [0, n_docs) scores
  * -infinity and raises the table's error flag (see espn_table_check); nothing is read for it.
- * B = 0 or K = 0 is a no-op.  Table must be HBM-resident.
+ * B = 0 or K = 0 is a no-op.  The table must be HBM-resident (ESPN_ERR_UNSUPPORTED otherwise).
  * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
  */
 int espn_score(espn_table *table, const void *q, const int64_t *cand,
@@ -133,6 +133,57 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
  * returns ESPN_ERR_ID_RANGE if any candidate id was out of range, else ESPN_OK; clears the flag.
  */
 int espn_table_check(espn_table *table, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Host-resident tables.  The table stays in pinned host memory (the one-GPU analogue of keeping the
+ * re-ranking embeddings in a slower tier, Sec. 4); the documents a batch needs are copied to an HBM
+ * staging slot ahead of scoring, on a side stream, while the previous batch is scored from the
+ * other slot (Sec. 4.2: fetching overlapped with computation; Sec. 4.1: fetched straight into GPU
+ * memory).  Typical loop, batch n:
+ *     espn_prefetch(t, cand[n+1], B, K, (n+1) % 2, side);            // returns at once
+ *     espn_rerank_staged(t, n % 2, q[n], cand[n], ..., main);        // returns at once
+ * Ordering between the two streams is handled inside with events: a staged re-rank waits for the
+ * prefetch of its slot, and a prefetch waits for the last re-rank that read its slot.  No call here
+ * blocks the host except espn_staging_create and espn_staging_counters.
+ * ------------------------------------------------------------------------------------------- */
+
+/*
+ * Allocate the two staging slots of a host-resident table (replacing earlier ones).
+ *   capacity_rows  embedding rows one slot can hold (each slot takes capacity_rows * dim * 2 bytes of
+ *                  HBM, plus 8 bytes per document of the table for its row map).
+ *   capacity_docs  distinct documents one slot can hold.
+ * A prefetch that needs more raises a flag that espn_table_check reports as ESPN_ERR_NOMEM.
+ * Synchronous.  Errors: ARG, UNSUPPORTED (table is HBM-resident), NOMEM, HIP.
+ */
+int espn_staging_create(espn_table *table, int64_t capacity_rows, int64_t capacity_docs);
+
+/*
+ * Copy every distinct document named in cand to staging slot `slot` (0 or 1): a document listed by
+ * several queries crosses PCIe once.  Runs entirely on the GPU on `side_stream` (mark distinct ids,
+ * reserve rows, copy rows out of pinned host memory).
+ *   cand  [B, K] int64, DEVICE; must stay unchanged until the prefetch has run.
+ * Errors: ARG, HIP.  Ids out of range are flagged as in espn_score.
+ */
+int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, int32_t K, int32_t slot, void *side_stream);
+
+/*
+ * espn_rerank for a host-resident table: scores cand against the rows held by `slot` (which must have
+ * been prefetched with the same candidates), then ranks.  Arguments as espn_rerank; afterwards the
+ * workspace holds all B*K scores as binary32 [B, K].  A candidate the slot does not hold scores
+ * -infinity and raises a flag (espn_table_check: ESPN_ERR_SHAPE).
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
+ */
+int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, const int64_t *cand,
+                       int32_t B, int32_t Q, int32_t K, int32_t k,
+                       int64_t *out_ids, float *out_scores,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Waits for `stream`, then reports what the last prefetch into `slot` did: out4[0] distinct documents,
+ * out4[1] rows reserved, out4[2] bytes that crossed PCIe (rows * dim * 2), out4[3] slot capacity in rows.
+ * out4 is a HOST pointer to four uint64.
+ */
+int espn_staging_counters(espn_table *table, int32_t slot, void *stream, uint64_t *out4);
 
 #ifdef __cplusplus
 }

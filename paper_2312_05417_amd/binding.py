@@ -34,6 +34,11 @@ SIGNATURES = {
     "espn_workspace_bytes": (_c_sz, [_c_i32, _c_i32]),
     "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "espn_table_check": (ctypes.c_int, [_c_p, _c_p]),
+    "espn_staging_create": (ctypes.c_int, [_c_p, _c_i64, _c_i64]),
+    "espn_prefetch": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p]),
+    "espn_rerank_staged": (ctypes.c_int, [_c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
+                                          _c_p, _c_sz, _c_p]),
+    "espn_staging_counters": (ctypes.c_int, [_c_p, _c_i32, _c_p, ctypes.POINTER(ctypes.c_uint64)]),
 }
 
 _lib = None
@@ -203,3 +208,40 @@ def espn_rerank(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_i
 def espn_table_check(table: Table, stream=None) -> None:
     """Waits for the stream; raises EspnError(ESPN_ERR_ID_RANGE) if a kernel met an id out of range."""
     _check(lib().espn_table_check(table.handle, _stream_ptr(stream)))
+
+
+def espn_staging_create(table: Table, capacity_rows: int, capacity_docs: int) -> None:
+    _check(lib().espn_staging_create(table.handle, capacity_rows, capacity_docs))
+
+
+def espn_prefetch(table: Table, cand: torch.Tensor, slot: int, side_stream=None) -> None:
+    if cand.dim() != 2:
+        raise ValueError("cand must be [B,K]")
+    _check(lib().espn_prefetch(table.handle, _dev(cand, torch.int64, "cand"), cand.shape[0], cand.shape[1], slot,
+                               _stream_ptr(side_stream)))
+
+
+def espn_rerank_staged(table: Table, slot: int, q: torch.Tensor, cand: torch.Tensor, k: int,
+                       out_ids: torch.Tensor | None = None, out_scores: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None, stream=None):
+    """Returns (out_ids, out_scores, workspace); the workspace starts with all scores, fp32 [B,K]."""
+    B, Q, K = _batch_shape(q, cand)
+    if q.shape[2] != table.dim:
+        raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
+    if out_ids is None:
+        out_ids = torch.empty((B, max(k, 0)), dtype=torch.int64, device=q.device)
+    if out_scores is None:
+        out_scores = torch.empty((B, max(k, 0)), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(espn_workspace_bytes(B, K), dtype=torch.uint8, device=q.device)
+    _check(lib().espn_rerank_staged(table.handle, slot, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
+                                    B, Q, K, k, _dev(out_ids, torch.int64, "out_ids"),
+                                    _dev(out_scores, torch.float32, "out_scores"),
+                                    _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_scores, workspace
+
+
+def espn_staging_counters(table: Table, slot: int, stream=None) -> dict:
+    out = (ctypes.c_uint64 * 4)()
+    _check(lib().espn_staging_counters(table.handle, slot, _stream_ptr(stream), out))
+    return {"distinct_docs": int(out[0]), "rows": int(out[1]), "pcie_bytes": int(out[2]), "capacity_rows": int(out[3])}

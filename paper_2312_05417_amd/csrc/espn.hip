@@ -3,6 +3,7 @@
 // kernels of maxsim_kernels.h / topk_kernels.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -10,6 +11,7 @@
 
 #include "../../include/espn.h"
 #include "maxsim_kernels.h"
+#include "staging_kernels.h"
 #include "topk_kernels.h"
 
 #define ESPN_API extern "C" __attribute__((visibility("default")))
@@ -53,13 +55,25 @@ struct DeviceScope {
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxGridY = 65535;
+constexpr unsigned kGatherBlocks = 256;   // workgroups of the host-to-HBM copy kernel
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
 
+// One HBM staging slot of a host-resident table (all device memory, owned by the table).
+struct StagingSlot {
+    uint16_t *rows = nullptr;              // [capacity_rows, dim]
+    int64_t *row_map = nullptr;            // [n_docs] first staged row of a document (valid if its bit is set)
+    unsigned *bits = nullptr;              // [ceil(n_docs / 32)] documents held by the slot
+    int64_t *uniq = nullptr;               // [capacity_docs] distinct documents of the batch
+    unsigned long long *counters = nullptr;  // [4]: distinct documents, rows reserved
+    hipEvent_t ready = nullptr;            // recorded when a prefetch into the slot has been enqueued
+    hipEvent_t consumed = nullptr;         // recorded when a re-rank reading the slot has been enqueued
+};
+
 struct espn_table {
-    const uint16_t *emb = nullptr;   // borrowed
+    const uint16_t *emb = nullptr;   // borrowed; the device-visible address if the table is in host memory
     int64_t *off_dev = nullptr;      // owned, [n_docs + 1]
     unsigned *err_dev = nullptr;     // owned, one flag word
     int64_t n_docs = 0;
@@ -67,6 +81,10 @@ struct espn_table {
     int32_t dim = 0;
     int32_t residency = 0;
     int32_t device = 0;
+    StagingSlot slot[2];
+    int64_t capacity_rows = 0;
+    int64_t capacity_docs = 0;
+    bool has_staging = false;
 };
 
 ESPN_API const char *espn_status_string(int status)
@@ -113,6 +131,17 @@ ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64
     espn_table *t = new (std::nothrow) espn_table;
     if (!t) return fail(ESPN_ERR_NOMEM, "host allocation failed");
     t->emb = static_cast<const uint16_t *>(emb);
+    if (residency == ESPN_RESIDENT_HOST_PINNED && total > 0) {
+        void *dev_view = nullptr;
+        hipError_t he = hipHostGetDevicePointer(&dev_view, const_cast<void *>(emb), 0);
+        if (he != hipSuccess || !dev_view) {
+            (void)hipGetLastError();
+            delete t;
+            return fail(ESPN_ERR_ARG, "emb is not pinned host memory the device can address (%s)",
+                        hipGetErrorString(he));
+        }
+        t->emb = static_cast<const uint16_t *>(dev_view);
+    }
     t->n_docs = n_docs;
     t->total_rows = total;
     t->dim = dim;
@@ -135,11 +164,29 @@ ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64
     return ESPN_OK;
 }
 
+namespace {
+void free_staging(espn_table *t)
+{
+    for (StagingSlot &s : t->slot) {
+        (void)hipFree(s.rows);
+        (void)hipFree(s.row_map);
+        (void)hipFree(s.bits);
+        (void)hipFree(s.uniq);
+        (void)hipFree(s.counters);
+        if (s.ready) (void)hipEventDestroy(s.ready);
+        if (s.consumed) (void)hipEventDestroy(s.consumed);
+        s = StagingSlot();
+    }
+    t->has_staging = false;
+}
+}  // namespace
+
 ESPN_API int espn_table_free(espn_table *table)
 {
     if (!table) return ESPN_OK;
     DeviceScope scope(table->device);
     (void)hipDeviceSynchronize();
+    free_staging(table);
     (void)hipFree(table->off_dev);
     (void)hipFree(table->err_dev);
     delete table;
@@ -182,47 +229,51 @@ int docs_per_wave(int64_t pairs)
 }
 
 template <int D, int DOCS, int P>
-void launch_mfma_as(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
-                    hipStream_t st)
+void launch_mfma_as(const espn::DocSource &src, unsigned *err, const void *q, const int64_t *cand, int B, int Q,
+                    int K, float *scores, hipStream_t st)
 {
     const int waves = (K + DOCS - 1) / DOCS;
     const dim3 grid((waves + 3) / 4, B), block(256);
-    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P>), grid, block, 0, st, t->emb, t->off_dev, t->n_docs,
-                       static_cast<const uint16_t *>(q), cand, B, Q, K, scores, t->err_dev);
+    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P>), grid, block, 0, st, src,
+                       static_cast<const uint16_t *>(q), cand, B, Q, K, scores, err);
 }
 
 template <int D>
-void launch_mfma(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
-                 hipStream_t st)
+void launch_mfma(const espn::DocSource &src, unsigned *err, const void *q, const int64_t *cand, int B, int Q, int K,
+                 float *scores, hipStream_t st)
 {
     constexpr int P = (D == 32) ? 4 : 3;     // register pipeline depth in 16-row tiles
     switch (docs_per_wave((int64_t)B * K)) {
-        case 32: launch_mfma_as<D, 32, P>(t, q, cand, B, Q, K, scores, st); break;
-        case 8: launch_mfma_as<D, 8, P>(t, q, cand, B, Q, K, scores, st); break;
-        default: launch_mfma_as<D, 4, P>(t, q, cand, B, Q, K, scores, st); break;
+        case 32: launch_mfma_as<D, 32, P>(src, err, q, cand, B, Q, K, scores, st); break;
+        case 8: launch_mfma_as<D, 8, P>(src, err, q, cand, B, Q, K, scores, st); break;
+        default: launch_mfma_as<D, 4, P>(src, err, q, cand, B, Q, K, scores, st); break;
     }
 }
 
-int enqueue_score(const espn_table *t, const void *q, const int64_t *cand, int B, int Q, int K, float *scores,
-                  hipStream_t st)
+// Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot).
+int enqueue_score(const espn_table *t, const espn::DocSource &src, const void *q, const int64_t *cand, int B, int Q,
+                  int K, float *scores, hipStream_t st)
 {
     using namespace espn;
-    if (t->residency != ESPN_RESIDENT_HBM)
-        return fail(ESPN_ERR_UNSUPPORTED, "table is not HBM-resident");
     if (B == 0 || K == 0) return ESPN_OK;
     if ((t->dim == 32 || t->dim == 128) && Q <= 32) {
-        if (t->dim == 32) launch_mfma<32>(t, q, cand, B, Q, K, scores, st);
-        else launch_mfma<128>(t, q, cand, B, Q, K, scores, st);
+        if (t->dim == 32) launch_mfma<32>(src, t->err_dev, q, cand, B, Q, K, scores, st);
+        else launch_mfma<128>(src, t->err_dev, q, cand, B, Q, K, scores, st);
     } else {
         const size_t lds = (size_t)Q * t->dim * 2;
         if (lds > 64 * 1024)
             return fail(ESPN_ERR_UNSUPPORTED, "Q * dim * 2 = %zu bytes exceeds the 64 KiB the generic kernel holds", lds);
         const dim3 grid((K + 3) / 4, B), block(256);
-        hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, t->emb, t->off_dev, t->n_docs, t->dim,
+        hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim,
                            static_cast<const uint16_t *>(q), cand, B, Q, K, scores, t->err_dev);
     }
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
+}
+
+espn::DocSource hbm_source(const espn_table *t)
+{
+    return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs};
 }
 
 int enqueue_topk(const float *scores, const int64_t *cand, int B, int K, int k, int64_t *out_ids, float *out_scores,
@@ -251,7 +302,9 @@ ESPN_API int espn_score(espn_table *table, const void *q, const int64_t *cand, i
     if (B > 0 && K > 0 && !scores) return fail(ESPN_ERR_ARG, "scores is NULL");
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
-    return enqueue_score(table, q, cand, B, Q, K, scores, static_cast<hipStream_t>(stream));
+    if (table->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
+    return enqueue_score(table, hbm_source(table), q, cand, B, Q, K, scores, static_cast<hipStream_t>(stream));
 }
 
 ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k, int64_t *out_ids,
@@ -270,11 +323,10 @@ ESPN_API size_t espn_workspace_bytes(int32_t B, int32_t K)
     return (bytes + kAlign - 1) / kAlign * kAlign;
 }
 
-ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
-                         int32_t k, int64_t *out_ids, float *out_scores, void *workspace, size_t workspace_bytes,
-                         void *stream)
+namespace {
+int check_rerank_outputs(int32_t B, int32_t K, int32_t k, const int64_t *out_ids, const float *out_scores,
+                         const void *workspace, size_t workspace_bytes)
 {
-    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
     if (k < 0) return fail(ESPN_ERR_ARG, "k = %d is negative", k);
     if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
     if (B > 0 && k > 0 && (!out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "output pointer is NULL");
@@ -286,11 +338,23 @@ ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, 
             return fail(ESPN_ERR_SHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes,
                         espn_workspace_bytes(B, K));
     }
+    return ESPN_OK;
+}
+}  // namespace
+
+ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
+                         int32_t k, int64_t *out_ids, float *out_scores, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if (int rc = check_rerank_outputs(B, K, k, out_ids, out_scores, workspace, workspace_bytes)) return rc;
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    if (table->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *scores = static_cast<float *>(workspace);
-    if (int rc = enqueue_score(table, q, cand, B, Q, K, scores, st)) return rc;
+    if (int rc = enqueue_score(table, hbm_source(table), q, cand, B, Q, K, scores, st)) return rc;
     return enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, st);
 }
 
@@ -309,5 +373,123 @@ ESPN_API int espn_table_check(espn_table *table, void *stream)
     }
     if (flags & espn::ERR_ID_RANGE) return fail(ESPN_ERR_ID_RANGE, "a candidate id was outside [0, %lld)",
                                                 (long long)table->n_docs);
+    if (flags & espn::ERR_STAGING_FULL)
+        return fail(ESPN_ERR_NOMEM, "a prefetch needed more than the %lld rows / %lld documents a staging slot holds",
+                    (long long)table->capacity_rows, (long long)table->capacity_docs);
+    if (flags & espn::ERR_NOT_STAGED)
+        return fail(ESPN_ERR_SHAPE, "a staged re-rank named a document its slot does not hold "
+                                    "(candidates differ from the prefetched ones, or the slot overflowed)");
+    return ESPN_OK;
+}
+
+ESPN_API int espn_staging_create(espn_table *table, int64_t capacity_rows, int64_t capacity_docs)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (table->residency != ESPN_RESIDENT_HOST_PINNED)
+        return fail(ESPN_ERR_UNSUPPORTED, "staging is for host-resident tables");
+    if (capacity_rows < 1 || capacity_docs < 1) return fail(ESPN_ERR_ARG, "capacities must be positive");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    (void)hipDeviceSynchronize();
+    free_staging(table);
+    const size_t n_words = (size_t)(table->n_docs + 31) / 32 + 1;
+    hipError_t e = hipSuccess;
+    for (StagingSlot &s : table->slot) {
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.rows), (size_t)capacity_rows * table->dim * 2);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.row_map), sizeof(int64_t) * (size_t)(table->n_docs + 1));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.bits), sizeof(unsigned) * n_words);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.uniq), sizeof(int64_t) * (size_t)capacity_docs);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.counters), kAlign);
+        if (e == hipSuccess) e = hipMemset(s.bits, 0, sizeof(unsigned) * n_words);
+        if (e == hipSuccess) e = hipMemset(s.counters, 0, kAlign);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&s.ready, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&s.consumed, hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        free_staging(table);
+        (void)hipGetLastError();
+        return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "staging set-up failed: %s",
+                    hipGetErrorString(e));
+    }
+    table->capacity_rows = capacity_rows;
+    table->capacity_docs = capacity_docs;
+    table->has_staging = true;
+    return ESPN_OK;
+}
+
+namespace {
+int check_slot(const espn_table *table, int32_t slot)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (!table->has_staging) return fail(ESPN_ERR_ARG, "espn_staging_create has not been called for this table");
+    if (slot < 0 || slot > 1) return fail(ESPN_ERR_ARG, "slot = %d, expected 0 or 1", slot);
+    return ESPN_OK;
+}
+}  // namespace
+
+ESPN_API int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, int32_t K, int32_t slot,
+                           void *side_stream)
+{
+    if (int rc = check_slot(table, slot)) return rc;
+    if (B < 0 || K < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d: negative size", B, K);
+    if (B > 0 && K > 0 && !cand) return fail(ESPN_ERR_ARG, "cand is NULL");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(side_stream);
+    StagingSlot &s = table->slot[slot];
+    // the slot may still be read by the re-rank that used it last
+    HIP_TRY(hipStreamWaitEvent(st, s.consumed, 0));
+    const int64_t n_words = (table->n_docs + 31) / 32 + 1;
+    const int64_t n_pairs = (int64_t)B * K;
+    hipLaunchKernelGGL(espn::staging_clear_kernel, dim3((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024)),
+                       dim3(256), 0, st, s.bits, n_words, s.counters);
+    if (n_pairs > 0) {
+        hipLaunchKernelGGL(espn::staging_mark_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, cand,
+                           n_pairs, table->off_dev, table->n_docs, s.bits, s.row_map, s.uniq, s.counters,
+                           table->capacity_rows, table->capacity_docs, table->err_dev);
+        // a modest grid: the copy is bound by PCIe, not by compute units, and shares the GPU with scoring
+        hipLaunchKernelGGL(espn::staging_gather_kernel, dim3(kGatherBlocks), dim3(256), 0, st, table->emb,
+                           table->off_dev, s.uniq, s.row_map, s.counters, table->capacity_docs, s.rows, table->dim);
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(s.ready, st));
+    return ESPN_OK;
+}
+
+ESPN_API int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, const int64_t *cand, int32_t B,
+                                int32_t Q, int32_t K, int32_t k, int64_t *out_ids, float *out_scores,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_slot(table, slot)) return rc;
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if (int rc = check_rerank_outputs(B, K, k, out_ids, out_scores, workspace, workspace_bytes)) return rc;
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    StagingSlot &s = table->slot[slot];
+    HIP_TRY(hipStreamWaitEvent(st, s.ready, 0));
+    const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs};
+    float *scores = static_cast<float *>(workspace);
+    if (int rc = enqueue_score(table, src, q, cand, B, Q, K, scores, st)) return rc;
+    if (int rc = enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, st)) return rc;
+    HIP_TRY(hipEventRecord(s.consumed, st));
+    return ESPN_OK;
+}
+
+ESPN_API int espn_staging_counters(espn_table *table, int32_t slot, void *stream, uint64_t *out4)
+{
+    if (int rc = check_slot(table, slot)) return rc;
+    if (!out4) return fail(ESPN_ERR_ARG, "out4 is NULL");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned long long c[4] = {0, 0, 0, 0};
+    HIP_TRY(hipMemcpyAsync(c, table->slot[slot].counters, sizeof(c), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    out4[0] = c[0];
+    out4[1] = c[1];
+    out4[2] = c[1] * (uint64_t)table->dim * 2u;
+    out4[3] = (uint64_t)table->capacity_rows;
     return ESPN_OK;
 }

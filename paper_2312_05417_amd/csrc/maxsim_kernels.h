@@ -17,7 +17,46 @@ namespace espn {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr unsigned ERR_ID_RANGE = 1u;
+constexpr unsigned ERR_ID_RANGE = 1u;        // a candidate id outside [0, n_docs)
+constexpr unsigned ERR_STAGING_FULL = 2u;    // a prefetch needed more staging rows than the slot holds
+constexpr unsigned ERR_NOT_STAGED = 4u;      // a staged re-rank met a document its slot does not hold
+
+// Where a document's rows are.  Table in HBM: rows off[id] .. off[id+1]-1 of `emb`.  Staged (table in
+// host memory, a prefetch copied this batch's documents into an HBM slot): `emb` is the slot, the
+// document's first row there is row_map[id], valid only if bit id of staged_bits is set.
+struct DocSource {
+    const uint16_t *emb;
+    const int64_t *off;
+    const int64_t *row_map;        // nullptr: table in HBM
+    const unsigned *staged_bits;
+    int64_t n_docs;
+};
+
+// (first row, row count) of document `id`; count 0 and an error flag if it cannot be read.
+__device__ __forceinline__ void locate_document(const DocSource &src, int64_t id, unsigned *err,
+                                                int64_t &row0, int &ntok)
+{
+    row0 = 0;
+    ntok = 0;
+    if (id < 0 || id >= src.n_docs) {
+        atomicOr(err, ERR_ID_RANGE);
+        return;
+    }
+    const int64_t first = src.off[id];
+    const int n = (int)(src.off[id + 1] - first);
+    if (src.row_map == nullptr) {
+        row0 = first;
+        ntok = n;
+        return;
+    }
+    const int64_t staged = src.row_map[id];
+    if (((src.staged_bits[id >> 5] >> (id & 31)) & 1u) == 0u || staged < 0) {
+        atomicOr(err, ERR_NOT_STAGED);
+        return;
+    }
+    row0 = staged;
+    ntok = n;
+}
 
 __device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
 
@@ -131,10 +170,10 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D> &buf, const uint16_t 
 
 template <int D, int DOCS, int P>
 __global__ __launch_bounds__(256) void maxsim_mfma_kernel(
-    const uint16_t *__restrict__ emb, const int64_t *__restrict__ off, int64_t n_docs,
-    const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
+    const DocSource src, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
     int B, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
 {
+    const uint16_t *__restrict__ emb = src.emb;
     static_assert((D == 32 || D == 128) && DOCS >= 1 && DOCS <= 64 && P >= 1, "unsupported shape");
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     const int lane = threadIdx.x & 63;
@@ -148,15 +187,7 @@ __global__ __launch_bounds__(256) void maxsim_mfma_kernel(
     // per-lane document descriptors: lane i describes candidate j0 + i
     int64_t row0 = 0;
     int ntok = 0;
-    if (lane < ndoc) {
-        const int64_t id = cand[(size_t)b * K + j0 + lane];
-        if (id >= 0 && id < n_docs) {
-            row0 = off[id];
-            ntok = (int)(off[id + 1] - row0);
-        } else {
-            atomicOr(err, ERR_ID_RANGE);
-        }
-    }
+    if (lane < ndoc) locate_document(src, cand[(size_t)b * K + j0 + lane], err, row0, ntok);
 
     // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
     half8 qf[2][KS];
@@ -251,8 +282,7 @@ __device__ __forceinline__ void unpack8(const uint4 &u, float (&f)[8])
 }
 
 __global__ __launch_bounds__(256) void maxsim_generic_kernel(
-    const uint16_t *__restrict__ emb, const int64_t *__restrict__ off, int64_t n_docs, int D,
-    const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
+    const DocSource src, int D, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
     int B, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
 {
     extern __shared__ uint4 q_lds[];         // [Q][D/8] chunks of 8 binary16
@@ -266,17 +296,17 @@ __global__ __launch_bounds__(256) void maxsim_generic_kernel(
 
     const int j = blockIdx.x * 4 + wave;
     if (j >= K) return;
-    const int64_t id = cand[(size_t)b * K + j];
-    if (id < 0 || id >= n_docs) {
-        if (lane == 0) {
-            atomicOr(err, ERR_ID_RANGE);
-            scores[(size_t)b * K + j] = neg_inf();
-        }
-        return;
+    int64_t s0;
+    int t;
+    {
+        // lane 0 looks the document up (and raises the flag once), the wave shares the result
+        int64_t s0_lane = 0;
+        int t_lane = 0;
+        if (lane == 0) locate_document(src, cand[(size_t)b * K + j], err, s0_lane, t_lane);
+        s0 = readlane64(s0_lane, 0);
+        t = __builtin_amdgcn_readlane(t_lane, 0);
     }
-    const int64_t s0 = off[id];
-    const int t = (int)(off[id + 1] - s0);
-    const uint4 *rows = reinterpret_cast<const uint4 *>(emb + (size_t)s0 * D);
+    const uint4 *rows = reinterpret_cast<const uint4 *>(src.emb + (size_t)s0 * D);
 
     float total = 0.f;
     for (int i0 = 0; i0 < Q; i0 += 16) {

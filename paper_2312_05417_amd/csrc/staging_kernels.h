@@ -1,0 +1,117 @@
+// Prefetch of a batch's candidate documents from a host-resident table into an HBM staging slot:
+// the one-GPU analogue of fetching the re-ranking embeddings from a slower tier into GPU memory
+// ahead of scoring (Sec. 4.1, Sec. 4.2: fetch overlapped with other work, so that only what is
+// left over shows on the critical path).  Everything runs on the GPU, on a side stream:
+//
+//   clear   zero the slot's document bitmap and its counters
+//   mark    one thread per (query, candidate): set the document's bit; the thread that sets it
+//           first reserves the document's rows in the slot (wave-aggregated atomic add) and appends
+//           the id to the slot's list of distinct documents.  A document listed by many queries
+//           is therefore copied once.
+//   gather  one wave per distinct document: copy its rows from pinned host memory (read across
+//           PCIe by the kernel itself, 16 bytes per lane, lane-linear) into the slot.
+//
+// The order of documents inside a slot depends on the order in which atomics land; nothing that is
+// computed from the slot depends on it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "maxsim_kernels.h"
+
+namespace espn {
+
+// counters: [0] distinct documents, [1] rows reserved
+__global__ void staging_clear_kernel(unsigned *__restrict__ bits, int64_t n_words,
+                                     unsigned long long *__restrict__ counters)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += stride) bits[i] = 0u;
+    if (blockIdx.x == 0 && threadIdx.x < 4) counters[threadIdx.x] = 0ull;
+}
+
+__global__ __launch_bounds__(256) void staging_mark_kernel(
+    const int64_t *__restrict__ cand, int64_t n_pairs, const int64_t *__restrict__ off, int64_t n_docs,
+    unsigned *__restrict__ bits, int64_t *__restrict__ row_map, int64_t *__restrict__ uniq,
+    unsigned long long *__restrict__ counters, int64_t capacity_rows, int64_t capacity_docs,
+    unsigned *__restrict__ err)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool first = false;
+    int64_t id = 0;
+    long long len = 0;
+    if (i < n_pairs) {
+        id = cand[i];
+        if (id >= 0 && id < n_docs) {
+            const unsigned m = 1u << (id & 31);
+            first = (atomicOr(&bits[id >> 5], m) & m) == 0u;
+            if (first) len = off[id + 1] - off[id];
+        } else {
+            atomicOr(err, ERR_ID_RANGE);
+        }
+    }
+    const uint64_t firsts = __ballot(first);
+    if (firsts == 0) return;                                   // wave-uniform
+    // inclusive prefix sum of len over the wave
+    long long incl = len;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const long long up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    const long long total = __shfl(incl, 63);
+    const int n_first = __builtin_popcountll(firsts);
+    unsigned long long row_base = 0, doc_base = 0;
+    const int leader = __builtin_ctzll(firsts);
+    if (lane == leader) {
+        row_base = atomicAdd(&counters[1], (unsigned long long)total);
+        doc_base = atomicAdd(&counters[0], (unsigned long long)n_first);
+    }
+    row_base = __shfl(row_base, leader);
+    doc_base = __shfl(doc_base, leader);
+    if (first) {
+        const long long r0 = (long long)row_base + (incl - len);
+        const int rank = __builtin_popcountll(firsts & ((1ull << lane) - 1ull));
+        const long long slot_pos = (long long)doc_base + rank;
+        // every list position below the capacity is written (the copy kernel reads them all);
+        // a document that does not fit is listed with no rows
+        const bool fits = r0 + len <= capacity_rows && slot_pos < capacity_docs;
+        if (slot_pos < capacity_docs) uniq[slot_pos] = id;
+        row_map[id] = fits ? r0 : -1;
+        if (!fits) atomicOr(err, ERR_STAGING_FULL);
+    }
+}
+
+// D = row length in binary16 elements (multiple of 8).  host_emb is device-visible pinned host memory.
+__global__ __launch_bounds__(256) void staging_gather_kernel(
+    const uint16_t *__restrict__ host_emb, const int64_t *__restrict__ off, const int64_t *__restrict__ uniq,
+    const int64_t *__restrict__ row_map, const unsigned long long *__restrict__ counters, int64_t capacity_docs,
+    uint16_t *__restrict__ slot, int D)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int64_t n = min((int64_t)counters[0], capacity_docs);
+    const int chunks_per_row = D / 8;
+    for (int64_t u = wave; u < n; u += n_waves) {
+        const int64_t id = uniq[u];
+        const int64_t r0 = row_map[id];
+        if (r0 < 0) continue;
+        const int64_t first = off[id];
+        const int64_t n_chunks = (off[id + 1] - first) * chunks_per_row;
+        const uint4 *src = reinterpret_cast<const uint4 *>(host_emb + (size_t)first * D);
+        uint4 *dst = reinterpret_cast<uint4 *>(slot + (size_t)r0 * D);
+        int64_t x = lane;
+        for (; x + 7 * 64 < n_chunks; x += 8 * 64) {           // 8 KiB in flight per wave
+            uint4 v[8];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) v[y] = src[x + 64 * y];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) dst[x + 64 * y] = v[y];
+        }
+        for (; x < n_chunks; x += 64) dst[x] = src[x];
+    }
+}
+
+}  // namespace espn

@@ -1,0 +1,127 @@
+"""Host-resident table: prefetch into HBM staging slots + staged re-rank, against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_05417_amd import binding as espn
+from paper_2312_05417_amd import synth
+from tests.parity import assert_scores_close, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def host_table(w, seed=synth.DEFAULT_SEED):
+    off = synth.offsets_from_counts(synth.token_counts(w, seed))
+    pinned = torch.empty((int(off[-1]), w.dim), dtype=torch.float16, pin_memory=True)
+    synth.table(w, seed, device="cpu", out=pinned)
+    return pinned, off
+
+
+def scores_of(ws, B, K):
+    return ws[: 4 * B * K].view(torch.float32).view(B, K).cpu().numpy()
+
+
+@pytest.mark.parametrize("key,changes", [
+    ("c5", dict(n_docs=20_000, B=16, K=300)),                  # d=128, Zipf: heavy repeats across queries
+    ("c2", dict(n_docs=5_000, B=8, K=200, cand_law="zipf")),   # d=32
+    ("c1", dict(dim=64, n_docs=2_000, B=4, K=50)),             # generic kernel
+])
+def test_double_buffered_batches_match_the_oracle(key, changes):
+    w = synth.scaled(synth.WORKLOADS[key], **changes)
+    say("host-resident %s d=%d N=%d B=%d K=%d" % (w.name, w.dim, w.n_docs, w.B, w.K))
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    assert table.info()["residency"] == espn.ESPN_RESIDENT_HOST_PINNED
+    espn.espn_staging_create(table, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    n_batches = 5
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    cands_d = [torch.from_numpy(c).to(DEV) for c in cands]
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    qs_d = [x.to(DEV) for x in qs]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    outs = []
+    espn.espn_prefetch(table, cands_d[0], 0, side)
+    for n in range(n_batches):
+        if n + 1 < n_batches:
+            espn.espn_prefetch(table, cands_d[n + 1], (n + 1) % 2, side)
+        outs.append(espn.espn_rerank_staged(table, n % 2, qs_d[n], cands_d[n], w.k, stream=main))
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    e = emb.numpy()
+    for n in range(n_batches):
+        ids, top, ws = outs[n]
+        o_ids, o_top, o_all = oracle.rerank(e, off, qs[n].numpy(), cands[n], w.k)
+        assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
+        for b in range(w.B):
+            assert_topk_matches(ids[b].cpu().numpy(), top[b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+    # what the last prefetches moved: exactly the distinct documents of their batches, each once
+    for n in (n_batches - 2, n_batches - 1):
+        c = espn.espn_staging_counters(table, n % 2)
+        uniq = np.unique(cands[n])
+        rows = int((off[uniq + 1] - off[uniq]).sum())
+        assert c["distinct_docs"] == uniq.size and c["rows"] == rows and c["pcie_bytes"] == rows * w.dim * 2
+        assert c["distinct_docs"] < cands[n].size          # the candidate law repeats documents
+    table.free()
+
+
+def test_hbm_entry_points_refuse_a_host_table_and_staging_refuses_an_hbm_table():
+    w = synth.scaled(synth.WORKLOADS["c1"], n_docs=500, B=2, K=20)
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    q, cand = synth.queries(w).to(DEV), torch.from_numpy(synth.candidates(w)).to(DEV)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_rerank(table, q, cand, 5)
+    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch(table, cand, 0)                  # no staging yet
+    assert ei.value.status == espn.ESPN_ERR_ARG
+    espn.espn_staging_create(table, 100, 10)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch(table, cand, 2)
+    assert ei.value.status == espn.ESPN_ERR_ARG
+    hbm = espn.espn_table_load(emb.to(DEV), off)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_staging_create(hbm, 100, 10)
+    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+
+
+def test_slot_overflow_and_foreign_candidates_are_flagged_not_read():
+    w = synth.scaled(synth.WORKLOADS["c1"], n_docs=500, B=4, K=40)
+    say("staging overflow / not staged")
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    cand = synth.candidates(w)
+    cand_d = torch.from_numpy(cand).to(DEV)
+    q = synth.queries(w)
+    q_d = q.to(DEV)
+    # slot too small for the batch: flagged, the documents that did not fit score -inf, the rest are right
+    espn.espn_staging_create(table, capacity_rows=600, capacity_docs=500)
+    espn.espn_prefetch(table, cand_d, 0)
+    ids, top, ws = espn.espn_rerank_staged(table, 0, q_d, cand_d, w.k)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_table_check(table)
+    assert ei.value.status in (espn.ESPN_ERR_NOMEM, espn.ESPN_ERR_SHAPE)
+    g = scores_of(ws, w.B, w.K)
+    o = oracle.scores(emb.numpy(), off, q.numpy(), cand)
+    held = ~np.isneginf(g)
+    assert held.any() and (~held).any()
+    assert_scores_close(g[held], o[held], w.Q)
+    # big enough slot, but the re-rank names documents that were not prefetched
+    espn.espn_staging_create(table, capacity_rows=int(off[-1]), capacity_docs=500)
+    part = cand_d[:, :20].contiguous()
+    espn.espn_prefetch(table, part, 1)
+    ids, top, ws = espn.espn_rerank_staged(table, 1, q_d, cand_d, w.k)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_table_check(table)
+    assert ei.value.status == espn.ESPN_ERR_SHAPE
+    g = scores_of(ws, w.B, w.K)
+    staged = np.isin(cand, cand[:, :20])
+    assert np.all(np.isneginf(g[~staged]))
+    assert_scores_close(g[staged], o[staged], w.Q)
+    table.free()
