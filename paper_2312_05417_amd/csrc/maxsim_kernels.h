@@ -168,20 +168,17 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D> &buf, const uint16_t 
     }
 }
 
+// Scores candidates j0 .. j0+DOCS-1 (j0 < K) of query b with the calling wave and stores them.
 template <int D, int DOCS, int P>
-__global__ __launch_bounds__(256) void maxsim_mfma_kernel(
-    const DocSource src, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
-    int B, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
+__device__ __forceinline__ void maxsim_mfma_wave(
+    const DocSource &src, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
+    int b, int j0, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
 {
     const uint16_t *__restrict__ emb = src.emb;
     static_assert((D == 32 || D == 128) && DOCS >= 1 && DOCS <= 64 && P >= 1, "unsupported shape");
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
     const int r = lane & 15, c = lane >> 4;
-    const int b = blockIdx.y;
-    const int j0 = (blockIdx.x * 4 + wave) * DOCS;   // first candidate slot of this wave
-    if (j0 >= K) return;
     const int ndoc = min(DOCS, K - j0);
 
     // per-lane document descriptors: lane i describes candidate j0 + i
@@ -267,6 +264,18 @@ __global__ __launch_bounds__(256) void maxsim_mfma_kernel(
         }
     }
     if (lane < ndoc) scores[(size_t)b * K + j0 + lane] = result;
+}
+
+// grid = (ceil(ceil(K / DOCS) / 4), B), 256 threads: wave w of workgroup x takes candidates
+// (4x + w) * DOCS .. of query blockIdx.y
+template <int D, int DOCS, int P>
+__global__ __launch_bounds__(256) void maxsim_mfma_kernel(
+    const DocSource src, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
+    int B, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
+{
+    const int j0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * DOCS;
+    if (j0 >= K) return;
+    maxsim_mfma_wave<D, DOCS, P>(src, q, cand, blockIdx.y, j0, Q, K, scores, err);
 }
 
 // ---------------------------------------------------------------------------------------------

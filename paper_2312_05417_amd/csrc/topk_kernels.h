@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
 // picked).  Each lane holds PER keys in registers.  The k-th largest of the 64 per-lane maxima is a
 // lower bound theta for the k-th best key overall (at least k elements reach it), so every entry
 // that can appear in the ranked top-k, including all ties with the k-th, has key >= theta.  Those
-// few entries are compacted (ballot + mbcnt, in slot order), their ids are fetched, and each one
+// few entries are compacted (ballot + mbcnt, in slot order) together with their ids, and each one
 // counts how many others rank before it; entries whose count is below k write themselves to that
 // position.  Only if more than 64 entries survive (massive exact ties) the survivors are ranked by
 // the k-round selection, from LDS.
@@ -155,26 +155,43 @@ __device__ __forceinline__ unsigned wave_max_u32(unsigned v)
     return max(max(a, b), max(c, d));
 }
 
+// LDS one wave needs for topk_wave_body<PER>
 template <int PER>
-__global__ __launch_bounds__(64) void topk_wave_kernel(
-    const float *__restrict__ scores, const int64_t *__restrict__ cand, int K, int k,
-    int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
-{
-    __shared__ unsigned s_key[64 * PER];
-    __shared__ int s_slot[64 * PER];
-    const int b = blockIdx.x;
-    const int lane = threadIdx.x;
-    const float *sc = scores + (size_t)b * K;
-    const int64_t *ids = cand + (size_t)b * K;
+struct TopkWaveLds {
+    unsigned key[64 * PER];
+    int slot[64 * PER];
+    int64_t id[64 * PER];
+};
 
+// Executed by ONE wave (lane = 0..63) for one query: sc/ids point at the query's K scores and ids,
+// out_ids/out_scores at its k outputs.  Uses no workgroup barrier, so a single wave of a larger
+// workgroup may call it.
+template <int PER>
+__device__ __forceinline__ void topk_wave_body(
+    const float *sc, const int64_t *ids, int K, int k, int64_t *out_ids, float *out_scores, int lane,
+    TopkWaveLds<PER> &lds)
+{
+    unsigned *s_key = lds.key;
+    int *s_slot = lds.slot;
+    int64_t *s_id = lds.id;
+
+    // scores and ids are fetched together (one round trip to memory instead of two dependent ones)
     unsigned key[PER];
+    int64_t idr[PER];
+    {
+        float v[PER];
+#pragma unroll
+        for (int x = 0; x < PER; ++x) {      // all loads first: one round trip, not PER of them
+            const int slot = min(x * 64 + lane, K - 1);
+            v[x] = sc[slot];
+            idr[x] = ids[slot];
+        }
+#pragma unroll
+        for (int x = 0; x < PER; ++x) key[x] = (x * 64 + lane < K) ? order_key(v[x]) : 0u;
+    }
     unsigned local_max = 0;
 #pragma unroll
-    for (int x = 0; x < PER; ++x) {
-        const int slot = x * 64 + lane;
-        key[x] = slot < K ? order_key(sc[slot]) : 0u;
-        local_max = max(local_max, key[x]);
-    }
+    for (int x = 0; x < PER; ++x) local_max = max(local_max, key[x]);
 
     // theta = k-th largest of the per-lane maxima (1 if fewer than k lanes hold anything)
     unsigned theta = 1u;
@@ -200,17 +217,19 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
                                                               __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
             s_key[pos] = key[x];
             s_slot[pos] = x * 64 + lane;
+            s_id[pos] = idr[x];
         }
         total += __builtin_popcountll(mask);
     }
-    __syncthreads();
+    // the same wave wrote and now reads: LDS keeps a wave's accesses in order, the fence keeps the compiler from moving them
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 
     if (total <= 64) {
         // one survivor per lane: rank = number of survivors that come before it
         const bool have = lane < total;
         const unsigned my_key = have ? s_key[lane] : 0u;
-        const int my_slot = have ? s_slot[lane] : 0;
-        const int64_t my_id = have ? ids[my_slot] : 0;
+        const int64_t my_id = have ? s_id[lane] : 0;
         int rank = 0;
         for (int i = 0; i < total; ++i) {
             const unsigned ki = (unsigned)__builtin_amdgcn_readlane((int)my_key, i);
@@ -221,13 +240,13 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
             rank += before ? 1 : 0;
         }
         if (have && rank < k) {
-            out_ids[(size_t)b * k + rank] = my_id;
-            out_scores[(size_t)b * k + rank] = key_to_score(my_key);
+            out_ids[rank] = my_id;
+            out_scores[rank] = key_to_score(my_key);
         }
         // fewer rankable entries than k (NaN scores): mark the rest
         for (int rest = total + lane; rest < k; rest += 64) {
-            out_ids[(size_t)b * k + rest] = -1;
-            out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+            out_ids[rest] = -1;
+            out_scores[rest] = __builtin_nanf("");
         }
         return;
     }
@@ -242,7 +261,7 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
             Ranked e;
             e.score = key_to_score(s_key[i]);
             e.slot = s_slot[i];
-            e.id = ids[e.slot];
+            e.id = s_id[i];
             const bool after_prev = (round == 0) || ranks_before(prev, e);
             if (after_prev && ranks_before(e, best)) best = e;
         }
@@ -252,18 +271,29 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
             if (ranks_before(o, best)) best = o;
         }
         if (lane == 0) {
-            out_ids[(size_t)b * k + round] = best.slot >= 0 ? best.id : (int64_t)-1;
-            out_scores[(size_t)b * k + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+            out_ids[round] = best.slot >= 0 ? best.id : (int64_t)-1;
+            out_scores[round] = best.slot >= 0 ? best.score : __builtin_nanf("");
         }
         prev = best;
         if (best.slot < 0) {
             for (int rest = round + 1 + lane; rest < k; rest += 64) {
-                out_ids[(size_t)b * k + rest] = -1;
-                out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+                out_ids[rest] = -1;
+                out_scores[rest] = __builtin_nanf("");
             }
             break;
         }
     }
+}
+
+template <int PER>
+__global__ __launch_bounds__(64) void topk_wave_kernel(
+    const float *__restrict__ scores, const int64_t *__restrict__ cand, int K, int k,
+    int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
+{
+    __shared__ TopkWaveLds<PER> lds;
+    const int b = blockIdx.x;
+    topk_wave_body<PER>(scores + (size_t)b * K, cand + (size_t)b * K, K, k, out_ids + (size_t)b * k,
+                        out_scores + (size_t)b * k, (int)threadIdx.x, lds);
 }
 
 }  // namespace espn
