@@ -148,12 +148,14 @@ int espn_table_check(espn_table *table, void *stream);
  * ------------------------------------------------------------------------------------------- */
 
 /*
- * Allocate the two staging slots of a host-resident table (replacing earlier ones).
+ * Allocate the two staging slots of a table (replacing earlier ones).  Meant for host-resident
+ * tables; an HBM-resident table may be staged too (the prefetch is then a stand-alone gather of the
+ * batch's distinct documents, HBM to HBM).
  *   capacity_rows  embedding rows one slot can hold (each slot takes capacity_rows * dim * 2 bytes of
  *                  HBM, plus 8 bytes per document of the table for its row map).
  *   capacity_docs  distinct documents one slot can hold.
  * A prefetch that needs more raises a flag that espn_table_check reports as ESPN_ERR_NOMEM.
- * Synchronous.  Errors: ARG, UNSUPPORTED (table is HBM-resident), NOMEM, HIP.
+ * Synchronous.  Errors: ARG, NOMEM, HIP.
  */
 int espn_staging_create(espn_table *table, int64_t capacity_rows, int64_t capacity_docs);
 

@@ -385,8 +385,6 @@ ESPN_API int espn_table_check(espn_table *table, void *stream)
 ESPN_API int espn_staging_create(espn_table *table, int64_t capacity_rows, int64_t capacity_docs)
 {
     if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
-    if (table->residency != ESPN_RESIDENT_HOST_PINNED)
-        return fail(ESPN_ERR_UNSUPPORTED, "staging is for host-resident tables");
     if (capacity_rows < 1 || capacity_docs < 1) return fail(ESPN_ERR_ARG, "capacities must be positive");
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);

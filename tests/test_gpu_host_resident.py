@@ -70,7 +70,7 @@ def test_double_buffered_batches_match_the_oracle(key, changes):
     table.free()
 
 
-def test_hbm_entry_points_refuse_a_host_table_and_staging_refuses_an_hbm_table():
+def test_hbm_entry_points_refuse_a_host_table():
     w = synth.scaled(synth.WORKLOADS["c1"], n_docs=500, B=2, K=20)
     emb, off = host_table(w)
     table = espn.espn_table_load(emb, off)
@@ -85,10 +85,25 @@ def test_hbm_entry_points_refuse_a_host_table_and_staging_refuses_an_hbm_table()
     with pytest.raises(espn.EspnError) as ei:
         espn.espn_prefetch(table, cand, 2)
     assert ei.value.status == espn.ESPN_ERR_ARG
-    hbm = espn.espn_table_load(emb.to(DEV), off)
-    with pytest.raises(espn.EspnError) as ei:
-        espn.espn_staging_create(hbm, 100, 10)
-    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+
+
+def test_an_hbm_table_can_be_staged_too_as_a_standalone_gather():
+    w = synth.scaled(synth.WORKLOADS["c4"], n_docs=3_000, B=8, K=100)
+    say("stand-alone gather HBM -> HBM")
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    cand = synth.candidates(w)
+    cand_d, q = torch.from_numpy(cand).to(DEV), synth.queries(w)
+    espn.espn_staging_create(table, int(off[-1]), w.n_docs)
+    espn.espn_prefetch(table, cand_d, 0)
+    ids, top, ws = espn.espn_rerank_staged(table, 0, q.to(DEV), cand_d, w.k)
+    ids2, top2 = espn.espn_rerank(table, q.to(DEV), cand_d, w.k)
+    espn.espn_table_check(table)
+    assert torch.equal(ids, ids2) and torch.equal(top, top2)          # same rows, same kernel: bit-identical
+    o = oracle.scores(emb.numpy(), off, q.numpy(), cand)
+    assert_scores_close(scores_of(ws, w.B, w.K), o, w.Q)
+    u = np.unique(cand)
+    assert espn.espn_staging_counters(table, 0)["distinct_docs"] == u.size
 
 
 def test_slot_overflow_and_foreign_candidates_are_flagged_not_read():
