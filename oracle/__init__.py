@@ -48,6 +48,16 @@ def _load():
         lib.espn_oracle_rerank.restype = ctypes.c_int
         lib.espn_oracle_rerank.argtypes = [c_p, c_p, c_i64, c_i32, c_p, c_p, c_i32, c_i32, c_i32, c_i32,
                                            c_p, c_p, c_p, c_i32]
+        lib.espn_oracle_scores_prior.restype = ctypes.c_int
+        lib.espn_oracle_scores_prior.argtypes = [c_p, c_p, c_i64, c_i32, c_p, c_p, c_p, ctypes.c_double,
+                                                 c_i32, c_i32, c_i32, c_p, c_i32]
+        lib.espn_oracle_rerank_partial.restype = ctypes.c_int
+        lib.espn_oracle_rerank_partial.argtypes = [c_p, c_p, c_i64, c_i32, c_p, c_p, c_i32, c_i32, c_i32, c_i32,
+                                                   c_i32, c_p, c_p, c_i32]
+        lib.espn_oracle_merge.restype = ctypes.c_int
+        lib.espn_oracle_merge.argtypes = [c_p, c_p, c_i32, c_p, c_p, c_i32, c_i32, c_i32, c_p, c_p]
+        lib.espn_oracle_batch_threshold.restype = ctypes.c_double
+        lib.espn_oracle_batch_threshold.argtypes = [ctypes.c_double] * 3
         lib.espn_oracle_max_threads.restype = c_i32
         lib.espn_oracle_max_threads.argtypes = []
         _lib = lib
@@ -144,3 +154,57 @@ def rerank(emb, offsets, q, cand, k: int, threads: int = 0):
 
 def max_threads() -> int:
     return int(_load().espn_oracle_max_threads())
+
+
+def scores_prior(emb, offsets, q, cand, prior, alpha: float, threads: int = 0) -> np.ndarray:
+    """MaxSim score plus alpha times the first-stage score (Sec. 3.1): fp64 [B,K]."""
+    eb, off, qb, cd = _check(emb, offsets, q, cand)
+    pr = np.ascontiguousarray(np.asarray(prior, dtype=np.float32))
+    if pr.shape != cd.shape:
+        raise ValueError("prior must be [B,K]")
+    B, Q, d = qb.shape
+    K = cd.shape[1]
+    out = np.empty((B, K), dtype=np.float64)
+    rc = _load().espn_oracle_scores_prior(_ptr(eb), _ptr(off), off.shape[0] - 1, d, _ptr(qb), _ptr(cd), _ptr(pr),
+                                          float(alpha), B, Q, K, _ptr(out), threads)
+    if rc != 0:
+        raise ValueError("candidate id outside [0, n_docs)")
+    return out
+
+
+def rerank_partial(emb, offsets, q, cand, R: int, k: int, threads: int = 0):
+    """Partial re-ranking (Sec. 4.4): (ids [B,k], scores [B,k]); entries beyond the re-ranked R carry NaN."""
+    eb, off, qb, cd = _check(emb, offsets, q, cand)
+    B, Q, d = qb.shape
+    K = cd.shape[1]
+    ids = np.empty((B, k), dtype=np.int64)
+    top = np.empty((B, k), dtype=np.float64)
+    rc = _load().espn_oracle_rerank_partial(_ptr(eb), _ptr(off), off.shape[0] - 1, d, _ptr(qb), _ptr(cd),
+                                            B, Q, K, R, k, _ptr(ids), _ptr(top), threads)
+    if rc != 0:
+        raise ValueError("bad R or k, or candidate id outside [0, n_docs)")
+    return ids, top
+
+
+def merge(ids_a, sc_a, ids_b, sc_b, k: int):
+    """First k of the union of two scored lists per query (Sec. 4.3), in ranking order."""
+    ia = np.ascontiguousarray(np.asarray(ids_a, dtype=np.int64))
+    ib = np.ascontiguousarray(np.asarray(ids_b, dtype=np.int64))
+    sa = np.ascontiguousarray(np.asarray(sc_a, dtype=np.float64))
+    sb = np.ascontiguousarray(np.asarray(sc_b, dtype=np.float64))
+    if ia.shape != sa.shape or ib.shape != sb.shape or ia.ndim != 2 or ib.ndim != 2 or ia.shape[0] != ib.shape[0]:
+        raise ValueError("expected [B,ka] and [B,kb] lists")
+    if np.isnan(sa).any() or np.isnan(sb).any():
+        raise ValueError("NaN scores have no rank")
+    B = ia.shape[0]
+    ids = np.empty((B, k), dtype=np.int64)
+    out = np.empty((B, k), dtype=np.float64)
+    if _load().espn_oracle_merge(_ptr(ia), _ptr(sa), ia.shape[1], _ptr(ib), _ptr(sb), ib.shape[1], B, k,
+                                 _ptr(ids), _ptr(out)) != 0:
+        raise ValueError("k must lie in [0, ka + kb]")
+    return ids, out
+
+
+def batch_threshold(bandwidth_bytes_per_s: float, budget_s: float, bytes_per_query: float) -> float:
+    """Eq. 4."""
+    return float(_load().espn_oracle_batch_threshold(bandwidth_bytes_per_s, budget_s, bytes_per_query))

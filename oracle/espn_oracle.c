@@ -163,6 +163,96 @@ int espn_oracle_rerank(const uint16_t *emb, const int64_t *offsets, int64_t n_do
     return rc;
 }
 
+/*
+ * Score aggregation (Sec. 3.1): the MaxSim score of a candidate is combined with the score the
+ * candidate generator gave it, through a scaling factor:  total = S + alpha * prior.
+ *   prior : [B, K] binary32 first-stage scores (widened exactly), alpha a plain argument.
+ */
+int espn_oracle_scores_prior(const uint16_t *emb, const int64_t *offsets, int64_t n_docs, int32_t d,
+                             const uint16_t *q, const int64_t *cand, const float *prior, double alpha,
+                             int32_t B, int32_t Q, int32_t K, double *scores, int32_t threads)
+{
+    int rc = espn_oracle_scores(emb, offsets, n_docs, d, q, cand, B, Q, K, scores, threads);
+    if (rc != 0) return rc;
+    for (int64_t x = 0; x < (int64_t)B * K; ++x) scores[x] = scores[x] + alpha * (double)prior[x];
+    return 0;
+}
+
+/*
+ * Partial re-ranking (Sec. 4.4).  The candidate list of a query arrives in the first stage's order,
+ * best first.  Only its first R entries are scored with MaxSim and sorted by that score; the other
+ * K - R entries are appended behind them in the order they came.  The first k entries of the
+ * resulting list are written out.  Entries that were not re-ranked carry no MaxSim score: NaN.
+ *   cand [B,K]  ->  out_ids [B,k], out_scores [B,k];  0 <= R <= K, 0 <= k <= K.
+ */
+int espn_oracle_rerank_partial(const uint16_t *emb, const int64_t *offsets, int64_t n_docs, int32_t d,
+                               const uint16_t *q, const int64_t *cand,
+                               int32_t B, int32_t Q, int32_t K, int32_t R, int32_t k,
+                               int64_t *out_ids, double *out_scores, int32_t threads)
+{
+    if (R < 0 || R > K || k < 0 || k > K) return -1;
+    int64_t *head = (int64_t *)malloc(sizeof(int64_t) * ((size_t)B * R + 1));
+    int64_t *ids = (int64_t *)malloc(sizeof(int64_t) * ((size_t)B * R + 1));
+    double *top = (double *)malloc(sizeof(double) * ((size_t)B * R + 1));
+    if (!head || !ids || !top) { free(head); free(ids); free(top); return -1; }
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t j = 0; j < R; ++j) head[(int64_t)b * R + j] = cand[(int64_t)b * K + j];
+    /* the first R candidates, fully ranked among themselves */
+    int rc = espn_oracle_rerank(emb, offsets, n_docs, d, q, head, B, Q, R, R, ids, top, NULL, threads);
+    if (rc == 0) {
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t j = 0; j < k; ++j) {
+                if (j < R) {
+                    out_ids[(int64_t)b * k + j] = ids[(int64_t)b * R + j];
+                    out_scores[(int64_t)b * k + j] = top[(int64_t)b * R + j];
+                } else {
+                    out_ids[(int64_t)b * k + j] = cand[(int64_t)b * K + j];
+                    out_scores[(int64_t)b * k + j] = NAN;
+                }
+            }
+    }
+    free(head); free(ids); free(top);
+    return rc;
+}
+
+/*
+ * Merging two scored lists of one query (Sec. 4.3: the documents re-ranked early by the
+ * prefetcher and those re-ranked afterwards are combined by sorting on the score).
+ *   a: ids_a/sc_a [B,ka], b: ids_b/sc_b [B,kb]  ->  the first k of their union in ranking order.
+ */
+int espn_oracle_merge(const int64_t *ids_a, const double *sc_a, int32_t ka,
+                      const int64_t *ids_b, const double *sc_b, int32_t kb,
+                      int32_t B, int32_t k, int64_t *out_ids, double *out_scores)
+{
+    const int32_t n = ka + kb;
+    if (ka < 0 || kb < 0 || k < 0 || k > n) return -1;
+    int64_t *ids = (int64_t *)malloc(sizeof(int64_t) * ((size_t)B * n + 1));
+    double *sc = (double *)malloc(sizeof(double) * ((size_t)B * n + 1));
+    if (!ids || !sc) { free(ids); free(sc); return -1; }
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t j = 0; j < ka; ++j) {
+            ids[(int64_t)b * n + j] = ids_a[(int64_t)b * ka + j];
+            sc[(int64_t)b * n + j] = sc_a[(int64_t)b * ka + j];
+        }
+        for (int32_t j = 0; j < kb; ++j) {
+            ids[(int64_t)b * n + ka + j] = ids_b[(int64_t)b * kb + j];
+            sc[(int64_t)b * n + ka + j] = sc_b[(int64_t)b * kb + j];
+        }
+    }
+    int rc = espn_oracle_topk(sc, ids, B, n, k, out_ids, out_scores);
+    free(ids); free(sc);
+    return rc;
+}
+
+/*
+ * Eq. 4: the largest query batch whose embedding fetch still fits the time it may hide behind,
+ *   threshold = bandwidth * budget / (data size per query).
+ */
+double espn_oracle_batch_threshold(double bandwidth_bytes_per_s, double budget_s, double bytes_per_query)
+{
+    return bandwidth_bytes_per_s * budget_s / bytes_per_query;
+}
+
 /* Number of threads the parallel loop over queries will use (for reporting). */
 int32_t espn_oracle_max_threads(void)
 {

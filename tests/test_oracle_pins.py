@@ -332,3 +332,110 @@ def test_thread_count_does_not_change_results():
     b = oracle.rerank(emb, off, q, cand, 5, threads=4)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+# ================================================================ widened path: partial re-ranking,
+# score aggregation, merging, batch threshold
+def parse_extras(path):
+    out = {"partial": []}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        tag, *rest = line.split()
+        if tag == "partial":
+            i, j = rest.index("ids"), rest.index("scores")
+            out["partial"].append((int(rest[0]), [int(x) for x in rest[i + 1:j]], [float(x) for x in rest[j + 1:]]))
+        elif tag == "prior_alpha":
+            out["alpha"] = float(rest[0])
+        elif tag == "prior":
+            out["prior"] = [float(x) for x in rest]
+        elif tag == "prior_rank_ids":
+            out["prior_ids"] = [int(x) for x in rest]
+        elif tag == "prior_rank_scores":
+            out["prior_scores"] = [float(x) for x in rest]
+    return out
+
+
+def same_with_nan(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    return np.array_equal(np.isnan(a), np.isnan(b)) and np.array_equal(a[~np.isnan(a)], b[~np.isnan(b)])
+
+
+def test_handworked_partial_reranking():
+    path = os.path.join(GOLDEN, "handworked_rerank.txt")
+    emb, off, q, cand, _ = parse_rerank(path)
+    for R, ids_want, sc_want in parse_extras(path)["partial"]:
+        for k in range(0, 6):
+            ids, sc = oracle.rerank_partial(emb, off, q, cand, R, k)
+            assert ids[0].tolist() == ids_want[:k]
+            assert same_with_nan(sc[0], sc_want[:k])
+
+
+def test_partial_reranking_reduces_to_the_full_ranking_and_to_the_prefix_ranking():
+    emb, off, q, cand = small_problem(21, N=60, K=30, B=4)
+    K = cand.shape[1]
+    full_ids, full_top, _ = oracle.rerank(emb, off, q, cand, K)
+    ids, sc = oracle.rerank_partial(emb, off, q, cand, K, K)
+    assert np.array_equal(ids, full_ids) and np.array_equal(sc, full_top)
+    for R in (1, 7, 16):
+        head_ids, head_top, _ = oracle.rerank(emb, off, q, np.ascontiguousarray(cand[:, :R]), R)
+        ids, sc = oracle.rerank_partial(emb, off, q, cand, R, K)
+        assert np.array_equal(ids[:, :R], head_ids) and np.array_equal(sc[:, :R], head_top)
+        assert np.array_equal(ids[:, R:], cand[:, R:]) and np.isnan(sc[:, R:]).all()
+        assert all(sorted(r.tolist()) == sorted(c.tolist()) for r, c in zip(ids, cand))   # a permutation of the list
+    ids, sc = oracle.rerank_partial(emb, off, q, cand, 0, 9)
+    assert np.array_equal(ids, cand[:, :9]) and np.isnan(sc).all()
+    with pytest.raises(ValueError):
+        oracle.rerank_partial(emb, off, q, cand, K + 1, 3)
+
+
+def test_handworked_score_aggregation_and_its_special_cases():
+    path = os.path.join(GOLDEN, "handworked_rerank.txt")
+    emb, off, q, cand, _ = parse_rerank(path)
+    ex = parse_extras(path)
+    tot = oracle.scores_prior(emb, off, q, cand, np.array([ex["prior"]], dtype=np.float32), ex["alpha"])
+    ids, top = oracle.topk(tot, cand, 5)
+    assert ids[0].tolist() == ex["prior_ids"] and top[0].tolist() == ex["prior_scores"]
+    emb, off, q, cand = small_problem(22, integer=True, lo=1)
+    base = oracle.scores(emb, off, q, cand)
+    prior = np.random.default_rng(0).integers(-9, 10, size=cand.shape).astype(np.float32)
+    assert np.array_equal(oracle.scores_prior(emb, off, q, cand, prior, 0.0), base)            # alpha = 0
+    assert np.array_equal(oracle.scores_prior(emb, off, q, cand, prior, 0.5), base + 0.5 * prior)   # exact values
+    assert np.array_equal(oracle.scores_prior(emb, off, q, cand, np.zeros_like(prior), 3.0), base)
+    a = oracle.scores_prior(emb, off, q, cand, prior, 1.0) + oracle.scores_prior(emb, off, q, cand, -prior, 1.0)
+    assert np.array_equal(a, 2 * base)
+
+
+def test_merging_two_parts_of_a_list_gives_the_ranking_of_the_whole():
+    rng = np.random.default_rng(23)
+    B, K = 3, 40
+    sc = np.round(rng.normal(size=(B, K)), 1)
+    ids = np.stack([rng.permutation(500)[:K] for _ in range(B)]).astype(np.int64)
+    for cut, k in ((0, 5), (13, 10), (39, 40), (40, 7)):
+        want_ids, want_sc = oracle.topk(sc, ids, k)
+        got_ids, got_sc = oracle.merge(ids[:, :cut], sc[:, :cut], ids[:, cut:], sc[:, cut:], k)
+        assert np.array_equal(got_ids, want_ids) and np.array_equal(got_sc, want_sc)
+    # merging ranked top lists of the two parts is enough for the top of the whole
+    a_ids, a_sc = oracle.topk(sc[:, :20], ids[:, :20], 6)
+    b_ids, b_sc = oracle.topk(sc[:, 20:], ids[:, 20:], 6)
+    want_ids, want_sc = oracle.topk(sc, ids, 6)
+    got_ids, got_sc = oracle.merge(a_ids, a_sc, b_ids, b_sc, 6)
+    assert np.array_equal(got_ids, want_ids) and np.array_equal(got_sc, want_sc)
+    # hand-made: a = (5: id 7), (1: id 2); b = (5: id 3), (4: id 9) -> 3, 7, 9, 2
+    got_ids, got_sc = oracle.merge([[7, 2]], [[5.0, 1.0]], [[3, 9]], [[5.0, 4.0]], 4)
+    assert got_ids.tolist() == [[3, 7, 9, 2]] and got_sc.tolist() == [[5.0, 5.0, 4.0, 1.0]]
+    with pytest.raises(ValueError):
+        oracle.merge([[7, 2]], [[5.0, 1.0]], [[3, 9]], [[5.0, 4.0]], 5)
+
+
+def test_batch_threshold_follows_eq4_and_the_papers_own_scaling_statements():
+    # the value itself
+    assert oracle.batch_threshold(3e9, 0.028, 7e6) == 3e9 * 0.028 / 7e6
+    # Sec. 5.4: twice the bandwidth doubles the limit (12 -> "around 24")
+    base = oracle.batch_threshold(1.0e9, 0.05, 4.0e6)
+    assert oracle.batch_threshold(2.0e9, 0.05, 4.0e6) == 2 * base
+    # Sec. 5.5: fetching the top 64 instead of 1000 documents per query cuts the data per query by
+    # 1000/64 and raises a limit of 12 to about the 192 the paper reports (187.5)
+    limit = 12 * oracle.batch_threshold(1.0, 1.0, 64.0) / oracle.batch_threshold(1.0, 1.0, 1000.0)
+    assert abs(limit - 192) / 192 < 0.03
