@@ -129,6 +129,60 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Partial re-ranking (Sec. 4.4): the candidate list of a query arrives best-first from the first
+ * stage; only its first R entries are scored with MaxSim and ranked, the remaining K - R entries
+ * follow them in the order they came.  Writes the first k entries of that combined list.
+ *
+ *   cand        [B, K] int64, DEVICE.   0 <= R <= K,  0 <= k <= K.
+ *   out_ids     [B, k] int64, DEVICE.   out_scores [B, k] binary32, DEVICE: the MaxSim score for
+ *               ranks below R, NaN (not scored) from rank R on.
+ *   workspace   DEVICE, 256-byte aligned, at least espn_workspace_bytes(B, R) bytes.
+ * Only R documents per query are read from the table.  HBM-resident tables only.
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
+ */
+int espn_rerank_partial(espn_table *table, const void *q, const int64_t *cand,
+                        int32_t B, int32_t Q, int32_t K, int32_t R, int32_t k,
+                        int64_t *out_ids, float *out_scores,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Re-ranking with score aggregation (Sec. 3.1: the MaxSim score is combined with the score the
+ * candidate generator gave the document, through a scaling factor):
+ *     total[b,j] = MaxSim(q[b], cand[b,j]) + alpha * prior[b,j]
+ * ranked as in espn_rerank; out_scores holds the totals.  The factor is a plain argument (the paper's
+ * is learned with the model).
+ *
+ *   prior  [B, K] binary32, DEVICE.   Other arguments as espn_rerank; afterwards the workspace holds
+ *          all B*K totals.
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
+ */
+int espn_rerank_prior(espn_table *table, const void *q, const int64_t *cand, const float *prior, float alpha,
+                      int32_t B, int32_t Q, int32_t K, int32_t k,
+                      int64_t *out_ids, float *out_scores,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Merge two scored lists per query (Sec. 4.3: documents re-ranked early, while the first stage was
+ * still running, and documents re-ranked afterwards are combined by sorting on the score): the first
+ * k entries of the union, in the order of espn_topk.  The lists need not be sorted.  A document that
+ * is in both lists appears twice.
+ *
+ *   ids_a [B, ka] int64, scores_a [B, ka] binary32;  ids_b [B, kb], scores_b [B, kb];  all DEVICE.
+ *   out_ids [B, k], out_scores [B, k], DEVICE, written.   0 <= k <= ka + kb.
+ * Errors: ARG, SHAPE, HIP.
+ */
+int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_t ka,
+                    const int64_t *ids_b, const float *scores_b, int32_t kb,
+                    int32_t B, int32_t k, int64_t *out_ids, float *out_scores, void *stream);
+
+/*
+ * Eq. 4: the largest query batch whose embedding fetch still fits the time it can hide behind,
+ *     bandwidth * budget / (data size per query).
+ * Host arithmetic only (no device is touched); returns 0 if bytes_per_query is not positive.
+ */
+double espn_batch_threshold(double bandwidth_bytes_per_s, double budget_s, double bytes_per_query);
+
+/*
  * Wait for `stream` and report errors kernels recorded for this table since the last check:
  * returns ESPN_ERR_ID_RANGE if any candidate id was out of range, else ESPN_OK; clears the flag.
  */

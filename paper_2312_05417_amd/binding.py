@@ -33,6 +33,12 @@ SIGNATURES = {
     "espn_topk": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
     "espn_workspace_bytes": (_c_sz, [_c_i32, _c_i32]),
     "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "espn_rerank_partial": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
+                                           _c_p, _c_sz, _c_p]),
+    "espn_rerank_prior": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_p, ctypes.c_float, _c_i32, _c_i32, _c_i32, _c_i32,
+                                         _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "espn_merge_topk": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
+    "espn_batch_threshold": (ctypes.c_double, [ctypes.c_double, ctypes.c_double, ctypes.c_double]),
     "espn_table_check": (ctypes.c_int, [_c_p, _c_p]),
     "espn_staging_create": (ctypes.c_int, [_c_p, _c_i64, _c_i64]),
     "espn_prefetch": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p]),
@@ -245,3 +251,65 @@ def espn_staging_counters(table: Table, slot: int, stream=None) -> dict:
     out = (ctypes.c_uint64 * 4)()
     _check(lib().espn_staging_counters(table.handle, slot, _stream_ptr(stream), out))
     return {"distinct_docs": int(out[0]), "rows": int(out[1]), "pcie_bytes": int(out[2]), "capacity_rows": int(out[3])}
+
+
+def _outputs(B, k, device, out_ids, out_scores):
+    if out_ids is None:
+        out_ids = torch.empty((B, max(k, 0)), dtype=torch.int64, device=device)
+    if out_scores is None:
+        out_scores = torch.empty((B, max(k, 0)), dtype=torch.float32, device=device)
+    return out_ids, out_scores
+
+
+def espn_rerank_partial(table: Table, q: torch.Tensor, cand: torch.Tensor, R: int, k: int,
+                        out_ids: torch.Tensor | None = None, out_scores: torch.Tensor | None = None,
+                        workspace: torch.Tensor | None = None, stream=None):
+    B, Q, K = _batch_shape(q, cand)
+    if q.shape[2] != table.dim:
+        raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
+    out_ids, out_scores = _outputs(B, k, q.device, out_ids, out_scores)
+    if workspace is None:
+        workspace = torch.empty(espn_workspace_bytes(B, max(R, 0)), dtype=torch.uint8, device=q.device)
+    _check(lib().espn_rerank_partial(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
+                                     B, Q, K, R, k, _dev(out_ids, torch.int64, "out_ids"),
+                                     _dev(out_scores, torch.float32, "out_scores"),
+                                     _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_scores
+
+
+def espn_rerank_prior(table: Table, q: torch.Tensor, cand: torch.Tensor, prior: torch.Tensor, alpha: float, k: int,
+                      out_ids: torch.Tensor | None = None, out_scores: torch.Tensor | None = None,
+                      workspace: torch.Tensor | None = None, stream=None):
+    """Returns (out_ids, out_scores, workspace); the workspace starts with all totals, fp32 [B,K]."""
+    B, Q, K = _batch_shape(q, cand)
+    if q.shape[2] != table.dim:
+        raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
+    if tuple(prior.shape) != (B, K):
+        raise ValueError("prior must be [B,K]")
+    out_ids, out_scores = _outputs(B, k, q.device, out_ids, out_scores)
+    if workspace is None:
+        workspace = torch.empty(espn_workspace_bytes(B, K), dtype=torch.uint8, device=q.device)
+    _check(lib().espn_rerank_prior(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
+                                   _dev(prior, torch.float32, "prior"), float(alpha), B, Q, K, k,
+                                   _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
+                                   _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_scores, workspace
+
+
+def espn_merge_topk(ids_a: torch.Tensor, scores_a: torch.Tensor, ids_b: torch.Tensor, scores_b: torch.Tensor, k: int,
+                    out_ids: torch.Tensor | None = None, out_scores: torch.Tensor | None = None, stream=None):
+    if ids_a.dim() != 2 or ids_b.dim() != 2 or ids_a.shape != scores_a.shape or ids_b.shape != scores_b.shape \
+            or ids_a.shape[0] != ids_b.shape[0]:
+        raise ValueError("expected ids/scores [B,ka] and [B,kb]")
+    B = ids_a.shape[0]
+    out_ids, out_scores = _outputs(B, k, ids_a.device, out_ids, out_scores)
+    _check(lib().espn_merge_topk(_dev(ids_a, torch.int64, "ids_a"), _dev(scores_a, torch.float32, "scores_a"),
+                                 ids_a.shape[1], _dev(ids_b, torch.int64, "ids_b"),
+                                 _dev(scores_b, torch.float32, "scores_b"), ids_b.shape[1], B, k,
+                                 _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
+                                 _stream_ptr(stream)))
+    return out_ids, out_scores
+
+
+def espn_batch_threshold(bandwidth_bytes_per_s: float, budget_s: float, bytes_per_query: float) -> float:
+    return float(lib().espn_batch_threshold(bandwidth_bytes_per_s, budget_s, bytes_per_query))

@@ -229,46 +229,50 @@ int docs_per_wave(int64_t pairs)
 }
 
 template <int D, int DOCS, int P>
-void launch_mfma_as(const espn::DocSource &src, unsigned *err, const void *q, const int64_t *cand, int B, int Q,
-                    int K, float *scores, hipStream_t st)
+void launch_mfma_as(const espn::DocSource &src, const espn::Batch &bt, int B, unsigned *err, float *scores,
+                    hipStream_t st)
 {
-    const int waves = (K + DOCS - 1) / DOCS;
+    const int waves = (bt.K + DOCS - 1) / DOCS;
     const dim3 grid((waves + 3) / 4, B), block(256);
-    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P>), grid, block, 0, st, src,
-                       static_cast<const uint16_t *>(q), cand, B, Q, K, scores, err);
+    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P>), grid, block, 0, st, src, bt, scores, err);
 }
 
 template <int D>
-void launch_mfma(const espn::DocSource &src, unsigned *err, const void *q, const int64_t *cand, int B, int Q, int K,
-                 float *scores, hipStream_t st)
+void launch_mfma(const espn::DocSource &src, const espn::Batch &bt, int B, unsigned *err, float *scores,
+                 hipStream_t st)
 {
     constexpr int P = (D == 32) ? 4 : 3;     // register pipeline depth in 16-row tiles
-    switch (docs_per_wave((int64_t)B * K)) {
-        case 32: launch_mfma_as<D, 32, P>(src, err, q, cand, B, Q, K, scores, st); break;
-        case 8: launch_mfma_as<D, 8, P>(src, err, q, cand, B, Q, K, scores, st); break;
-        default: launch_mfma_as<D, 4, P>(src, err, q, cand, B, Q, K, scores, st); break;
+    switch (docs_per_wave((int64_t)B * bt.K)) {
+        case 32: launch_mfma_as<D, 32, P>(src, bt, B, err, scores, st); break;
+        case 8: launch_mfma_as<D, 8, P>(src, bt, B, err, scores, st); break;
+        default: launch_mfma_as<D, 4, P>(src, bt, B, err, scores, st); break;
     }
 }
 
 // Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot).
-int enqueue_score(const espn_table *t, const espn::DocSource &src, const void *q, const int64_t *cand, int B, int Q,
-                  int K, float *scores, hipStream_t st)
+int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::Batch &bt, int B, float *scores,
+                  hipStream_t st)
 {
     using namespace espn;
-    if (B == 0 || K == 0) return ESPN_OK;
-    if ((t->dim == 32 || t->dim == 128) && Q <= 32) {
-        if (t->dim == 32) launch_mfma<32>(src, t->err_dev, q, cand, B, Q, K, scores, st);
-        else launch_mfma<128>(src, t->err_dev, q, cand, B, Q, K, scores, st);
+    if (B == 0 || bt.K == 0) return ESPN_OK;
+    if ((t->dim == 32 || t->dim == 128) && bt.Q <= 32) {
+        if (t->dim == 32) launch_mfma<32>(src, bt, B, t->err_dev, scores, st);
+        else launch_mfma<128>(src, bt, B, t->err_dev, scores, st);
     } else {
-        const size_t lds = (size_t)Q * t->dim * 2;
+        const size_t lds = (size_t)bt.Q * t->dim * 2;
         if (lds > 64 * 1024)
             return fail(ESPN_ERR_UNSUPPORTED, "Q * dim * 2 = %zu bytes exceeds the 64 KiB the generic kernel holds", lds);
-        const dim3 grid((K + 3) / 4, B), block(256);
-        hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim,
-                           static_cast<const uint16_t *>(q), cand, B, Q, K, scores, t->err_dev);
+        const dim3 grid((bt.K + 3) / 4, B), block(256);
+        hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim, bt, scores, t->err_dev);
     }
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
+}
+
+// A batch whose lists are scored whole, without a prior.
+espn::Batch plain_batch(const void *q, const int64_t *cand, int Q, int K)
+{
+    return espn::Batch{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, K};
 }
 
 espn::DocSource hbm_source(const espn_table *t)
@@ -276,19 +280,24 @@ espn::DocSource hbm_source(const espn_table *t)
     return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs};
 }
 
-int enqueue_topk(const float *scores, const int64_t *cand, int B, int K, int k, int64_t *out_ids, float *out_scores,
-                 hipStream_t st)
+// Ranks the first k of K scored candidates per query; cand rows have leading dimension ldc, output rows ldo.
+int enqueue_topk(const float *scores, const int64_t *cand, int ldc, int B, int K, int k, int ldo, int64_t *out_ids,
+                 float *out_scores, hipStream_t st)
 {
     using namespace espn;
     if (B == 0 || k == 0) return ESPN_OK;
     if (k <= 64 && K <= 64 * 16)
-        hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, K, k, out_ids, out_scores);
+        hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                           out_scores);
     else if (k <= 64 && K <= 64 * 32)
-        hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, K, k, out_ids, out_scores);
+        hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                           out_scores);
     else if (K <= 256 * 4)
-        hipLaunchKernelGGL((topk_rounds_kernel<4>), dim3(B), dim3(256), 0, st, scores, cand, K, k, out_ids, out_scores);
+        hipLaunchKernelGGL((topk_rounds_kernel<4>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                           out_scores);
     else
-        hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, K, k, out_ids, out_scores);
+        hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                           out_scores);
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }
@@ -304,7 +313,8 @@ ESPN_API int espn_score(espn_table *table, const void *q, const int64_t *cand, i
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     if (table->residency != ESPN_RESIDENT_HBM)
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
-    return enqueue_score(table, hbm_source(table), q, cand, B, Q, K, scores, static_cast<hipStream_t>(stream));
+    return enqueue_score(table, hbm_source(table), plain_batch(q, cand, Q, K), B, scores,
+                         static_cast<hipStream_t>(stream));
 }
 
 ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k, int64_t *out_ids,
@@ -313,7 +323,7 @@ ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int3
     if (B < 0 || K < 0 || k < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d, k = %d: negative size", B, K, k);
     if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
     if (B > 0 && k > 0 && (!scores || !cand || !out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "NULL pointer");
-    return enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, static_cast<hipStream_t>(stream));
+    return enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, static_cast<hipStream_t>(stream));
 }
 
 ESPN_API size_t espn_workspace_bytes(int32_t B, int32_t K)
@@ -354,8 +364,75 @@ ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, 
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *scores = static_cast<float *>(workspace);
-    if (int rc = enqueue_score(table, hbm_source(table), q, cand, B, Q, K, scores, st)) return rc;
-    return enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, st);
+    if (int rc = enqueue_score(table, hbm_source(table), plain_batch(q, cand, Q, K), B, scores, st)) return rc;
+    return enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st);
+}
+
+ESPN_API int espn_rerank_partial(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q,
+                                 int32_t K, int32_t R, int32_t k, int64_t *out_ids, float *out_scores,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if (R < 0 || R > K) return fail(ESPN_ERR_SHAPE, "R = %d outside [0, K = %d]", R, K);
+    if (int rc = check_rerank_outputs(B, R, std::min(k, R), out_ids, out_scores, workspace, workspace_bytes))
+        return rc;
+    if (k < 0) return fail(ESPN_ERR_ARG, "k = %d is negative", k);
+    if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
+    if (B > 0 && k > 0 && (!out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "output pointer is NULL");
+    if (table->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *scores = static_cast<float *>(workspace);
+    const espn::Batch bt{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, R};
+    if (int rc = enqueue_score(table, hbm_source(table), bt, B, scores, st)) return rc;
+    if (int rc = enqueue_topk(scores, cand, K, B, R, std::min(k, R), k, out_ids, out_scores, st)) return rc;
+    if (B > 0 && k > R) {
+        hipLaunchKernelGGL(espn::append_unranked_kernel, dim3((k - R + 255) / 256, B), dim3(256), 0, st, cand, K, R, k,
+                           out_ids, out_scores);
+        HIP_TRY(hipGetLastError());
+    }
+    return ESPN_OK;
+}
+
+ESPN_API int espn_rerank_prior(espn_table *table, const void *q, const int64_t *cand, const float *prior,
+                               float alpha, int32_t B, int32_t Q, int32_t K, int32_t k, int64_t *out_ids,
+                               float *out_scores, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if (int rc = check_rerank_outputs(B, K, k, out_ids, out_scores, workspace, workspace_bytes)) return rc;
+    if (B > 0 && K > 0 && !prior) return fail(ESPN_ERR_ARG, "prior is NULL");
+    if (table->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *scores = static_cast<float *>(workspace);
+    const espn::Batch bt{static_cast<const uint16_t *>(q), cand, prior, alpha, K, Q, K};
+    if (int rc = enqueue_score(table, hbm_source(table), bt, B, scores, st)) return rc;
+    return enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st);
+}
+
+ESPN_API int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_t ka, const int64_t *ids_b,
+                             const float *scores_b, int32_t kb, int32_t B, int32_t k, int64_t *out_ids,
+                             float *out_scores, void *stream)
+{
+    if (B < 0 || ka < 0 || kb < 0 || k < 0) return fail(ESPN_ERR_ARG, "negative size");
+    if ((int64_t)k > (int64_t)ka + kb) return fail(ESPN_ERR_SHAPE, "k = %d exceeds ka + kb = %d", k, ka + kb);
+    if (B == 0 || k == 0) return ESPN_OK;
+    if ((ka > 0 && (!ids_a || !scores_a)) || (kb > 0 && (!ids_b || !scores_b)) || !out_ids || !out_scores)
+        return fail(ESPN_ERR_ARG, "NULL pointer");
+    hipLaunchKernelGGL(espn::merge_topk_kernel, dim3(B), dim3(64), 0, static_cast<hipStream_t>(stream), ids_a,
+                       scores_a, ka, ids_b, scores_b, kb, k, out_ids, out_scores);
+    HIP_TRY(hipGetLastError());
+    return ESPN_OK;
+}
+
+ESPN_API double espn_batch_threshold(double bandwidth_bytes_per_s, double budget_s, double bytes_per_query)
+{
+    if (!(bytes_per_query > 0.0)) return 0.0;
+    return bandwidth_bytes_per_s * budget_s / bytes_per_query;
 }
 
 ESPN_API int espn_table_check(espn_table *table, void *stream)
@@ -469,8 +546,8 @@ ESPN_API int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, 
     HIP_TRY(hipStreamWaitEvent(st, s.ready, 0));
     const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs};
     float *scores = static_cast<float *>(workspace);
-    if (int rc = enqueue_score(table, src, q, cand, B, Q, K, scores, st)) return rc;
-    if (int rc = enqueue_topk(scores, cand, B, K, k, out_ids, out_scores, st)) return rc;
+    if (int rc = enqueue_score(table, src, plain_batch(q, cand, Q, K), B, scores, st)) return rc;
+    if (int rc = enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st)) return rc;
     HIP_TRY(hipEventRecord(s.consumed, st));
     return ESPN_OK;
 }

@@ -32,6 +32,25 @@ struct DocSource {
     int64_t n_docs;
 };
 
+// One batch of queries and their candidate lists.
+//   cand  [B, ldc] ids, of which the first K of every row are scored (ldc >= K: partial re-ranking
+//         scores a prefix of each list)
+//   prior [B, ldc] first-stage scores or nullptr; score = MaxSim + alpha * prior (Sec. 3.1)
+struct Batch {
+    const uint16_t *q;      // [B, Q, D]
+    const int64_t *cand;
+    const float *prior;
+    float alpha;
+    int ldc;
+    int Q;
+    int K;
+};
+
+__device__ __forceinline__ float with_prior(const Batch &bt, int b, int j, float maxsim)
+{
+    return bt.prior ? fmaf(bt.alpha, bt.prior[(size_t)b * bt.ldc + j], maxsim) : maxsim;
+}
+
 // (first row, row count) of document `id`; count 0 and an error flag if it cannot be read.
 __device__ __forceinline__ void locate_document(const DocSource &src, int64_t id, unsigned *err,
                                                 int64_t &row0, int &ntok)
@@ -171,10 +190,11 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D> &buf, const uint16_t 
 // Scores candidates j0 .. j0+DOCS-1 (j0 < K) of query b with the calling wave and stores them.
 template <int D, int DOCS, int P>
 __device__ __forceinline__ void maxsim_mfma_wave(
-    const DocSource &src, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
-    int b, int j0, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
+    const DocSource &src, const Batch &bt, int b, int j0, float *__restrict__ scores, unsigned *__restrict__ err)
 {
     const uint16_t *__restrict__ emb = src.emb;
+    const uint16_t *__restrict__ q = bt.q;
+    const int Q = bt.Q, K = bt.K;
     static_assert((D == 32 || D == 128) && DOCS >= 1 && DOCS <= 64 && P >= 1, "unsupported shape");
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     const int lane = threadIdx.x & 63;
@@ -184,7 +204,7 @@ __device__ __forceinline__ void maxsim_mfma_wave(
     // per-lane document descriptors: lane i describes candidate j0 + i
     int64_t row0 = 0;
     int ntok = 0;
-    if (lane < ndoc) locate_document(src, cand[(size_t)b * K + j0 + lane], err, row0, ntok);
+    if (lane < ndoc) locate_document(src, bt.cand[(size_t)b * bt.ldc + j0 + lane], err, row0, ntok);
 
     // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
     half8 qf[2][KS];
@@ -263,19 +283,18 @@ __device__ __forceinline__ void maxsim_mfma_wave(
             }
         }
     }
-    if (lane < ndoc) scores[(size_t)b * K + j0 + lane] = result;
+    if (lane < ndoc) scores[(size_t)b * K + j0 + lane] = with_prior(bt, b, j0 + lane, result);
 }
 
 // grid = (ceil(ceil(K / DOCS) / 4), B), 256 threads: wave w of workgroup x takes candidates
 // (4x + w) * DOCS .. of query blockIdx.y
 template <int D, int DOCS, int P>
 __global__ __launch_bounds__(256) void maxsim_mfma_kernel(
-    const DocSource src, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
-    int B, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
+    const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err)
 {
     const int j0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * DOCS;
-    if (j0 >= K) return;
-    maxsim_mfma_wave<D, DOCS, P>(src, q, cand, blockIdx.y, j0, Q, K, scores, err);
+    if (j0 >= bt.K) return;
+    maxsim_mfma_wave<D, DOCS, P>(src, bt, blockIdx.y, j0, scores, err);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -291,9 +310,10 @@ __device__ __forceinline__ void unpack8(const uint4 &u, float (&f)[8])
 }
 
 __global__ __launch_bounds__(256) void maxsim_generic_kernel(
-    const DocSource src, int D, const uint16_t *__restrict__ q, const int64_t *__restrict__ cand,
-    int B, int Q, int K, float *__restrict__ scores, unsigned *__restrict__ err)
+    const DocSource src, int D, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err)
 {
+    const uint16_t *__restrict__ q = bt.q;
+    const int Q = bt.Q, K = bt.K;
     extern __shared__ uint4 q_lds[];         // [Q][D/8] chunks of 8 binary16
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -311,7 +331,7 @@ __global__ __launch_bounds__(256) void maxsim_generic_kernel(
         // lane 0 looks the document up (and raises the flag once), the wave shares the result
         int64_t s0_lane = 0;
         int t_lane = 0;
-        if (lane == 0) locate_document(src, cand[(size_t)b * K + j], err, s0_lane, t_lane);
+        if (lane == 0) locate_document(src, bt.cand[(size_t)b * bt.ldc + j], err, s0_lane, t_lane);
         s0 = readlane64(s0_lane, 0);
         t = __builtin_amdgcn_readlane(t_lane, 0);
     }
@@ -350,7 +370,7 @@ __global__ __launch_bounds__(256) void maxsim_generic_kernel(
             if (i < nq) total += m;
         }
     }
-    if (lane == 0) scores[(size_t)b * K + j] = total;
+    if (lane == 0) scores[(size_t)b * K + j] = with_prior(bt, b, j, total);
 }
 
 }  // namespace espn

@@ -36,6 +36,10 @@ __device__ __forceinline__ Ranked shfl_xor_ranked(const Ranked &a, int mask)
     return o;
 }
 
+// Shapes common to the ranking kernels: scores [B, K] dense; cand rows have leading dimension ldc >= K
+// and output rows leading dimension ldo >= k (partial re-ranking ranks a prefix of each list into the
+// front of a longer output row).
+//
 // Selection in k rounds, one workgroup per query, any K and k <= K.  Round j picks the best
 // entry that ranks strictly after round j-1's winner; the order is total, so nothing has to be
 // marked as taken and the inputs are never modified.  PER entries per thread are cached in
@@ -43,14 +47,14 @@ __device__ __forceinline__ Ranked shfl_xor_ranked(const Ranked &a, int mask)
 // An entry whose score is NaN is never picked; rounds that find nothing write id -1, score NaN.
 template <int PER>
 __global__ __launch_bounds__(256) void topk_rounds_kernel(
-    const float *__restrict__ scores, const int64_t *__restrict__ cand, int K, int k,
+    const float *__restrict__ scores, const int64_t *__restrict__ cand, int ldc, int K, int k, int ldo,
     int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
 {
     __shared__ Ranked wave_best[4];
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sc = scores + (size_t)b * K;
-    const int64_t *ids = cand + (size_t)b * K;
+    const int64_t *ids = cand + (size_t)b * ldc;
 
     Ranked mine[PER];
 #pragma unroll
@@ -97,16 +101,16 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
             if (ranks_before(wave_best[w], best)) best = wave_best[w];
         __syncthreads();
         if (tid == 0) {
-            out_ids[(size_t)b * k + round] = best.slot >= 0 ? best.id : (int64_t)-1;
-            out_scores[(size_t)b * k + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+            out_ids[(size_t)b * ldo + round] = best.slot >= 0 ? best.id : (int64_t)-1;
+            out_scores[(size_t)b * ldo + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
         }
         prev = best;
         if (best.slot < 0) {
             // nothing left that can be ranked: fill the rest and stop
             if (tid == 0)
                 for (int rest = round + 1; rest < k; ++rest) {
-                    out_ids[(size_t)b * k + rest] = -1;
-                    out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+                    out_ids[(size_t)b * ldo + rest] = -1;
+                    out_scores[(size_t)b * ldo + rest] = __builtin_nanf("");
                 }
             break;
         }
@@ -287,13 +291,69 @@ __device__ __forceinline__ void topk_wave_body(
 
 template <int PER>
 __global__ __launch_bounds__(64) void topk_wave_kernel(
-    const float *__restrict__ scores, const int64_t *__restrict__ cand, int K, int k,
+    const float *__restrict__ scores, const int64_t *__restrict__ cand, int ldc, int K, int k, int ldo,
     int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
 {
     __shared__ TopkWaveLds<PER> lds;
     const int b = blockIdx.x;
-    topk_wave_body<PER>(scores + (size_t)b * K, cand + (size_t)b * K, K, k, out_ids + (size_t)b * k,
-                        out_scores + (size_t)b * k, (int)threadIdx.x, lds);
+    topk_wave_body<PER>(scores + (size_t)b * K, cand + (size_t)b * ldc, K, k, out_ids + (size_t)b * ldo,
+                        out_scores + (size_t)b * ldo, (int)threadIdx.x, lds);
+}
+
+// Partial re-ranking (Sec. 4.4): ranks R .. k-1 of every query are the candidates that were not
+// re-ranked, in the order the first stage listed them; they carry no MaxSim score (NaN).
+__global__ void append_unranked_kernel(const int64_t *__restrict__ cand, int ldc, int R, int k,
+                                       int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
+{
+    const int b = blockIdx.y;
+    const int j = R + blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < k) {
+        out_ids[(size_t)b * k + j] = cand[(size_t)b * ldc + j];
+        out_scores[(size_t)b * k + j] = __builtin_nanf("");
+    }
+}
+
+// Merge of two scored lists per query (Sec. 4.3: early re-ranked and later re-ranked documents are
+// combined by sorting on the score): the first k of their union in ranking order.  One wave per
+// query, k stateless selection rounds over the ka + kb entries (slot = position in a followed by b).
+__global__ __launch_bounds__(64) void merge_topk_kernel(
+    const int64_t *__restrict__ ids_a, const float *__restrict__ sc_a, int ka,
+    const int64_t *__restrict__ ids_b, const float *__restrict__ sc_b, int kb, int k,
+    int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
+{
+    const int b = blockIdx.x, lane = threadIdx.x, n = ka + kb;
+    Ranked prev;
+    prev.slot = -1;
+    for (int round = 0; round < k; ++round) {
+        Ranked best;
+        best.slot = -1; best.score = 0.f; best.id = 0;
+        for (int i = lane; i < n; i += 64) {
+            Ranked e;
+            e.slot = i;
+            e.score = i < ka ? sc_a[(size_t)b * ka + i] : sc_b[(size_t)b * kb + (i - ka)];
+            if (!(e.score == e.score)) continue;
+            e.id = i < ka ? ids_a[(size_t)b * ka + i] : ids_b[(size_t)b * kb + (i - ka)];
+            const bool after_prev = (round == 0) || ranks_before(prev, e);
+            if (after_prev && ranks_before(e, best)) best = e;
+        }
+#pragma unroll
+        for (int mask = 32; mask >= 1; mask >>= 1) {
+            const Ranked o = shfl_xor_ranked(best, mask);
+            if (ranks_before(o, best)) best = o;
+        }
+        if (lane == 0) {
+            out_ids[(size_t)b * k + round] = best.slot >= 0 ? best.id : (int64_t)-1;
+            out_scores[(size_t)b * k + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+        }
+        prev = best;
+        if (best.slot < 0) {
+            for (int rest = round + 1 + lane; rest < k; rest += 64) {
+                out_ids[(size_t)b * k + rest] = -1;
+                out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+            }
+            break;
+        }
+    }
 }
 
 }  // namespace espn
