@@ -21,8 +21,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, raw
-DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 6}
-DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3}
+DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 6, "c2p64": 400, "c3p64": 100}
+DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4}
 
 # HBM bytes per score-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
@@ -174,6 +174,47 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
                     "batch_over_transfer": ms_per_step / xfer_ms,
                     "logical_gb_per_batch": logical / 1e9, "pcie_gb_per_batch": pcie_bytes / 1e9},
     }
+    if args.sweep_batch:
+        # Eq. 4 with PCIe in the place of the SSD: the largest batch whose fetch fits a time budget.
+        # The prediction uses the measured PCIe rate and the mean bytes of a query's K documents (no
+        # sharing between queries, as in the paper); the measurement is the prefetch of the first b
+        # queries of batch 0, which benefits from documents shared between queries.
+        budget_s = args.budget_ms * 1e-3
+        per_query = float(np.mean([(2 * w.dim * counts[c]).sum() for c in cands_np])) / w.B
+        predicted = lib.espn_batch_threshold(achieved * 1e9, budget_s, per_query)
+        sweep = {}
+        b = 16
+        while b <= w.B:
+            part = cands[0][:b].contiguous()
+            t_ms = []
+            for rep in range(3):
+                e0.record(side_s)
+                rc = lib.espn_prefetch(h, part.data_ptr(), b, w.K, 0, st_side)
+                e1.record(side_s)
+                torch.cuda.synchronize()
+                if rc != 0:
+                    raise RuntimeError("espn_prefetch failed: " + espn.last_error())
+                t_ms.append(e0.elapsed_time(e1))
+            u = np.unique(cands_np[0][:b])
+            sweep[b] = {"transfer_ms": min(t_ms), "pcie_mb": float(counts[u].sum()) * w.dim * 2 / 1e6,
+                        "logical_mb": per_query * b / 1e6}
+            b *= 2
+        fits = [bb for bb, v in sweep.items() if v["transfer_ms"] <= args.budget_ms]
+        over = [bb for bb, v in sweep.items() if v["transfer_ms"] > args.budget_ms]
+        measured = None
+        if fits and over:                  # linear interpolation between the two batch sizes around the budget
+            lo, hi = max(fits), min(over)
+            t_lo, t_hi = sweep[lo]["transfer_ms"], sweep[hi]["transfer_ms"]
+            measured = lo + (hi - lo) * (args.budget_ms - t_lo) / (t_hi - t_lo)
+        result["batch_threshold"] = {"budget_ms": args.budget_ms, "bandwidth_gbs": achieved,
+                                     "bytes_per_query_mb": per_query / 1e6, "predicted_eq4": predicted,
+                                     "measured": measured, "sweep": sweep}
+        log("batch threshold for a %.0f ms budget: Eq. 4 predicts %.1f queries, measured %s" % (
+            args.budget_ms, predicted, "%.1f" % measured if measured else "outside the sweep"))
+        for bb, v in sweep.items():
+            log("  B=%4d: transfer %.2f ms, %.0f MB over PCIe (%.0f MB without sharing)" % (
+                bb, v["transfer_ms"], v["pcie_mb"], v["logical_mb"]))
+
     if not args.no_cpu_baseline:
         import oracle
         from tests.parity import assert_scores_close, assert_topk_matches
@@ -205,7 +246,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2p64", "c3p64"])
+    ap.add_argument("--sweep-batch", action="store_true",
+                    help="c5 only: also time the prefetch for smaller batches and compare the batch size at which "
+                         "it outgrows a time budget with Eq. 4's prediction")
+    ap.add_argument("--budget-ms", type=float, default=28.0, help="time budget for --sweep-batch")
     ap.add_argument("--host-docs", type=int, default=None,
                     help="c5 only: number of documents of the host-resident table (default 8.8 M = 156 GB pinned)")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
@@ -255,16 +300,19 @@ def main():
     qs = [synth.queries(w, seed, s, device=dev) for s in range(n_sets)]
     out_ids = [torch.empty((w.B, w.k), dtype=torch.int64, device=dev) for _ in range(n_sets)]
     out_sc = [torch.empty((w.B, w.k), dtype=torch.float32, device=dev) for _ in range(n_sets)]
-    ws_bytes = espn.espn_workspace_bytes(w.B, w.K)
+    R = w.rerank_top if w.rerank_top else w.K          # candidates per query that are actually scored
+    ws_bytes = espn.espn_workspace_bytes(w.B, R)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    scores_view = ws[: 4 * w.B * w.K].view(torch.float32).view(w.B, w.K)
-    log("inputs ready: %d sets of %d x %d candidates (%.1f s)" % (n_sets, w.B, w.K, time.time() - t_setup))
+    scores_view = ws[: 4 * w.B * R].view(torch.float32).view(w.B, R)
+    log("inputs ready: %d sets of %d x %d candidates, %d scored per query (%.1f s)" % (
+        n_sets, w.B, w.K, R, time.time() - t_setup))
 
-    # algorithmic bytes of one score-kernel launch: per pair the document's rows, its offset pair,
-    # its id and its score; per query its matrix once
-    pair_bytes = [float((2 * w.dim * counts[c]).sum()) + 28.0 * c.size for c in cands_np]
+    # algorithmic bytes of one score-kernel launch: per scored pair the document's rows, its offset
+    # pair, its id and its score; per query its matrix once
+    scored_np = [c[:, :R] for c in cands_np]
+    pair_bytes = [float((2 * w.dim * counts[c]).sum()) + 28.0 * c.size for c in scored_np]
     launch_bytes = float(np.mean(pair_bytes)) + w.B * w.Q * w.dim * 2
-    flops = float(np.mean([(2.0 * w.Q * w.dim * counts[c]).sum() for c in cands_np]))
+    flops = float(np.mean([(2.0 * w.Q * w.dim * counts[c]).sum() for c in scored_np]))
 
     stream = torch.cuda.current_stream()
     st = int(stream.cuda_stream)
@@ -272,20 +320,35 @@ def main():
 
     def rerank(i):
         s = i % n_sets
-        rc = lib.espn_rerank(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, w.k,
-                             out_ids[s].data_ptr(), out_sc[s].data_ptr(), ws.data_ptr(), ws_bytes, st)
+        if w.rerank_top:
+            rc = lib.espn_rerank_partial(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, R, w.k,
+                                         out_ids[s].data_ptr(), out_sc[s].data_ptr(), ws.data_ptr(), ws_bytes, st)
+        else:
+            rc = lib.espn_rerank(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, w.k,
+                                 out_ids[s].data_ptr(), out_sc[s].data_ptr(), ws.data_ptr(), ws_bytes, st)
         if rc != 0:
-            raise RuntimeError("espn_rerank failed: " + espn.last_error())
+            raise RuntimeError("re-rank failed: " + espn.last_error())
+
+    def score_only(i):
+        s = i % n_sets
+        if w.rerank_top:      # k = 0: the scoring kernel alone, on the first R candidates of every list
+            rc = lib.espn_rerank_partial(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, R, 0,
+                                         None, None, ws.data_ptr(), ws_bytes, st)
+        else:
+            rc = lib.espn_score(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, ws.data_ptr(), st)
+        if rc != 0:
+            raise RuntimeError("scoring failed: " + espn.last_error())
 
     def score_then_topk(i, ev0, ev1):
-        s = i % n_sets
         ev0.record(stream)
-        rc = lib.espn_score(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, ws.data_ptr(), st)
+        score_only(i)
         ev1.record(stream)
-        rc |= lib.espn_topk(ws.data_ptr(), cands[s].data_ptr(), w.B, w.K, w.k,
-                            out_ids[s].data_ptr(), out_sc[s].data_ptr(), st)
-        if rc != 0:
-            raise RuntimeError("espn_score/espn_topk failed: " + espn.last_error())
+        if not w.rerank_top:
+            s = i % n_sets
+            rc = lib.espn_topk(ws.data_ptr(), cands[s].data_ptr(), w.B, w.K, w.k,
+                               out_ids[s].data_ptr(), out_sc[s].data_ptr(), st)
+            if rc != 0:
+                raise RuntimeError("espn_topk failed: " + espn.last_error())
 
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -306,16 +369,10 @@ def main():
     wall = time.perf_counter() - t0
     espn.espn_table_check(table)
     ms_per_step = wall * 1e3 / steps
-    docs_per_s = w.B * w.K * steps / wall
+    docs_per_s = w.B * R * steps / wall            # documents actually MaxSim-scored
 
     # ---- the dominant (MaxSim) kernel on its own: `steps` launches back to back between one pair of
     # HIP events on the launch stream -> average duration of a launch (dispatch gap included)
-    def score_only(i):
-        s = i % n_sets
-        rc = lib.espn_score(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, ws.data_ptr(), st)
-        if rc != 0:
-            raise RuntimeError("espn_score failed: " + espn.last_error())
-
     for i in range(min(warmup, 3)):
         score_only(i)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -354,9 +411,10 @@ def main():
         "config": {
             "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": int(emb.shape[0]),
             "table_gb": emb.numel() * 2 / 1e9, "tokens_per_doc": "%s[%d,%d]" % (w.count_law, w.count_lo, w.count_hi),
-            "batch_queries": w.B, "query_tokens": w.Q, "candidates_per_query": w.K, "top_k": w.k,
-            "candidate_law": w.cand_law, "rotating_sets": n_sets, "accumulate": "f32", "seed": seed,
+            "batch_queries": w.B, "query_tokens": w.Q, "candidates_per_query": w.K, "scored_per_query": R,
+            "top_k": w.k, "candidate_law": w.cand_law, "rotating_sets": n_sets, "accumulate": "f32", "seed": seed,
         },
+        "queries_per_s": w.B * steps / wall,
         "wall_algorithmic_gbs": launch_bytes * steps / wall / 1e9,
         "wall_frac_of_hbm_peak": launch_bytes * steps / wall / 1e9 / HBM_PEAK_GBS,
         "roofline": {
@@ -374,17 +432,17 @@ def main():
         from tests.parity import assert_scores_close, assert_topk_matches
         # sample: whole batches 0..nb-1 (c1, c2) or the first nq queries of batch 0 (c3, c4), sized for
         # roughly 10-30 core-seconds of oracle work
-        nb = {"c1": min(16, n_sets), "c2": min(8, n_sets)}.get(args.workload, 1)
-        nq = w.B if args.workload in ("c1", "c2") else min(128, w.B)
+        nb = {"c1": min(16, n_sets), "c2": min(8, n_sets), "c2p64": min(8, n_sets)}.get(args.workload, 1)
+        nq = w.B if args.workload in ("c1", "c2", "c2p64") else min(128 * (w.K // R), w.B)
         if args.cpu_sample_queries is not None:
             nb, nq = 1, min(args.cpu_sample_queries, w.B)
         threads = oracle.max_threads()
         cpu_s, worst, pairs = 0.0, 0.0, 0
         for s in range(nb):
-            sub, loc_off, loc_cand, ids = synth.subtable(emb, off, cands_np[s][:nq])
+            sub, loc_off, loc_cand, ids = synth.subtable(emb, off, scored_np[s][:nq])
             q_np = qs[s][:nq].cpu().numpy()
             t1 = time.perf_counter()
-            o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k)
+            o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k)     # the scored prefix
             cpu_s += time.perf_counter() - t1
             # parity of the timed configuration on the same sample
             rerank(s)
@@ -393,8 +451,8 @@ def main():
             g_ids, g_top = out_ids[s][:nq].cpu().numpy(), out_sc[s][:nq].cpu().numpy()
             worst = max(worst, assert_scores_close(g_all, o_all, w.Q))
             for b in range(nq):
-                assert_topk_matches(g_ids[b], g_top[b], o_all[b], cands_np[s][b], w.k, w.Q)
-            pairs += nq * w.K
+                assert_topk_matches(g_ids[b], g_top[b], o_all[b], scored_np[s][b], w.k, w.Q)
+            pairs += nq * R
         result["cpu_baseline"] = {
             "value": pairs / cpu_s, "unit": "docs/s", "cores": threads, "kind": "oracle",
             "sample": "first %d queries of each of the first %d batches (%d pairs), fp64, %.1f s wall" % (

@@ -47,6 +47,7 @@ class Workload:
     zipf_alpha: float = 1.1
     host_resident: bool = False
     count_sigma: float = 0.5
+    rerank_top: int = 0     # > 0: partial re-ranking, only the first rerank_top candidates are scored
 
 
 WORKLOADS = {
@@ -61,6 +62,12 @@ WORKLOADS = {
     # table in pinned host memory, streamed over PCIe
     "c5": Workload("c5-host-d128", 8_800_000, 128, "lognormal", 8, 180, 70.0, 1024, 32, 1000, 10, "zipf",
                    host_resident=True),
+    # partial re-ranking (Sec. 4.4): only the 64 best-placed of the 1000 candidates are scored, so a
+    # batch of the same byte volume holds 16 times as many queries
+    "c2p64": Workload("c2-partial64-d32", 1_000_000, 32, "lognormal", 4, 128, 40.0, 1024, 32, 1000, 10, "uniform",
+                      rerank_top=64),
+    "c3p64": Workload("c3-partial64-d128", 2_000_000, 128, "lognormal", 8, 180, 70.0, 4096, 32, 1000, 10, "uniform",
+                      rerank_top=64),
 }
 
 
