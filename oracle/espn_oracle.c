@@ -191,7 +191,7 @@ int espn_oracle_rerank_partial(const uint16_t *emb, const int64_t *offsets, int6
                                int64_t *out_ids, double *out_scores, int32_t threads)
 {
     if (R < 0 || R > K || k < 0 || k > K) return -1;
-    int64_t *head = (int64_t *)malloc(sizeof(int64_t) * ((size_t)B * R + 1));
+    int64_t *head = (int64_t *)calloc((size_t)B * R + 1, sizeof(int64_t));
     int64_t *ids = (int64_t *)malloc(sizeof(int64_t) * ((size_t)B * R + 1));
     double *top = (double *)malloc(sizeof(double) * ((size_t)B * R + 1));
     if (!head || !ids || !top) { free(head); free(ids); free(top); return -1; }
