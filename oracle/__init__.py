@@ -58,6 +58,10 @@ def _load():
         lib.espn_oracle_merge.argtypes = [c_p, c_p, c_i32, c_p, c_p, c_i32, c_i32, c_i32, c_p, c_p]
         lib.espn_oracle_batch_threshold.restype = ctypes.c_double
         lib.espn_oracle_batch_threshold.argtypes = [ctypes.c_double] * 3
+        lib.espn_oracle_e4m3_to_double.restype = ctypes.c_double
+        lib.espn_oracle_e4m3_to_double.argtypes = [ctypes.c_uint8]
+        lib.espn_oracle_scores_e4m3.restype = ctypes.c_int
+        lib.espn_oracle_scores_e4m3.argtypes = [c_p, c_p, c_p, c_i64, c_i32, c_p, c_p, c_i32, c_i32, c_i32, c_p, c_i32]
         lib.espn_oracle_max_threads.restype = c_i32
         lib.espn_oracle_max_threads.argtypes = []
         _lib = lib
@@ -208,3 +212,33 @@ def merge(ids_a, sc_a, ids_b, sc_b, k: int):
 def batch_threshold(bandwidth_bytes_per_s: float, budget_s: float, bytes_per_query: float) -> float:
     """Eq. 4."""
     return float(_load().espn_oracle_batch_threshold(bandwidth_bytes_per_s, budget_s, bytes_per_query))
+
+
+def e4m3_to_double(code: int) -> float:
+    """Exact value of one E4M3 code (OCP 8-bit floating point)."""
+    return float(_load().espn_oracle_e4m3_to_double(int(code) & 0xFF))
+
+
+def scores_e4m3(codes, doc_scale, offsets, q, cand, threads: int = 0) -> np.ndarray:
+    """MaxSim scores on a compressed table: codes uint8 [T,d] (E4M3), one positive fp32 scale per document."""
+    cb = np.ascontiguousarray(np.asarray(codes))
+    if cb.dtype != np.uint8 or cb.ndim != 2:
+        raise TypeError("codes must be uint8 [T,d]")
+    qb = _f16_bits(q)
+    off = np.ascontiguousarray(np.asarray(offsets, dtype=np.int64))
+    cd = np.ascontiguousarray(np.asarray(cand, dtype=np.int64))
+    sc = np.ascontiguousarray(np.asarray(doc_scale, dtype=np.float32))
+    if qb.ndim != 3 or cd.ndim != 2 or qb.shape[2] != cb.shape[1] or cd.shape[0] != qb.shape[0]:
+        raise ValueError("shape mismatch")
+    if off[0] != 0 or off[-1] != cb.shape[0] or np.any(np.diff(off) < 0) or sc.shape != (off.shape[0] - 1,):
+        raise ValueError("offsets / scales do not describe the table")
+    if not (np.all(sc > 0) and np.all(np.isfinite(sc))):
+        raise ValueError("document scales must be positive and finite")
+    B, Q, d = qb.shape
+    K = cd.shape[1]
+    out = np.empty((B, K), dtype=np.float64)
+    rc = _load().espn_oracle_scores_e4m3(_ptr(cb), _ptr(sc), _ptr(off), off.shape[0] - 1, d, _ptr(qb), _ptr(cd),
+                                         B, Q, K, _ptr(out), threads)
+    if rc != 0:
+        raise ValueError("candidate id outside [0, n_docs)")
+    return out

@@ -253,6 +253,62 @@ double espn_oracle_batch_threshold(double bandwidth_bytes_per_s, double budget_s
     return bandwidth_bytes_per_s * budget_s / bytes_per_query;
 }
 
+/*
+ * Compressed table (Sec. 6: newer 8-bit formats shrink the re-ranking index, which lowers the data
+ * size per query of Eq. 4).  A token vector is stored as d codes of the 8-bit floating-point format
+ * E4M3 of the OCP 8-bit floating point specification (1 sign bit, 4 exponent bits with bias 7,
+ * 3 fraction bits; no infinities; S.1111.111 is NaN), and every document carries one positive
+ * scale: the stored vector is  scale[doc] * decode(code).
+ */
+double espn_oracle_e4m3_to_double(uint8_t c)
+{
+    int sign = (c >> 7) & 1;
+    int expo = (c >> 3) & 0xf;
+    int frac = c & 0x7;
+    double v;
+    if (expo == 15 && frac == 7) v = NAN;
+    else if (expo == 0) v = ldexp((double)frac, -9);          /* subnormal: frac/8 * 2^-6 */
+    else v = ldexp((double)(8 + frac), expo - 10);            /* (1 + frac/8) * 2^(expo-7) */
+    return sign ? -v : v;
+}
+
+/* Eq. 1 on a compressed table: same loops as espn_oracle_maxsim_pair on the decoded rows; the
+ * document's scale multiplies every one of its dot products. */
+int espn_oracle_scores_e4m3(const uint8_t *codes, const float *doc_scale, const int64_t *offsets,
+                            int64_t n_docs, int32_t d, const uint16_t *q, const int64_t *cand,
+                            int32_t B, int32_t Q, int32_t K, double *scores, int32_t threads)
+{
+    int bad = 0;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for collapse(2) schedule(dynamic, 16) reduction(| : bad)
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t kk = 0; kk < K; ++kk) {
+            int64_t id = cand[(int64_t)b * K + kk];
+            if (id < 0 || id >= n_docs) { bad |= 1; continue; }
+            int64_t s = offsets[id], e = offsets[id + 1];
+            double scale = (double)doc_scale[id];
+            double score = 0.0;
+            for (int32_t i = 0; i < Q; ++i) {
+                double best = -INFINITY;
+                for (int64_t j = s; j < e; ++j) {
+                    double dot = 0.0;
+                    for (int32_t c = 0; c < d; ++c)
+                        dot += espn_oracle_half_to_double(q[((int64_t)b * Q + i) * d + c]) *
+                               (scale * espn_oracle_e4m3_to_double(codes[j * d + c]));
+                    if (dot > best) best = dot;
+                }
+                score += best;
+            }
+            scores[(int64_t)b * K + kk] = score;
+        }
+    }
+    return bad ? -1 : 0;
+}
+
 /* Number of threads the parallel loop over queries will use (for reporting). */
 int32_t espn_oracle_max_threads(void)
 {

@@ -209,3 +209,30 @@ def subtable(emb: torch.Tensor, off: np.ndarray, cand: np.ndarray):
     idx = torch.from_numpy(rows).to(emb.device)
     sub = emb.index_select(0, idx).cpu().numpy() if total else np.zeros((0, emb.shape[1]), dtype=np.float16)
     return sub, loc_off, local.reshape(np.asarray(cand).shape).astype(np.int64), ids
+
+
+E4M3_MAX = 448.0
+
+
+def compress_e4m3(emb: torch.Tensor, off: np.ndarray):
+    """An 8-bit copy of a table: (codes uint8 [T,dim] in the OCP E4M3 format, scale float32 numpy [n_docs]).
+    Every document gets one scale = (largest magnitude in the document) / 448 (1 for an empty or all-zero
+    document); a stored value stands for scale * decode(code).  Rounding is torch's float8_e4m3fn
+    conversion (round to nearest even).  Works on the device the table lives on, chunk by chunk."""
+    n_docs = off.shape[0] - 1
+    dev = emb.device
+    counts = torch.from_numpy(np.diff(off)).to(dev)
+    doc_of_row = torch.repeat_interleave(torch.arange(n_docs, device=dev), counts)
+    amax = torch.zeros(n_docs, dtype=torch.float32, device=dev)
+    codes = torch.empty(emb.shape, dtype=torch.uint8, device=dev)
+    step = _ROWS_PER_CHUNK
+    for r0 in range(0, emb.shape[0], step):
+        r1 = min(emb.shape[0], r0 + step)
+        row_max = emb[r0:r1].float().abs().amax(dim=1)
+        amax.scatter_reduce_(0, doc_of_row[r0:r1], row_max, reduce="amax", include_self=True)
+    scale = torch.where(amax > 0, amax / E4M3_MAX, torch.ones_like(amax))
+    for r0 in range(0, emb.shape[0], step):
+        r1 = min(emb.shape[0], r0 + step)
+        x = emb[r0:r1].float() / scale[doc_of_row[r0:r1]].unsqueeze(1)
+        codes[r0:r1] = x.clamp_(-E4M3_MAX, E4M3_MAX).to(torch.float8_e4m3fn).view(torch.uint8)
+    return codes, scale.cpu().numpy()

@@ -439,3 +439,61 @@ def test_batch_threshold_follows_eq4_and_the_papers_own_scaling_statements():
     # 1000/64 and raises a limit of 12 to about the 192 the paper reports (187.5)
     limit = 12 * oracle.batch_threshold(1.0, 1.0, 64.0) / oracle.batch_threshold(1.0, 1.0, 1000.0)
     assert abs(limit - 192) / 192 < 0.03
+
+
+# ================================================================ compressed (E4M3) table
+def test_e4m3_decoding_matches_the_format_for_every_code():
+    import torch
+    want = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).double().numpy()   # torch's own decoder
+    got = np.array([oracle.e4m3_to_double(c) for c in range(256)])
+    nan = np.isnan(want)
+    assert nan.sum() == 2 and np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan]) and np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # values the format's definition fixes: 1.0, the largest finite number, the smallest subnormal and normal
+    assert oracle.e4m3_to_double(0x38) == 1.0 and oracle.e4m3_to_double(0x7E) == 448.0
+    assert oracle.e4m3_to_double(0x01) == 2.0 ** -9 and oracle.e4m3_to_double(0x08) == 2.0 ** -6
+    assert oracle.e4m3_to_double(0xB8) == -1.0 and oracle.e4m3_to_double(0x00) == 0.0
+
+
+def test_compressed_scores_reduce_to_the_plain_path_on_the_decoded_table():
+    # every E4M3 value is exactly a binary16 value, so scoring the codes with scale s must equal
+    # s times the (pinned) plain scores of the decoded table when s is a power of two
+    rng = np.random.default_rng(31)
+    counts = rng.integers(0, 6, size=30)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    codes = rng.integers(0, 256, size=(int(off[-1]), 8), dtype=np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x38                                  # no NaN codes
+    decoded = np.array([oracle.e4m3_to_double(c) for c in range(256)])[codes].astype(np.float16)
+    assert np.array_equal(decoded.astype(np.float64), np.array([oracle.e4m3_to_double(c) for c in range(256)])[codes])
+    q = (rng.integers(-8, 9, size=(2, 3, 8)) / 4).astype(np.float16)
+    cand = np.stack([rng.permutation(30)[:12] for _ in range(2)]).astype(np.int64)
+    scale = (2.0 ** rng.integers(-3, 4, size=30)).astype(np.float32)
+    got = oracle.scores_e4m3(codes, scale, off, q, cand)
+    plain = oracle.scores(decoded, off, q, cand)
+    want = plain * scale[cand]
+    assert np.array_equal(np.isneginf(got), np.isneginf(want))
+    fin = ~np.isneginf(want)
+    assert np.allclose(got[fin], want[fin], rtol=1e-13, atol=0)
+    # a general (not power-of-two) scale is still just a factor on the document's score
+    scale2 = (scale * 1.3).astype(np.float32)
+    got2 = oracle.scores_e4m3(codes, scale2, off, q, cand)
+    assert np.allclose(got2[fin], (plain * scale2[cand].astype(np.float64))[fin], rtol=1e-12, atol=0)
+    with pytest.raises(ValueError):
+        oracle.scores_e4m3(codes, -scale, off, q, cand)
+
+
+def test_compression_recipe_round_trips_within_the_format_s_precision():
+    import torch
+    from paper_2312_05417_amd import synth
+    w = synth.scaled(synth.WORKLOADS["c1"], n_docs=300)
+    emb, off = synth.table(w)
+    codes, scale = synth.compress_e4m3(emb, off)
+    assert codes.dtype == torch.uint8 and codes.shape == emb.shape and scale.shape == (300,) and np.all(scale > 0)
+    lut = np.array([oracle.e4m3_to_double(c) for c in range(256)])
+    assert not np.isnan(lut[codes.numpy()]).any()
+    back = lut[codes.numpy()] * np.repeat(scale.astype(np.float64), np.diff(off))[:, None]
+    err = np.abs(back - emb.double().numpy())
+    amax = np.repeat(scale.astype(np.float64) * 448, np.diff(off))[:, None]
+    # 3 fraction bits: relative step 2^-3, so rounding error <= 2^-4 of the value (or of the smallest normal / subnormal step)
+    assert np.all(err <= np.maximum(np.abs(emb.double().numpy()) * 2.0 ** -4, amax / 448 * 2.0 ** -10) * (1 + 1e-6))
+    assert np.abs(lut[codes.numpy()]).max() == 448.0                       # the largest entry of some document maps to the top code
