@@ -73,6 +73,23 @@ const char *espn_last_error(void);
 int espn_table_load(const void *emb, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
                     int32_t residency, int32_t device, espn_table **out);
 
+/*
+ * Register a compressed table (Sec. 6: 8-bit formats shrink the re-ranking index and with it the data
+ * moved per query).  A token vector is stored as `dim` one-byte codes in the E4M3 format of the OCP
+ * 8-bit floating point specification (no NaN codes allowed), and every document has one scale: a
+ * stored component stands for doc_scale[doc] * decode(code).  Every entry point that takes a table
+ * works on such a table; codes are widened exactly to binary16 inside the scoring kernel, products
+ * accumulate in binary32 as for binary16 tables, and the scale multiplies the document's score.
+ *
+ *   codes           [total_rows, dim] uint8, row-major, packed like `emb` of espn_table_load; DEVICE or
+ *                   pinned HOST pointer according to residency; BORROWED; 16-byte aligned.
+ *   doc_scale_host  [n_docs] binary32 HOST pointer, each positive and finite; COPIED.
+ *   dim             32 or 128 (ESPN_ERR_UNSUPPORTED otherwise); queries: 1..32 rows of binary16.
+ * Other arguments and errors as espn_table_load.
+ */
+int espn_table_load_e4m3(const void *codes, const float *doc_scale_host, const int64_t *offsets_host,
+                         int64_t n_docs, int32_t dim, int32_t residency, int32_t device, espn_table **out);
+
 /* Release a table handle (the offsets copy and the library's own buffers; never `emb`).
  * Synchronises the device first.  NULL is allowed. */
 int espn_table_free(espn_table *table);

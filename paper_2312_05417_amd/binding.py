@@ -26,6 +26,7 @@ SIGNATURES = {
     "espn_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "espn_last_error": (ctypes.c_char_p, []),
     "espn_table_load": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
+    "espn_table_load_e4m3": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
     "espn_table_free": (ctypes.c_int, [_c_p]),
     "espn_table_info": (ctypes.c_int, [_c_p, ctypes.POINTER(_c_i64), ctypes.POINTER(_c_i64),
                                        ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
@@ -100,10 +101,12 @@ def _dev(t: torch.Tensor, dtype, name: str) -> int:
 class Table:
     """Handle of a loaded table (espn_table_load / espn_table_free).  Keeps `emb` alive."""
 
-    def __init__(self, emb: torch.Tensor, offsets, dim: int | None = None, device: int | None = None):
+    def __init__(self, emb: torch.Tensor, offsets, dim: int | None = None, device: int | None = None,
+                 doc_scale=None):
         import numpy as np
-        if emb.dtype != torch.float16 or emb.dim() != 2 or not emb.is_contiguous():
-            raise TypeError("emb must be a contiguous [rows, dim] float16 tensor")
+        want = torch.float16 if doc_scale is None else torch.uint8
+        if emb.dtype != want or emb.dim() != 2 or not emb.is_contiguous():
+            raise TypeError("emb must be a contiguous [rows, dim] tensor of %s" % want)
         off = np.ascontiguousarray(np.asarray(offsets, dtype=np.int64))
         if off.ndim != 1 or off.shape[0] < 1:
             raise TypeError("offsets must be a 1-d int64 array of n_docs + 1 entries")
@@ -118,8 +121,15 @@ class Table:
         self.emb, self.n_docs, self.dim = emb, off.shape[0] - 1, emb.shape[1] if dim is None else dim
         self.device = dev
         self._h = _c_p()
-        _check(lib().espn_table_load(emb.data_ptr(), off.ctypes.data, self.n_docs, self.dim, residency, dev,
-                                     ctypes.byref(self._h)))
+        if doc_scale is None:
+            _check(lib().espn_table_load(emb.data_ptr(), off.ctypes.data, self.n_docs, self.dim, residency, dev,
+                                         ctypes.byref(self._h)))
+        else:
+            sc = np.ascontiguousarray(np.asarray(doc_scale, dtype=np.float32))
+            if sc.shape != (self.n_docs,):
+                raise ValueError("doc_scale must hold one value per document")
+            _check(lib().espn_table_load_e4m3(emb.data_ptr(), sc.ctypes.data, off.ctypes.data, self.n_docs, self.dim,
+                                              residency, dev, ctypes.byref(self._h)))
 
     def free(self) -> None:
         if self._h:
@@ -148,6 +158,10 @@ class Table:
 
 def espn_table_load(emb: torch.Tensor, offsets, device: int | None = None) -> Table:
     return Table(emb, offsets, device=device)
+
+
+def espn_table_load_e4m3(codes: torch.Tensor, doc_scale, offsets, device: int | None = None) -> Table:
+    return Table(codes, offsets, device=device, doc_scale=doc_scale)
 
 
 def espn_table_free(table: Table) -> None:

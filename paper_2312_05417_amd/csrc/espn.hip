@@ -63,7 +63,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // One HBM staging slot of a host-resident table (all device memory, owned by the table).
 struct StagingSlot {
-    uint16_t *rows = nullptr;              // [capacity_rows, dim]
+    void *rows = nullptr;                  // [capacity_rows, dim] in the table's row format
     int64_t *row_map = nullptr;            // [n_docs] first staged row of a document (valid if its bit is set)
     unsigned *bits = nullptr;              // [ceil(n_docs / 32)] documents held by the slot
     int64_t *uniq = nullptr;               // [capacity_docs] distinct documents of the batch
@@ -73,7 +73,9 @@ struct StagingSlot {
 };
 
 struct espn_table {
-    const uint16_t *emb = nullptr;   // borrowed; the device-visible address if the table is in host memory
+    const void *emb = nullptr;       // borrowed; the device-visible address if the table is in host memory
+    float *scale_dev = nullptr;      // owned, [n_docs] document scales of an E4M3 table, else nullptr
+    int32_t elem_bytes = 2;          // 2: binary16 rows, 1: E4M3 codes
     int64_t *off_dev = nullptr;      // owned, [n_docs + 1]
     unsigned *err_dev = nullptr;     // owned, one flag word
     int64_t n_docs = 0;
@@ -105,8 +107,32 @@ ESPN_API const char *espn_status_string(int status)
 
 ESPN_API const char *espn_last_error(void) { return g_err; }
 
+namespace {
+int load_table(const void *emb, const float *doc_scale_host, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
+               int32_t residency, int32_t device, espn_table **out);
+}
+
 ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
                              int32_t residency, int32_t device, espn_table **out)
+{
+    return load_table(emb, nullptr, offsets_host, n_docs, dim, residency, device, out);
+}
+
+ESPN_API int espn_table_load_e4m3(const void *codes, const float *doc_scale_host, const int64_t *offsets_host,
+                                  int64_t n_docs, int32_t dim, int32_t residency, int32_t device, espn_table **out)
+{
+    if (out) *out = nullptr;
+    if (!doc_scale_host) return fail(ESPN_ERR_ARG, "doc_scale_host is NULL");
+    if (dim != 32 && dim != 128) return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables need dim 32 or 128, got %d", dim);
+    for (int64_t i = 0; i < n_docs; ++i)
+        if (!(doc_scale_host[i] > 0.f) || !(doc_scale_host[i] < __builtin_inff()))
+            return fail(ESPN_ERR_ARG, "scale of document %lld is not positive and finite", (long long)i);
+    return load_table(codes, doc_scale_host, offsets_host, n_docs, dim, residency, device, out);
+}
+
+namespace {
+int load_table(const void *emb, const float *doc_scale_host, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
+               int32_t residency, int32_t device, espn_table **out)
 {
     if (!out) return fail(ESPN_ERR_ARG, "out is NULL");
     *out = nullptr;
@@ -130,7 +156,8 @@ ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", device);
     espn_table *t = new (std::nothrow) espn_table;
     if (!t) return fail(ESPN_ERR_NOMEM, "host allocation failed");
-    t->emb = static_cast<const uint16_t *>(emb);
+    t->emb = emb;
+    t->elem_bytes = doc_scale_host ? 1 : 2;
     if (residency == ESPN_RESIDENT_HOST_PINNED && total > 0) {
         void *dev_view = nullptr;
         hipError_t he = hipHostGetDevicePointer(&dev_view, const_cast<void *>(emb), 0);
@@ -140,7 +167,7 @@ ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64
             return fail(ESPN_ERR_ARG, "emb is not pinned host memory the device can address (%s)",
                         hipGetErrorString(he));
         }
-        t->emb = static_cast<const uint16_t *>(dev_view);
+        t->emb = dev_view;
     }
     t->n_docs = n_docs;
     t->total_rows = total;
@@ -152,10 +179,16 @@ ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&t->err_dev), kAlign);
     if (e == hipSuccess) e = hipMemcpy(t->off_dev, offsets_host, off_bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(t->err_dev, 0, kAlign);
+    if (e == hipSuccess && doc_scale_host) {
+        e = hipMalloc(reinterpret_cast<void **>(&t->scale_dev), sizeof(float) * (size_t)(n_docs + 1));
+        if (e == hipSuccess && n_docs > 0)
+            e = hipMemcpy(t->scale_dev, doc_scale_host, sizeof(float) * (size_t)n_docs, hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(t->off_dev);
         (void)hipFree(t->err_dev);
+        (void)hipFree(t->scale_dev);
         delete t;
         return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "table set-up failed: %s",
                     hipGetErrorString(e));
@@ -163,6 +196,7 @@ ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64
     *out = t;
     return ESPN_OK;
 }
+}  // namespace
 
 namespace {
 void free_staging(espn_table *t)
@@ -189,6 +223,7 @@ ESPN_API int espn_table_free(espn_table *table)
     free_staging(table);
     (void)hipFree(table->off_dev);
     (void)hipFree(table->err_dev);
+    (void)hipFree(table->scale_dev);
     delete table;
     return ESPN_OK;
 }
@@ -228,24 +263,25 @@ int docs_per_wave(int64_t pairs)
     return 4;
 }
 
-template <int D, int DOCS, int P>
+template <int D, int DOCS, int P, int EB>
 void launch_mfma_as(const espn::DocSource &src, const espn::Batch &bt, int B, unsigned *err, float *scores,
                     hipStream_t st)
 {
     const int waves = (bt.K + DOCS - 1) / DOCS;
     const dim3 grid((waves + 3) / 4, B), block(256);
-    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P>), grid, block, 0, st, src, bt, scores, err);
+    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P, EB>), grid, block, 0, st, src, bt, scores, err);
 }
 
-template <int D>
+// EB = bytes per stored component (2: binary16, 1: E4M3)
+template <int D, int EB>
 void launch_mfma(const espn::DocSource &src, const espn::Batch &bt, int B, unsigned *err, float *scores,
                  hipStream_t st)
 {
-    constexpr int P = (D == 32) ? 4 : 3;     // register pipeline depth in 16-row tiles
+    constexpr int P = (D == 32) ? 4 : (EB == 2 ? 3 : 4);     // register pipeline depth in 16-row tiles
     switch (docs_per_wave((int64_t)B * bt.K)) {
-        case 32: launch_mfma_as<D, 32, P>(src, bt, B, err, scores, st); break;
-        case 8: launch_mfma_as<D, 8, P>(src, bt, B, err, scores, st); break;
-        default: launch_mfma_as<D, 4, P>(src, bt, B, err, scores, st); break;
+        case 32: launch_mfma_as<D, 32, P, EB>(src, bt, B, err, scores, st); break;
+        case 8: launch_mfma_as<D, 8, P, EB>(src, bt, B, err, scores, st); break;
+        default: launch_mfma_as<D, 4, P, EB>(src, bt, B, err, scores, st); break;
     }
 }
 
@@ -255,9 +291,13 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
 {
     using namespace espn;
     if (B == 0 || bt.K == 0) return ESPN_OK;
-    if ((t->dim == 32 || t->dim == 128) && bt.Q <= 32) {
-        if (t->dim == 32) launch_mfma<32>(src, bt, B, t->err_dev, scores, st);
-        else launch_mfma<128>(src, bt, B, t->err_dev, scores, st);
+    if (t->elem_bytes == 1) {
+        if (bt.Q > 32) return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables take at most 32 query rows, got %d", bt.Q);
+        if (t->dim == 32) launch_mfma<32, 1>(src, bt, B, t->err_dev, scores, st);
+        else launch_mfma<128, 1>(src, bt, B, t->err_dev, scores, st);
+    } else if ((t->dim == 32 || t->dim == 128) && bt.Q <= 32) {
+        if (t->dim == 32) launch_mfma<32, 2>(src, bt, B, t->err_dev, scores, st);
+        else launch_mfma<128, 2>(src, bt, B, t->err_dev, scores, st);
     } else {
         const size_t lds = (size_t)bt.Q * t->dim * 2;
         if (lds > 64 * 1024)
@@ -277,7 +317,7 @@ espn::Batch plain_batch(const void *q, const int64_t *cand, int Q, int K)
 
 espn::DocSource hbm_source(const espn_table *t)
 {
-    return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs};
+    return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs, t->scale_dev};
 }
 
 // Ranks the first k of K scored candidates per query; cand rows have leading dimension ldc, output rows ldo.
@@ -470,7 +510,7 @@ ESPN_API int espn_staging_create(espn_table *table, int64_t capacity_rows, int64
     const size_t n_words = (size_t)(table->n_docs + 31) / 32 + 1;
     hipError_t e = hipSuccess;
     for (StagingSlot &s : table->slot) {
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.rows), (size_t)capacity_rows * table->dim * 2);
+        if (e == hipSuccess) e = hipMalloc(&s.rows, (size_t)capacity_rows * table->dim * table->elem_bytes);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.row_map), sizeof(int64_t) * (size_t)(table->n_docs + 1));
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.bits), sizeof(unsigned) * n_words);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.uniq), sizeof(int64_t) * (size_t)capacity_docs);
@@ -524,8 +564,9 @@ ESPN_API int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, in
                            n_pairs, table->off_dev, table->n_docs, s.bits, s.row_map, s.uniq, s.counters,
                            table->capacity_rows, table->capacity_docs, table->err_dev);
         // a modest grid: the copy is bound by PCIe, not by compute units, and shares the GPU with scoring
-        hipLaunchKernelGGL(espn::staging_gather_kernel, dim3(kGatherBlocks), dim3(256), 0, st, table->emb,
-                           table->off_dev, s.uniq, s.row_map, s.counters, table->capacity_docs, s.rows, table->dim);
+        hipLaunchKernelGGL(espn::staging_gather_kernel, dim3(kGatherBlocks), dim3(256), 0, st,
+                           static_cast<const uint4 *>(table->emb), table->off_dev, s.uniq, s.row_map, s.counters,
+                           table->capacity_docs, static_cast<uint4 *>(s.rows), table->dim * table->elem_bytes / 16);
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s.ready, st));
@@ -544,7 +585,7 @@ ESPN_API int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     StagingSlot &s = table->slot[slot];
     HIP_TRY(hipStreamWaitEvent(st, s.ready, 0));
-    const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs};
+    const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs, table->scale_dev};
     float *scores = static_cast<float *>(workspace);
     if (int rc = enqueue_score(table, src, plain_batch(q, cand, Q, K), B, scores, st)) return rc;
     if (int rc = enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st)) return rc;
@@ -564,7 +605,7 @@ ESPN_API int espn_staging_counters(espn_table *table, int32_t slot, void *stream
     HIP_TRY(hipStreamSynchronize(st));
     out4[0] = c[0];
     out4[1] = c[1];
-    out4[2] = c[1] * (uint64_t)table->dim * 2u;
+    out4[2] = c[1] * (uint64_t)table->dim * (uint64_t)table->elem_bytes;
     out4[3] = (uint64_t)table->capacity_rows;
     return ESPN_OK;
 }

@@ -6,7 +6,8 @@
 //   maxsim_mfma_kernel<D>   D in {32,128}: the Q x D x t contraction of each document runs on the
 //                           matrix cores (v_mfma_f32_16x16x32_f16); document rows stream from HBM
 //                           through a register pipeline into the MFMA A operand, the query sits
-//                           in VGPRs.
+//                           in VGPRs.  Rows are binary16, or E4M3 codes widened exactly to binary16
+//                           on the way into the MFMA.
 //   maxsim_generic_kernel   any D multiple of 8, any Q: plain FMA, one wave per document.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -24,12 +25,16 @@ constexpr unsigned ERR_NOT_STAGED = 4u;      // a staged re-rank met a document 
 // Where a document's rows are.  Table in HBM: rows off[id] .. off[id+1]-1 of `emb`.  Staged (table in
 // host memory, a prefetch copied this batch's documents into an HBM slot): `emb` is the slot, the
 // document's first row there is row_map[id], valid only if bit id of staged_bits is set.
+//
+// Rows are binary16 (2 bytes per component), or E4M3 codes (1 byte per component, OCP 8-bit floating
+// point) with one positive scale per document: a stored component stands for doc_scale[id] * decode(code).
 struct DocSource {
-    const uint16_t *emb;
+    const void *emb;
     const int64_t *off;
     const int64_t *row_map;        // nullptr: table in HBM
     const unsigned *staged_bits;
     int64_t n_docs;
+    const float *doc_scale;        // nullptr: binary16 rows
 };
 
 // One batch of queries and their candidate lists.
@@ -163,36 +168,70 @@ struct TileCursor {
     }
 };
 
-template <int D>
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+// Registers one lane holds of one 16-row tile: EB = bytes per component (2: binary16, 1: E4M3).
+template <int D, int EB>
 struct TileBuf {
-    uint4 v[D / 32];
+    static constexpr int NW = D / 32 * 2 * EB;     // dwords
+    unsigned w[NW];
 };
 
-template <int D>
-__device__ __forceinline__ void issue_tile_load(TileBuf<D> &buf, const uint16_t *__restrict__ emb,
+template <int D, int EB>
+__device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8_t *__restrict__ emb,
                                                 const TileCursor &cur, int lane)
 {
-    constexpr int KS = D / 32;
+    constexpr int ROW = D * EB;                    // bytes per row
     if constexpr (D == 32) {
-        // lane-linear: chunk `lane` of the 64 chunks of 16 rows x 64 B; past the end: the last valid chunk
-        const int nchunk = min(16, cur.t - cur.tile) * 4;
-        const uint4 *p = reinterpret_cast<const uint4 *>(emb + ((size_t)cur.row0 + cur.tile) * D);
-        buf.v[0] = p[min(lane, nchunk - 1)];
+        // lane-linear: piece `lane` of the 64 pieces of the 16-row tile (16 B each for binary16 rows,
+        // 8 B for E4M3 rows); past the document's end: the last valid piece
+        const int npiece = min(16, cur.t - cur.tile) * 4;
+        const uint8_t *p = emb + ((size_t)cur.row0 + cur.tile) * ROW;
+        const int piece = min(lane, npiece - 1);
+        if constexpr (EB == 2) {
+            const uint4 v = reinterpret_cast<const uint4 *>(p)[piece];
+            buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
+        } else {
+            const uint2 v = reinterpret_cast<const uint2 *>(p)[piece];
+            buf.w[0] = v.x; buf.w[1] = v.y;
+        }
     } else {
+        // lane (r, c) loads the c-th quarter of tile row r: 64 contiguous bytes (binary16) or 32 (E4M3)
         const int r = lane & 15, c = lane >> 4;
         const int row = min(cur.tile + r, cur.t - 1);
-        const uint4 *p = reinterpret_cast<const uint4 *>(emb + ((size_t)cur.row0 + row) * D) + KS * c;
+        const uint4 *p = reinterpret_cast<const uint4 *>(emb + ((size_t)cur.row0 + row) * ROW + c * (ROW / 4));
 #pragma unroll
-        for (int s = 0; s < KS; ++s) buf.v[s] = p[s];
+        for (int x = 0; x < TileBuf<D, EB>::NW / 4; ++x) {
+            const uint4 v = p[x];
+            buf.w[4 * x] = v.x; buf.w[4 * x + 1] = v.y; buf.w[4 * x + 2] = v.z; buf.w[4 * x + 3] = v.w;
+        }
+    }
+}
+
+// Eight consecutive components as binary16: two dwords of E4M3 codes are widened exactly
+// (v_cvt_scalef32_pk_f16_fp8 with scale 1), four dwords of binary16 are taken as they are.
+template <int EB>
+__device__ __forceinline__ half8 fragment_of(const unsigned *w)
+{
+    if constexpr (EB == 2) {
+        const uint4 v = {w[0], w[1], w[2], w[3]};
+        return __builtin_bit_cast(half8, v);
+    } else {
+        const half2v h01 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[0], 1.0f, false);
+        const half2v h23 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[0], 1.0f, true);
+        const half2v h45 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[1], 1.0f, false);
+        const half2v h67 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[1], 1.0f, true);
+        const half8 a = {h01[0], h01[1], h23[0], h23[1], h45[0], h45[1], h67[0], h67[1]};
+        return a;
     }
 }
 
 // Scores candidates j0 .. j0+DOCS-1 (j0 < K) of query b with the calling wave and stores them.
-template <int D, int DOCS, int P>
+template <int D, int DOCS, int P, int EB>
 __device__ __forceinline__ void maxsim_mfma_wave(
     const DocSource &src, const Batch &bt, int b, int j0, float *__restrict__ scores, unsigned *__restrict__ err)
 {
-    const uint16_t *__restrict__ emb = src.emb;
+    const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const uint16_t *__restrict__ q = bt.q;
     const int Q = bt.Q, K = bt.K;
     static_assert((D == 32 || D == 128) && DOCS >= 1 && DOCS <= 64 && P >= 1, "unsupported shape");
@@ -204,7 +243,12 @@ __device__ __forceinline__ void maxsim_mfma_wave(
     // per-lane document descriptors: lane i describes candidate j0 + i
     int64_t row0 = 0;
     int ntok = 0;
-    if (lane < ndoc) locate_document(src, bt.cand[(size_t)b * bt.ldc + j0 + lane], err, row0, ntok);
+    float doc_scale = 1.f;
+    if (lane < ndoc) {
+        const int64_t id = bt.cand[(size_t)b * bt.ldc + j0 + lane];
+        locate_document(src, id, err, row0, ntok);
+        if (EB == 1 && ntok > 0) doc_scale = src.doc_scale[id];
+    }
 
     // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
     half8 qf[2][KS];
@@ -229,10 +273,10 @@ __device__ __forceinline__ void maxsim_mfma_wave(
         ld.enter_next(ntok, row0);
         TileCursor cs = ld;
 
-        TileBuf<D> buf[P];
+        TileBuf<D, EB> buf[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            issue_tile_load<D>(buf[p], emb, ld, lane);
+            issue_tile_load<D, EB>(buf[p], emb, ld, lane);
             ld.advance(ntok, row0);
         }
 
@@ -243,18 +287,17 @@ __device__ __forceinline__ void maxsim_mfma_wave(
                 if (!cs.done) {
                     half8 a[KS];
                     if constexpr (D == 32) {
-                        // lane (r, c) takes chunk c of tile row min(r, rows-1) from lane 4*row + c
+                        // lane (r, c) takes piece c of tile row min(r, rows-1) from lane 4*row + c
                         const int rows = min(16, cs.t - cs.tile);
-                        const int src = (4 * min(r, rows - 1) + c) * 4;
-                        uint4 w;
-                        w.x = __builtin_amdgcn_ds_bpermute(src, buf[p].v[0].x);
-                        w.y = __builtin_amdgcn_ds_bpermute(src, buf[p].v[0].y);
-                        w.z = __builtin_amdgcn_ds_bpermute(src, buf[p].v[0].z);
-                        w.w = __builtin_amdgcn_ds_bpermute(src, buf[p].v[0].w);
-                        a[0] = __builtin_bit_cast(half8, w);
+                        const int from = (4 * min(r, rows - 1) + c) * 4;
+                        unsigned w[TileBuf<D, EB>::NW];
+#pragma unroll
+                        for (int x = 0; x < TileBuf<D, EB>::NW; ++x)
+                            w[x] = (unsigned)__builtin_amdgcn_ds_bpermute(from, (int)buf[p].w[x]);
+                        a[0] = fragment_of<EB>(w);
                     } else {
 #pragma unroll
-                        for (int s = 0; s < KS; ++s) a[s] = __builtin_bit_cast(half8, buf[p].v[s]);
+                        for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&buf[p].w[2 * EB * s]);
                     }
                     floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -278,23 +321,24 @@ __device__ __forceinline__ void maxsim_mfma_wave(
                     }
                     cs.advance(ntok, row0);
                 }
-                issue_tile_load<D>(buf[p], emb, ld, lane);
+                issue_tile_load<D, EB>(buf[p], emb, ld, lane);
                 ld.advance(ntok, row0);
             }
         }
     }
+    if (EB == 1) result *= doc_scale;        // one positive scale per document: max and sum commute with it
     if (lane < ndoc) scores[(size_t)b * K + j0 + lane] = with_prior(bt, b, j0 + lane, result);
 }
 
 // grid = (ceil(ceil(K / DOCS) / 4), B), 256 threads: wave w of workgroup x takes candidates
 // (4x + w) * DOCS .. of query blockIdx.y
-template <int D, int DOCS, int P>
+template <int D, int DOCS, int P, int EB>
 __global__ __launch_bounds__(256) void maxsim_mfma_kernel(
     const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err)
 {
     const int j0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * DOCS;
     if (j0 >= bt.K) return;
-    maxsim_mfma_wave<D, DOCS, P>(src, bt, blockIdx.y, j0, scores, err);
+    maxsim_mfma_wave<D, DOCS, P, EB>(src, bt, blockIdx.y, j0, scores, err);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -335,7 +379,7 @@ __global__ __launch_bounds__(256) void maxsim_generic_kernel(
         s0 = readlane64(s0_lane, 0);
         t = __builtin_amdgcn_readlane(t_lane, 0);
     }
-    const uint4 *rows = reinterpret_cast<const uint4 *>(src.emb + (size_t)s0 * D);
+    const uint4 *rows = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(src.emb) + (size_t)s0 * D);
 
     float total = 0.f;
     for (int i0 = 0; i0 < Q; i0 += 16) {

@@ -83,25 +83,24 @@ __global__ __launch_bounds__(256) void staging_mark_kernel(
     }
 }
 
-// D = row length in binary16 elements (multiple of 8).  host_emb is device-visible pinned host memory.
+// chunks_per_row = bytes of a row / 16.  host_emb is device-visible pinned host memory (or HBM).
 __global__ __launch_bounds__(256) void staging_gather_kernel(
-    const uint16_t *__restrict__ host_emb, const int64_t *__restrict__ off, const int64_t *__restrict__ uniq,
+    const uint4 *__restrict__ host_emb, const int64_t *__restrict__ off, const int64_t *__restrict__ uniq,
     const int64_t *__restrict__ row_map, const unsigned long long *__restrict__ counters, int64_t capacity_docs,
-    uint16_t *__restrict__ slot, int D)
+    uint4 *__restrict__ slot, int chunks_per_row)
 {
     const int lane = threadIdx.x & 63;
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int64_t n = min((int64_t)counters[0], capacity_docs);
-    const int chunks_per_row = D / 8;
     for (int64_t u = wave; u < n; u += n_waves) {
         const int64_t id = uniq[u];
         const int64_t r0 = row_map[id];
         if (r0 < 0) continue;
         const int64_t first = off[id];
         const int64_t n_chunks = (off[id + 1] - first) * chunks_per_row;
-        const uint4 *src = reinterpret_cast<const uint4 *>(host_emb + (size_t)first * D);
-        uint4 *dst = reinterpret_cast<uint4 *>(slot + (size_t)r0 * D);
+        const uint4 *src = host_emb + (size_t)first * chunks_per_row;
+        uint4 *dst = slot + (size_t)r0 * chunks_per_row;
         int64_t x = lane;
         for (; x + 7 * 64 < n_chunks; x += 8 * 64) {           // 8 KiB in flight per wave
             uint4 v[8];
