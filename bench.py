@@ -21,8 +21,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, raw
-DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 6, "c2p64": 400, "c3p64": 100}
-DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4}
+DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 6, "c2p64": 400, "c3p64": 100,
+                 "c2e4m3": 400, "c3e4m3": 100}
+DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4, "c2e4m3": 32, "c3e4m3": 8}
 
 # HBM bytes per score-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
@@ -246,13 +247,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2p64", "c3p64"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2p64", "c3p64", "c2e4m3", "c3e4m3"])
     ap.add_argument("--sweep-batch", action="store_true",
                     help="c5 only: also time the prefetch for smaller batches and compare the batch size at which "
                          "it outgrows a time budget with Eq. 4's prediction")
     ap.add_argument("--budget-ms", type=float, default=28.0, help="time budget for --sweep-batch")
     ap.add_argument("--host-docs", type=int, default=None,
                     help="c5 only: number of documents of the host-resident table (default 8.8 M = 156 GB pinned)")
+    ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -281,6 +283,8 @@ def main():
     lib = espn.lib()                       # fails loudly if the HIP library is not built
 
     w = synth.WORKLOADS[args.workload]
+    if args.batch is not None:
+        w = synth.scaled(w, B=args.batch, name="%s-B%d" % (w.name, args.batch))
     seed = synth.DEFAULT_SEED if args.seed is None else args.seed
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload]
     warmup = args.warmup if args.warmup is not None else max(3, steps // 10)
@@ -292,9 +296,16 @@ def main():
     t_setup = time.time()
     emb, off = synth.table(w, seed, device=dev)
     counts = np.diff(off)
-    table = espn.espn_table_load(emb, off)
+    elem_bytes, doc_scale = 2, None
+    if w.codec == "e4m3":
+        codes, doc_scale = synth.compress_e4m3(emb, off)
+        del emb
+        emb, elem_bytes = codes, 1
+        table = espn.espn_table_load_e4m3(emb, doc_scale, off)
+    else:
+        table = espn.espn_table_load(emb, off)
     log("%s: table %d docs, %d rows x %d, %.2f GB in HBM (%.1f s)" % (
-        w.name, w.n_docs, emb.shape[0], w.dim, emb.numel() * 2 / 1e9, time.time() - t_setup))
+        w.name, w.n_docs, emb.shape[0], w.dim, emb.numel() * elem_bytes / 1e9, time.time() - t_setup))
     cands_np = [synth.candidates(w, seed, s) for s in range(n_sets)]
     cands = [torch.from_numpy(c).to(dev) for c in cands_np]
     qs = [synth.queries(w, seed, s, device=dev) for s in range(n_sets)]
@@ -310,7 +321,8 @@ def main():
     # algorithmic bytes of one score-kernel launch: per scored pair the document's rows, its offset
     # pair, its id and its score; per query its matrix once
     scored_np = [c[:, :R] for c in cands_np]
-    pair_bytes = [float((2 * w.dim * counts[c]).sum()) + 28.0 * c.size for c in scored_np]
+    per_pair = 28.0 + (4.0 if elem_bytes == 1 else 0.0)             # + the document's scale
+    pair_bytes = [float((elem_bytes * w.dim * counts[c]).sum()) + per_pair * c.size for c in scored_np]
     launch_bytes = float(np.mean(pair_bytes)) + w.B * w.Q * w.dim * 2
     flops = float(np.mean([(2.0 * w.Q * w.dim * counts[c]).sum() for c in scored_np]))
 
@@ -410,7 +422,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": int(emb.shape[0]),
-            "table_gb": emb.numel() * 2 / 1e9, "tokens_per_doc": "%s[%d,%d]" % (w.count_law, w.count_lo, w.count_hi),
+            "table_gb": emb.numel() * elem_bytes / 1e9, "codec": w.codec, "tokens_per_doc": "%s[%d,%d]" % (w.count_law, w.count_lo, w.count_hi),
             "batch_queries": w.B, "query_tokens": w.Q, "candidates_per_query": w.K, "scored_per_query": R,
             "top_k": w.k, "candidate_law": w.cand_law, "rotating_sets": n_sets, "accumulate": "f32", "seed": seed,
         },
@@ -432,8 +444,11 @@ def main():
         from tests.parity import assert_scores_close, assert_topk_matches
         # sample: whole batches 0..nb-1 (c1, c2) or the first nq queries of batch 0 (c3, c4), sized for
         # roughly 10-30 core-seconds of oracle work
-        nb = {"c1": min(16, n_sets), "c2": min(8, n_sets), "c2p64": min(8, n_sets)}.get(args.workload, 1)
-        nq = w.B if args.workload in ("c1", "c2", "c2p64") else min(128 * (w.K // R), w.B)
+        nb = {"c1": min(16, n_sets), "c2": min(8, n_sets), "c2p64": min(8, n_sets),
+              "c2e4m3": min(4, n_sets)}.get(args.workload, 1)
+        nq = w.B if args.workload in ("c1", "c2", "c2p64", "c2e4m3") else min(128 * (w.K // R), w.B)
+        if w.codec == "e4m3" and args.workload != "c2e4m3":
+            nq = min(32, w.B)
         if args.cpu_sample_queries is not None:
             nb, nq = 1, min(args.cpu_sample_queries, w.B)
         threads = oracle.max_threads()
@@ -442,7 +457,11 @@ def main():
             sub, loc_off, loc_cand, ids = synth.subtable(emb, off, scored_np[s][:nq])
             q_np = qs[s][:nq].cpu().numpy()
             t1 = time.perf_counter()
-            o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k)     # the scored prefix
+            if w.codec == "e4m3":
+                o_all = oracle.scores_e4m3(sub, doc_scale[ids], loc_off, q_np, loc_cand)
+                o_ids, o_top = oracle.topk(o_all, loc_cand, w.k)
+            else:
+                o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k)     # the scored prefix
             cpu_s += time.perf_counter() - t1
             # parity of the timed configuration on the same sample
             rerank(s)

@@ -291,18 +291,28 @@ int espn_oracle_scores_e4m3(const uint8_t *codes, const float *doc_scale, const 
             if (id < 0 || id >= n_docs) { bad |= 1; continue; }
             int64_t s = offsets[id], e = offsets[id + 1];
             double scale = (double)doc_scale[id];
-            double score = 0.0;
-            for (int32_t i = 0; i < Q; ++i) {
-                double best = -INFINITY;
-                for (int64_t j = s; j < e; ++j) {
-                    double dot = 0.0;
-                    for (int32_t c = 0; c < d; ++c)
-                        dot += espn_oracle_half_to_double(q[((int64_t)b * Q + i) * d + c]) *
-                               (scale * espn_oracle_e4m3_to_double(codes[j * d + c]));
-                    if (dot > best) best = dot;
+            /* widen the query and the document once (exact decode, then the scale), then Eq. 1 as written */
+            double *qd = (double *)malloc(sizeof(double) * ((size_t)Q * d + 1));
+            double *dd = (double *)malloc(sizeof(double) * ((size_t)(e - s) * d + 1));
+            double score = NAN;
+            if (qd && dd) {
+                for (int64_t x = 0; x < (int64_t)Q * d; ++x)
+                    qd[x] = espn_oracle_half_to_double(q[(int64_t)b * Q * d + x]);
+                for (int64_t x = 0; x < (e - s) * d; ++x)
+                    dd[x] = scale * espn_oracle_e4m3_to_double(codes[s * d + x]);
+                score = 0.0;
+                for (int32_t i = 0; i < Q; ++i) {
+                    double best = -INFINITY;
+                    for (int64_t j = 0; j < e - s; ++j) {
+                        double dot = 0.0;
+                        for (int32_t c = 0; c < d; ++c) dot += qd[(int64_t)i * d + c] * dd[j * d + c];
+                        if (dot > best) best = dot;
+                    }
+                    score += best;
                 }
-                score += best;
             }
+            free(qd);
+            free(dd);
             scores[(int64_t)b * K + kk] = score;
         }
     }

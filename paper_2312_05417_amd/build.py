@@ -15,6 +15,11 @@ HIPCC_FLAGS = [
     "-fno-gpu-sanitize", "-Wall", "-Wextra", "-Wno-unused-parameter",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # device code only: inputs are finite by contract, so max() chains need no NaN quieting
+    # (v_max3_f32 instead of three v_max_f32 per operand pair); NaN tests in the kernels look at bits
+    "-Xarch_device", "-fno-honor-nans",
+    # MFMA results straight into VGPRs (no v_accvgpr_read before the VALU maximum)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

@@ -91,9 +91,24 @@ __device__ __forceinline__ int64_t readlane64(int64_t v, int lane)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-__device__ __forceinline__ float max4(const floatx4 &a)
+// max(a, b, c); becomes one v_max3_f32.  (Device code is built with -fno-honor-nans: without it the
+// compiler first quiets a possible signalling NaN in every operand, a v_max_f32 x, x, x each, which
+// triples the VALU work of the per-tile maximum.  The operands are MFMA results of finite inputs.)
+__device__ __forceinline__ float max3(float a, float b, float c)
 {
-    return fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3]));
+    return fmaxf(fmaxf(a, b), c);
+}
+
+// running maximum m updated with the four values of an accumulator
+__device__ __forceinline__ float max_into(float m, const floatx4 &a)
+{
+    return max3(max3(m, a[0], a[1]), a[2], a[3]);
+}
+
+// value of `v` in lane (lane ^ mask), through a precomputed byte address (4 * (lane ^ mask))
+__device__ __forceinline__ float from_lane(int addr, float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr, __builtin_bit_cast(int, v)));
 }
 
 // Sum over the 16 lanes of a DPP row; every lane of the row receives the total.
@@ -238,6 +253,7 @@ __device__ __forceinline__ void maxsim_mfma_wave(
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
+    const int xor16 = (lane ^ 16) * 4, xor32 = (lane ^ 32) * 4;     // ds_bpermute addresses
     const int ndoc = min(DOCS, K - j0);
 
     // per-lane document descriptors: lane i describes candidate j0 + i
@@ -305,14 +321,14 @@ __device__ __forceinline__ void maxsim_mfma_wave(
                         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[0][s], acc0, 0, 0, 0);
                         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[1][s], acc1, 0, 0, 0);
                     }
-                    m0 = fmaxf(m0, max4(acc0));
-                    m1 = fmaxf(m1, max4(acc1));
+                    m0 = max_into(m0, acc0);
+                    m1 = max_into(m1, acc1);
                     if (cs.last_tile()) {
                         // max over the four row groups (lanes l, l^16, l^32, l^48 hold the same query row)
-                        m0 = fmaxf(m0, __shfl_xor(m0, 16));
-                        m1 = fmaxf(m1, __shfl_xor(m1, 16));
-                        m0 = fmaxf(m0, __shfl_xor(m0, 32));
-                        m1 = fmaxf(m1, __shfl_xor(m1, 32));
+                        m0 = max3(m0, from_lane(xor16, m0), m0);
+                        m1 = max3(m1, from_lane(xor16, m1), m1);
+                        m0 = max3(m0, from_lane(xor32, m0), m0);
+                        m1 = max3(m1, from_lane(xor32, m1), m1);
                         // sum over the 32 query rows: rows r and r+16 in-lane, then across the 16 lanes
                         const float sum = row16_sum(m0 + m1);
                         if (lane == cs.doc) result = sum;

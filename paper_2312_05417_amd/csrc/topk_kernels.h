@@ -9,6 +9,16 @@
 
 namespace espn {
 
+// NaN test on the bit pattern (device code is built with -fno-honor-nans, which lets the compiler
+// fold x != x to false)
+__device__ __forceinline__ bool is_nan_bits(float x)
+{
+    return (__builtin_bit_cast(unsigned, x) & 0x7fffffffu) > 0x7f800000u;
+}
+
+// the "no score" marker, built from its bits for the same reason
+__device__ __forceinline__ float quiet_nan() { return __builtin_bit_cast(float, 0x7fc00000u); }
+
 struct Ranked {
     float score;
     int64_t id;
@@ -65,7 +75,7 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
         mine[x].id = 0;
         if (slot < K) {
             const float s = sc[slot];
-            if (s == s) { mine[x].score = s; mine[x].id = ids[slot]; mine[x].slot = slot; }
+            if (!is_nan_bits(s)) { mine[x].score = s; mine[x].id = ids[slot]; mine[x].slot = slot; }
         }
     }
 
@@ -82,7 +92,7 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
         for (int slot = tid + 256 * PER; slot < K; slot += 256) {
             Ranked e;
             e.score = sc[slot];
-            if (!(e.score == e.score)) continue;
+            if (is_nan_bits(e.score)) continue;
             e.id = ids[slot];
             e.slot = slot;
             const bool after_prev = (round == 0) || ranks_before(prev, e);
@@ -102,7 +112,7 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
         __syncthreads();
         if (tid == 0) {
             out_ids[(size_t)b * ldo + round] = best.slot >= 0 ? best.id : (int64_t)-1;
-            out_scores[(size_t)b * ldo + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+            out_scores[(size_t)b * ldo + round] = best.slot >= 0 ? best.score : quiet_nan();
         }
         prev = best;
         if (best.slot < 0) {
@@ -110,7 +120,7 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
             if (tid == 0)
                 for (int rest = round + 1; rest < k; ++rest) {
                     out_ids[(size_t)b * ldo + rest] = -1;
-                    out_scores[(size_t)b * ldo + rest] = __builtin_nanf("");
+                    out_scores[(size_t)b * ldo + rest] = quiet_nan();
                 }
             break;
         }
@@ -131,8 +141,9 @@ __global__ __launch_bounds__(256) void topk_rounds_kernel(
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ unsigned order_key(float s)
 {
-    if (!(s == s)) return 0u;
-    const unsigned u = __builtin_bit_cast(unsigned, s + 0.0f);   // -0 and +0 are the same score
+    const unsigned raw = __builtin_bit_cast(unsigned, s);
+    if (is_nan_bits(s)) return 0u;
+    const unsigned u = (raw << 1) == 0u ? 0u : raw;              // -0 and +0 are the same score
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
@@ -250,7 +261,7 @@ __device__ __forceinline__ void topk_wave_body(
         // fewer rankable entries than k (NaN scores): mark the rest
         for (int rest = total + lane; rest < k; rest += 64) {
             out_ids[rest] = -1;
-            out_scores[rest] = __builtin_nanf("");
+            out_scores[rest] = quiet_nan();
         }
         return;
     }
@@ -276,13 +287,13 @@ __device__ __forceinline__ void topk_wave_body(
         }
         if (lane == 0) {
             out_ids[round] = best.slot >= 0 ? best.id : (int64_t)-1;
-            out_scores[round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+            out_scores[round] = best.slot >= 0 ? best.score : quiet_nan();
         }
         prev = best;
         if (best.slot < 0) {
             for (int rest = round + 1 + lane; rest < k; rest += 64) {
                 out_ids[rest] = -1;
-                out_scores[rest] = __builtin_nanf("");
+                out_scores[rest] = quiet_nan();
             }
             break;
         }
@@ -309,7 +320,7 @@ __global__ void append_unranked_kernel(const int64_t *__restrict__ cand, int ldc
     const int j = R + blockIdx.x * blockDim.x + threadIdx.x;
     if (j < k) {
         out_ids[(size_t)b * k + j] = cand[(size_t)b * ldc + j];
-        out_scores[(size_t)b * k + j] = __builtin_nanf("");
+        out_scores[(size_t)b * k + j] = quiet_nan();
     }
 }
 
@@ -331,7 +342,7 @@ __global__ __launch_bounds__(64) void merge_topk_kernel(
             Ranked e;
             e.slot = i;
             e.score = i < ka ? sc_a[(size_t)b * ka + i] : sc_b[(size_t)b * kb + (i - ka)];
-            if (!(e.score == e.score)) continue;
+            if (is_nan_bits(e.score)) continue;
             e.id = i < ka ? ids_a[(size_t)b * ka + i] : ids_b[(size_t)b * kb + (i - ka)];
             const bool after_prev = (round == 0) || ranks_before(prev, e);
             if (after_prev && ranks_before(e, best)) best = e;
@@ -343,13 +354,13 @@ __global__ __launch_bounds__(64) void merge_topk_kernel(
         }
         if (lane == 0) {
             out_ids[(size_t)b * k + round] = best.slot >= 0 ? best.id : (int64_t)-1;
-            out_scores[(size_t)b * k + round] = best.slot >= 0 ? best.score : __builtin_nanf("");
+            out_scores[(size_t)b * k + round] = best.slot >= 0 ? best.score : quiet_nan();
         }
         prev = best;
         if (best.slot < 0) {
             for (int rest = round + 1 + lane; rest < k; rest += 64) {
                 out_ids[(size_t)b * k + rest] = -1;
-                out_scores[(size_t)b * k + rest] = __builtin_nanf("");
+                out_scores[(size_t)b * k + rest] = quiet_nan();
             }
             break;
         }

@@ -48,6 +48,7 @@ class Workload:
     host_resident: bool = False
     count_sigma: float = 0.5
     rerank_top: int = 0     # > 0: partial re-ranking, only the first rerank_top candidates are scored
+    codec: str = "f16"      # "f16": binary16 rows; "e4m3": 8-bit codes + one scale per document
 
 
 WORKLOADS = {
@@ -68,6 +69,11 @@ WORKLOADS = {
                       rerank_top=64),
     "c3p64": Workload("c3-partial64-d128", 2_000_000, 128, "lognormal", 8, 180, 70.0, 4096, 32, 1000, 10, "uniform",
                       rerank_top=64),
+    # the same tables compressed to 8 bits per component (Sec. 6)
+    "c2e4m3": Workload("c2-e4m3-d32", 1_000_000, 32, "lognormal", 4, 128, 40.0, 64, 32, 1000, 10, "uniform",
+                       codec="e4m3"),
+    "c3e4m3": Workload("c3-e4m3-d128", 2_000_000, 128, "lognormal", 8, 180, 70.0, 256, 32, 1000, 10, "uniform",
+                       codec="e4m3"),
 }
 
 
@@ -207,7 +213,7 @@ def subtable(emb: torch.Tensor, off: np.ndarray, cand: np.ndarray):
     start = np.repeat(off[ids] - loc_off[:-1], counts)
     rows = start + np.arange(total, dtype=np.int64)
     idx = torch.from_numpy(rows).to(emb.device)
-    sub = emb.index_select(0, idx).cpu().numpy() if total else np.zeros((0, emb.shape[1]), dtype=np.float16)
+    sub = emb.index_select(0, idx).cpu().numpy() if total else np.zeros((0, emb.shape[1]), dtype=np.float16 if emb.dtype == torch.float16 else np.uint8)
     return sub, loc_off, local.reshape(np.asarray(cand).shape).astype(np.int64), ids
 
 
