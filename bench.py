@@ -29,8 +29,10 @@ DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p
 # (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
 MEASURED_TRAFFIC_BYTES = {
     # (FETCH_SIZE KiB x 2.0 calibration + WRITE_SIZE KiB x 1.0) x 1024, MaxSim kernel, per launch
-    "c2": (86786.86 * 2.0 + 273.59) * 1024,       # profiles/maxsim_d32_c2_pmc.md
-    "c3": (2251394.18 * 2.0 + 1147.58) * 1024,    # profiles/maxsim_d128_c3_pmc.md
+    "c2": (86784.61 * 2.0 + 274.52) * 1024,          # profiles/maxsim_d32_c2_pmc.md
+    "c3": (2258221.04 * 2.0 + 1154.23) * 1024,       # profiles/maxsim_d128_c3_pmc.md
+    "c3e4m3": (1155091.85 * 2.0 + 1216.47) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
+    "c4": (17468853.39 * 2.0 + 8126.82) * 1024,      # profiles/maxsim_d128_c4_pmc.md
 }
 
 
