@@ -134,7 +134,8 @@ size_t espn_workspace_bytes(int32_t B, int32_t K);
 
 /*
  * The whole hot path for an HBM-resident table: gather + MaxSim + ranked top-k.
- * Same as espn_score into the workspace followed by espn_topk, both on `stream`.
+ * Same result as espn_score into the workspace followed by espn_topk, both on `stream`; short candidate
+ * lists are scored and ranked by one launch (espn_rerank_plan).
  *
  *   workspace        DEVICE, 256-byte aligned, at least espn_workspace_bytes(B, K) bytes; scratch
  *                    owned by the caller, contents undefined afterwards (it holds all B*K scores).
@@ -144,6 +145,16 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
                 int32_t B, int32_t Q, int32_t K, int32_t k,
                 int64_t *out_ids, float *out_scores,
                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * How espn_rerank (and its variants) would run a batch of this shape on this table: the candidate list
+ * of a query is cut into `slices` runs of `slice` candidates, one workgroup each; `launches` is 1 if the
+ * scoring kernel also ranks (one slice of at most 256 candidates per query), 2 if the stand-alone ranking kernel
+ * follows it, 0 for an empty batch.  Host arithmetic only; any out pointer may be NULL.
+ * For partial re-ranking pass K = R and k = min(k, R).  Errors: ARG, SHAPE.
+ */
+int espn_rerank_plan(const espn_table *table, int32_t B, int32_t Q, int32_t K, int32_t k,
+                     int32_t *slices, int32_t *slice, int32_t *launches);
 
 /*
  * Partial re-ranking (Sec. 4.4): the candidate list of a query arrives best-first from the first

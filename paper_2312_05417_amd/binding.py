@@ -33,6 +33,8 @@ SIGNATURES = {
     "espn_score": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p]),
     "espn_topk": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
     "espn_workspace_bytes": (_c_sz, [_c_i32, _c_i32]),
+    "espn_rerank_plan": (ctypes.c_int, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_i32),
+                                        ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
     "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "espn_rerank_partial": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
                                            _c_p, _c_sz, _c_p]),
@@ -90,6 +92,19 @@ def _stream_ptr(stream) -> int:
     if stream is None:
         stream = torch.cuda.current_stream()
     return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _workspace(B: int, K: int, device, stream) -> torch.Tensor:
+    """Scratch for one call.  It is handed back to torch's allocator as soon as the call returns, while
+    the kernels may still be running, so it has to be allocated in the order of the stream they run on:
+    a block released in stream order is only reused by work that stream runs later."""
+    nbytes = int(lib().espn_workspace_bytes(B, K))
+    if isinstance(stream, torch.cuda.Stream):
+        with torch.cuda.stream(stream):
+            return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    if stream is not None:
+        raise ValueError("pass a workspace along with a raw stream handle: torch cannot allocate in its order")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
 def _dev(t: torch.Tensor, dtype, name: str) -> int:
@@ -172,6 +187,14 @@ def espn_workspace_bytes(B: int, K: int) -> int:
     return int(lib().espn_workspace_bytes(B, K))
 
 
+def espn_rerank_plan(table: Table, B: int, Q: int, K: int, k: int) -> dict:
+    """How a batch of this shape would run: slices per query, candidates per slice, kernel launches."""
+    slices, slice_, launches = _c_i32(), _c_i32(), _c_i32()
+    _check(lib().espn_rerank_plan(table.handle, B, Q, K, k, ctypes.byref(slices), ctypes.byref(slice_),
+                                  ctypes.byref(launches)))
+    return {"slices": slices.value, "slice": slice_.value, "launches": launches.value}
+
+
 def _batch_shape(q: torch.Tensor, cand: torch.Tensor):
     if q.dim() != 3 or cand.dim() != 2 or q.shape[0] != cand.shape[0]:
         raise ValueError("expected q [B,Q,dim] and cand [B,K]")
@@ -218,7 +241,7 @@ def espn_rerank(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_i
     if out_scores is None:
         out_scores = torch.empty((B, max(k, 0)), dtype=torch.float32, device=q.device)
     if workspace is None:
-        workspace = torch.empty(espn_workspace_bytes(B, K), dtype=torch.uint8, device=q.device)
+        workspace = _workspace(B, K, q.device, stream)
     _check(lib().espn_rerank(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"), B, Q, K, k,
                              _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
@@ -253,7 +276,7 @@ def espn_rerank_staged(table: Table, slot: int, q: torch.Tensor, cand: torch.Ten
     if out_scores is None:
         out_scores = torch.empty((B, max(k, 0)), dtype=torch.float32, device=q.device)
     if workspace is None:
-        workspace = torch.empty(espn_workspace_bytes(B, K), dtype=torch.uint8, device=q.device)
+        workspace = _workspace(B, K, q.device, stream)
     _check(lib().espn_rerank_staged(table.handle, slot, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
                                     B, Q, K, k, _dev(out_ids, torch.int64, "out_ids"),
                                     _dev(out_scores, torch.float32, "out_scores"),
@@ -283,7 +306,7 @@ def espn_rerank_partial(table: Table, q: torch.Tensor, cand: torch.Tensor, R: in
         raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
     out_ids, out_scores = _outputs(B, k, q.device, out_ids, out_scores)
     if workspace is None:
-        workspace = torch.empty(espn_workspace_bytes(B, max(R, 0)), dtype=torch.uint8, device=q.device)
+        workspace = _workspace(B, max(R, 0), q.device, stream)
     _check(lib().espn_rerank_partial(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
                                      B, Q, K, R, k, _dev(out_ids, torch.int64, "out_ids"),
                                      _dev(out_scores, torch.float32, "out_scores"),
@@ -302,7 +325,7 @@ def espn_rerank_prior(table: Table, q: torch.Tensor, cand: torch.Tensor, prior: 
         raise ValueError("prior must be [B,K]")
     out_ids, out_scores = _outputs(B, k, q.device, out_ids, out_scores)
     if workspace is None:
-        workspace = torch.empty(espn_workspace_bytes(B, K), dtype=torch.uint8, device=q.device)
+        workspace = _workspace(B, K, q.device, stream)
     _check(lib().espn_rerank_prior(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
                                    _dev(prior, torch.float32, "prior"), float(alpha), B, Q, K, k,
                                    _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),

@@ -56,7 +56,6 @@ struct DeviceScope {
 constexpr size_t kAlign = 256;
 constexpr int kMaxGridY = 65535;
 constexpr unsigned kGatherBlocks = 256;   // workgroups of the host-to-HBM copy kernel
-
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -78,6 +77,7 @@ struct espn_table {
     int32_t elem_bytes = 2;          // 2: binary16 rows, 1: E4M3 codes
     int64_t *off_dev = nullptr;      // owned, [n_docs + 1]
     unsigned *err_dev = nullptr;     // owned, one flag word
+    int n_cu = 256;                  // compute units of the device
     int64_t n_docs = 0;
     int64_t total_rows = 0;
     int32_t dim = 0;
@@ -179,6 +179,11 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&t->err_dev), kAlign);
     if (e == hipSuccess) e = hipMemcpy(t->off_dev, offsets_host, off_bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(t->err_dev, 0, kAlign);
+    if (e == hipSuccess) {
+        int n_cu = 0;
+        e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device);
+        if (e == hipSuccess && n_cu > 0) t->n_cu = n_cu;
+    }
     if (e == hipSuccess && doc_scale_host) {
         e = hipMalloc(reinterpret_cast<void **>(&t->scale_dev), sizeof(float) * (size_t)(n_docs + 1));
         if (e == hipSuccess && n_docs > 0)
@@ -253,55 +258,72 @@ int check_batch(const espn_table *table, const void *q, const int64_t *cand, int
     return ESPN_OK;
 }
 
-// Documents per wave in the matrix-core kernel.  Small batches want many short waves (every wave is
-// resident at once and the kernel's tail is set by the longest wave); large batches can amortise the
-// per-wave set-up (descriptor look-up, query fragments) over more documents, which matters when
-// documents are short.  Measured on MI355X: 4 is best at 64 K pairs; beyond 256 K pairs 8..32 are equal
-// for documents of 2.5 KB and more, while 1.3 KB documents (E4M3, dim 32) gain 15 % from 32 over 8.
-int docs_per_wave(int64_t pairs, double mean_doc_bytes)
+// How a batch is cut into workgroup slices, and whether the scoring kernel ranks as well.
+struct SlicePlan {
+    int slice = 0;          // candidates per workgroup
+    int slices = 0;         // workgroups per query
+    bool rank = false;      // the scoring kernel writes the top-k itself
+};
+
+// Slices per query.  A launch small enough to be resident at once (two workgroups per compute unit)
+// is cut so that it fills the device exactly once: nothing is left to start late, and the waves of
+// a workgroup share its documents one by one, so all workgroups end together.  Larger launches use
+// slices of a fixed size that the dispatcher hands out as workgroups retire (measured on MI355X:
+// 125 candidates of 2.5 KB and 63 of 18 KB are the best sizes, +/- a factor 2 costs 1-2 %).
+// The kernel ranks as well when that leaves one slice of at most RANK_MAX candidates per query.
+SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
 {
-    if (pairs >= (int64_t)1 << 20) return 32;
-    if (pairs >= (int64_t)1 << 17) return (mean_doc_bytes < 2048.0 && pairs >= (int64_t)1 << 19) ? 32 : 8;
-    return 4;
+    const int waves = t->dim == 32 ? 16 : 8;
+    const int slots = 2 * t->n_cu;
+    const int one_round = (slots + B - 1) / B;
+    int slices;
+    if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, std::max(1, K / waves));
+    else slices = (K + (t->dim == 32 ? 125 : 63) - 1) / (t->dim == 32 ? 125 : 63);
+    slices = std::max(slices, (K + espn::MAX_SLICE - 1) / espn::MAX_SLICE);
+    SlicePlan p;
+    p.slice = (K + slices - 1) / slices;
+    p.slices = (K + p.slice - 1) / p.slice;
+    p.rank = p.slices == 1 && K <= espn::RANK_MAX && k >= 1;
+    return p;
 }
 
-template <int D, int DOCS, int P, int EB>
-void launch_mfma_as(const espn::DocSource &src, const espn::Batch &bt, int B, unsigned *err, float *scores,
-                    hipStream_t st)
+template <int D, int EB, bool RANK>
+void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
+                   float *scores, const espn::RankOut &ro, hipStream_t st)
 {
-    const int waves = (bt.K + DOCS - 1) / DOCS;
-    const dim3 grid((waves + 3) / 4, B), block(256);
-    hipLaunchKernelGGL((espn::maxsim_mfma_kernel<D, DOCS, P, EB>), grid, block, 0, st, src, bt, scores, err);
-}
-
-// EB = bytes per stored component (2: binary16, 1: E4M3)
-template <int D, int EB>
-void launch_mfma(const espn::DocSource &src, const espn::Batch &bt, int B, double mean_doc_bytes, unsigned *err,
-                 float *scores, hipStream_t st)
-{
+    constexpr int WAVES = D == 32 ? 16 : 8;
     constexpr int P = 4;                     // register pipeline depth in 16-row tiles
-    switch (docs_per_wave((int64_t)B * bt.K, mean_doc_bytes)) {
-        case 32: launch_mfma_as<D, 32, P, EB>(src, bt, B, err, scores, st); break;
-        case 8: launch_mfma_as<D, 8, P, EB>(src, bt, B, err, scores, st); break;
-        default: launch_mfma_as<D, 4, P, EB>(src, bt, B, err, scores, st); break;
-    }
+    hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK>), dim3(plan.slices, B), dim3(WAVES * 64), 0,
+                       st, src, bt, scores, err, plan.slice, ro);
 }
+
+template <int D, int EB>
+void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
+                   float *scores, const espn::RankOut &ro, hipStream_t st)
+{
+    if (plan.rank) launch_slices<D, EB, true>(src, bt, B, plan, err, scores, ro, st);
+    else launch_slices<D, EB, false>(src, bt, B, plan, err, scores, ro, st);
+}
+
+bool on_matrix_cores(const espn_table *t, int Q) { return (t->dim == 32 || t->dim == 128) && Q <= 32; }
 
 // Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot).
+// plan.rank: the kernel also writes the ranked top-k described by `ro`.
 int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::Batch &bt, int B, float *scores,
-                  hipStream_t st)
+                  const SlicePlan &plan, const espn::RankOut &ro, hipStream_t st)
 {
     using namespace espn;
     if (B == 0 || bt.K == 0) return ESPN_OK;
-    const double mean_doc_bytes =
-        t->n_docs > 0 ? (double)t->total_rows * t->dim * t->elem_bytes / (double)t->n_docs : 0.0;
-    if (t->elem_bytes == 1) {
-        if (bt.Q > 32) return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables take at most 32 query rows, got %d", bt.Q);
-        if (t->dim == 32) launch_mfma<32, 1>(src, bt, B, mean_doc_bytes, t->err_dev, scores, st);
-        else launch_mfma<128, 1>(src, bt, B, mean_doc_bytes, t->err_dev, scores, st);
-    } else if ((t->dim == 32 || t->dim == 128) && bt.Q <= 32) {
-        if (t->dim == 32) launch_mfma<32, 2>(src, bt, B, mean_doc_bytes, t->err_dev, scores, st);
-        else launch_mfma<128, 2>(src, bt, B, mean_doc_bytes, t->err_dev, scores, st);
+    if (t->elem_bytes == 1 && bt.Q > 32)
+        return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables take at most 32 query rows, got %d", bt.Q);
+    if (on_matrix_cores(t, bt.Q)) {
+        if (t->elem_bytes == 1) {
+            if (t->dim == 32) launch_slices<32, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);
+            else launch_slices<128, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);
+        } else {
+            if (t->dim == 32) launch_slices<32, 2>(src, bt, B, plan, t->err_dev, scores, ro, st);
+            else launch_slices<128, 2>(src, bt, B, plan, t->err_dev, scores, ro, st);
+        }
     } else {
         const size_t lds = (size_t)bt.Q * t->dim * 2;
         if (lds > 64 * 1024)
@@ -358,7 +380,7 @@ ESPN_API int espn_score(espn_table *table, const void *q, const int64_t *cand, i
     if (table->residency != ESPN_RESIDENT_HBM)
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
     return enqueue_score(table, hbm_source(table), plain_batch(q, cand, Q, K), B, scores,
-                         static_cast<hipStream_t>(stream));
+                         plan_slices(table, B, K, 0), espn::RankOut{}, static_cast<hipStream_t>(stream));
 }
 
 ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k, int64_t *out_ids,
@@ -396,6 +418,48 @@ int check_rerank_outputs(int32_t B, int32_t K, int32_t k, const int64_t *out_ids
 }
 }  // namespace
 
+namespace {
+
+// Score bt.K candidates per query into the workspace and write the first k of their ranking to
+// rows of leading dimension ldo: in one launch where the scoring kernel can rank, else in two.
+int enqueue_rerank(espn_table *t, const espn::DocSource &src, const espn::Batch &bt, int B, int k, int ldo,
+                   int64_t *out_ids, float *out_scores, void *workspace, hipStream_t st)
+{
+    if (B == 0 || bt.K == 0) return ESPN_OK;
+    float *scores = static_cast<float *>(workspace);
+    SlicePlan plan = plan_slices(t, B, bt.K, k);
+    if (!on_matrix_cores(t, bt.Q)) plan.rank = false;
+    const espn::RankOut ro{k, ldo, out_ids, out_scores};
+    if (int rc = enqueue_score(t, src, bt, B, scores, plan, ro, st)) return rc;
+    if (plan.rank) return ESPN_OK;
+    return enqueue_topk(scores, bt.cand, bt.ldc, B, bt.K, k, ldo, out_ids, out_scores, st);
+}
+
+}  // namespace
+
+ESPN_API int espn_rerank_plan(const espn_table *table, int32_t B, int32_t Q, int32_t K, int32_t k, int32_t *slices,
+                              int32_t *slice, int32_t *launches)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (B < 0 || K < 0 || k < 0 || Q < 1) return fail(ESPN_ERR_ARG, "B = %d, Q = %d, K = %d, k = %d", B, Q, K, k);
+    if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
+    SlicePlan plan;
+    int n = 0;
+    if (B > 0 && K > 0) {
+        if (on_matrix_cores(table, Q)) {
+            plan = plan_slices(table, B, K, k);
+        } else {
+            plan.slices = K;                 // the generic kernel: one wave per candidate, never ranks
+            plan.slice = 1;
+        }
+        n = 1 + ((k > 0 && !plan.rank) ? 1 : 0);
+    }
+    if (slices) *slices = plan.slices;
+    if (slice) *slice = plan.slice;
+    if (launches) *launches = n;
+    return ESPN_OK;
+}
+
 ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
                          int32_t k, int64_t *out_ids, float *out_scores, void *workspace, size_t workspace_bytes,
                          void *stream)
@@ -407,9 +471,8 @@ ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, 
     if (table->residency != ESPN_RESIDENT_HBM)
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float *scores = static_cast<float *>(workspace);
-    if (int rc = enqueue_score(table, hbm_source(table), plain_batch(q, cand, Q, K), B, scores, st)) return rc;
-    return enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st);
+    return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace,
+                          st);
 }
 
 ESPN_API int espn_rerank_partial(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q,
@@ -428,10 +491,9 @@ ESPN_API int espn_rerank_partial(espn_table *table, const void *q, const int64_t
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float *scores = static_cast<float *>(workspace);
     const espn::Batch bt{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, R};
-    if (int rc = enqueue_score(table, hbm_source(table), bt, B, scores, st)) return rc;
-    if (int rc = enqueue_topk(scores, cand, K, B, R, std::min(k, R), k, out_ids, out_scores, st)) return rc;
+    if (int rc = enqueue_rerank(table, hbm_source(table), bt, B, std::min(k, R), k, out_ids, out_scores, workspace, st))
+        return rc;
     if (B > 0 && k > R) {
         hipLaunchKernelGGL(espn::append_unranked_kernel, dim3((k - R + 255) / 256, B), dim3(256), 0, st, cand, K, R, k,
                            out_ids, out_scores);
@@ -452,10 +514,8 @@ ESPN_API int espn_rerank_prior(espn_table *table, const void *q, const int64_t *
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float *scores = static_cast<float *>(workspace);
     const espn::Batch bt{static_cast<const uint16_t *>(q), cand, prior, alpha, K, Q, K};
-    if (int rc = enqueue_score(table, hbm_source(table), bt, B, scores, st)) return rc;
-    return enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st);
+    return enqueue_rerank(table, hbm_source(table), bt, B, k, k, out_ids, out_scores, workspace, st);
 }
 
 ESPN_API int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_t ka, const int64_t *ids_b,
@@ -590,9 +650,8 @@ ESPN_API int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, 
     StagingSlot &s = table->slot[slot];
     HIP_TRY(hipStreamWaitEvent(st, s.ready, 0));
     const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs, table->scale_dev};
-    float *scores = static_cast<float *>(workspace);
-    if (int rc = enqueue_score(table, src, plain_batch(q, cand, Q, K), B, scores, st)) return rc;
-    if (int rc = enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, st)) return rc;
+    if (int rc = enqueue_rerank(table, src, plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace, st))
+        return rc;
     HIP_TRY(hipEventRecord(s.consumed, st));
     return ESPN_OK;
 }

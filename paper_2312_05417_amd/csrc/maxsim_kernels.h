@@ -3,15 +3,17 @@
 //   score[b,j] = sum_{i<Q} max_{r in doc(cand[b,j])} <q[b,i,:], emb[r,:]>
 //
 // Two kernels:
-//   maxsim_mfma_kernel<D>   D in {32,128}: the Q x D x t contraction of each document runs on the
+//   maxsim_slice_kernel<D>  D in {32,128}: the Q x D x t contraction of each document runs on the
 //                           matrix cores (v_mfma_f32_16x16x32_f16); document rows stream from HBM
 //                           through a register pipeline into the MFMA A operand, the query sits
 //                           in VGPRs.  Rows are binary16, or E4M3 codes widened exactly to binary16
-//                           on the way into the MFMA.
+//                           on the way into the MFMA.  Optionally ranks each query's top-k as well.
 //   maxsim_generic_kernel   any D multiple of 8, any Q: plain FMA, one wave per document.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "topk_kernels.h"
 
 namespace espn {
 
@@ -125,13 +127,13 @@ __device__ __forceinline__ float row16_sum(float v)
 // ---------------------------------------------------------------------------------------------
 // Matrix-core kernel.
 //
-// One wave scores DOCS consecutive candidates of one query.  v_mfma_f32_16x16x32_f16 computes a
-// 16x16 tile C[m][n] += sum_k A[m][k] B[k][n], k = 0..31; lane l supplies A[l%16][8*(l/16)..+7]
-// and B[8*(l/16)..+7][l%16] and receives C[4*(l/16)+v][l%16], v = 0..3.  Here m indexes 16
-// document rows (a "tile"), n indexes 16 query rows, so after the MFMA a lane holds the dot
-// products of ONE query row with FOUR document rows: the max over document rows is mostly an
-// in-lane v_max over accumulator registers carried across the tiles of a document, finished by two
-// cross-lane steps per document; the sum over query rows is one 16-lane DPP reduction per document.
+// v_mfma_f32_16x16x32_f16 computes a 16x16 tile C[m][n] += sum_k A[m][k] B[k][n], k = 0..31; lane l
+// supplies A[l%16][8*(l/16)..+7] and B[8*(l/16)..+7][l%16] and receives C[4*(l/16)+v][l%16],
+// v = 0..3.  Here m indexes 16 document rows (a "tile"), n indexes 16 query rows, so after the MFMA
+// a lane holds the dot products of ONE query row with FOUR document rows: the max over document
+// rows is mostly an in-lane v_max over accumulator registers carried across the tiles of a
+// document, finished by two cross-lane steps per document; the sum over query rows is one 16-lane
+// DPP reduction per document.
 //
 // The dot product does not care in which order the D components are visited as long as both
 // operands agree.  The k slots are assigned so that what a lane feeds to successive MFMA steps are
@@ -146,41 +148,42 @@ __device__ __forceinline__ float row16_sum(float v)
 //            4r + c to lane r + 16c.  Loading in the MFMA layout directly (16 B per lane at a 64 B
 //            stride) was measured ~30 % slower on the same gather.
 //
-// All tiles of the wave's documents form one sequence that is software-pipelined P deep through
-// registers: the load for tile u+P is issued right after tile u is consumed, across document
-// boundaries.  Loads are unconditional (an exhausted cursor re-reads its last tile) so that the
-// number of loads in flight is static and the waits the compiler inserts are exact.
+// Work split.  A workgroup of WAVES waves owns a SLICE of one query's candidate list (up to
+// MAX_SLICE consecutive candidates).  All its threads first look the slice's documents up
+// (candidate id -> offset pair) and leave the descriptors in LDS, so the two dependent memory
+// round trips are paid once per workgroup and not once per wave.  The waves then take documents
+// from the slice one at a time through an LDS counter, which keeps every wave busy until the slice
+// is exhausted however uneven the documents are.  The tiles of the documents a wave takes form one
+// sequence that is software-pipelined P deep through registers: the load for tile u+P is issued
+// right after tile u is consumed, across document boundaries.  Loads are unconditional (an
+// exhausted cursor re-reads its last tile) so that the number of loads in flight is static and the
+// waits the compiler inserts are exact.
 //
 // A partial last tile: rows beyond the document's end are replaced by its last row (D = 128: the
 // load address is clamped; D = 32: the bpermute source is clamped).  A duplicated row cannot change
 // a maximum, so no masking is needed.  Rows of the query beyond Q are zero vectors: they add
 // max(0,..,0) = 0 to the sum.
+//
+// Ranking (RANK = true; launches with one slice of at most RANK_MAX candidates per query, such as the
+// re-ranked prefix of partial re-ranking).  The workgroup also keeps its scores and ids in LDS and
+// ranks them when the slice is done: every wave takes some entries and counts, with one ballot per
+// 64 competitors, how many entries come before each; an entry whose count is below k writes itself
+// to that rank.  No second launch.  Longer lists are ranked by the stand-alone kernel: it spreads
+// the ranking of all queries over the whole device at once, which beats ranking at the tail of
+// each workgroup, and slices of one query cannot meet cheaply (an agent-scope release / acquire
+// pair per slice writes back and invalidates a whole L2 each: measured +25 % on the kernel).
 // ---------------------------------------------------------------------------------------------
+constexpr int MAX_SLICE = 1024;      // candidates per workgroup at most (LDS descriptor table)
+constexpr int RANK_MAX = 256;        // candidates per query at most for ranking inside the scoring kernel
 
-// Wave-uniform cursor over the tiles of the wave's non-empty documents.
-struct TileCursor {
-    uint64_t pending;   // documents not yet entered (bit i: candidate j0+i has rows)
-    int doc;            // lane index of the current document
+// Position of a wave in the sequence of tiles it streams (wave-uniform).
+struct DocCursor {
+    int64_t row0;       // first table row of the current document
     int t;              // its row count
     int tile;           // first row of the current tile (multiple of 16)
-    int64_t row0;       // its first table row
+    int idx;            // index of the current document in the slice
     bool done;          // moved past the last tile (position stays on the last tile)
-
-    __device__ __forceinline__ void enter_next(int ntok, int64_t row0_lane)
-    {
-        doc = __builtin_ctzll(pending);
-        pending &= pending - 1;
-        t = __builtin_amdgcn_readlane(ntok, doc);
-        row0 = readlane64(row0_lane, doc);
-        tile = 0;
-    }
     __device__ __forceinline__ bool last_tile() const { return tile + 16 >= t; }
-    __device__ __forceinline__ void advance(int ntok, int64_t row0_lane)
-    {
-        if (!last_tile()) tile += 16;
-        else if (pending) enter_next(ntok, row0_lane);
-        else done = true;
-    }
 };
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
@@ -194,7 +197,7 @@ struct TileBuf {
 
 template <int D, int EB>
 __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8_t *__restrict__ emb,
-                                                const TileCursor &cur, int lane)
+                                                const DocCursor &cur, int lane)
 {
     constexpr int ROW = D * EB;                    // bytes per row
     if constexpr (D == 32) {
@@ -241,59 +244,136 @@ __device__ __forceinline__ half8 fragment_of(const unsigned *w)
     }
 }
 
-// Scores candidates j0 .. j0+DOCS-1 (j0 < K) of query b with the calling wave and stores them.
-template <int D, int DOCS, int P, int EB>
-__device__ __forceinline__ void maxsim_mfma_wave(
-    const DocSource &src, const Batch &bt, int b, int j0, float *__restrict__ scores, unsigned *__restrict__ err)
+// Where a ranking kernel leaves its result (k = 0: no ranking).
+struct RankOut {
+    int k;                  // entries per query
+    int ldo;                // leading dimension of the output rows (>= k)
+    int64_t *out_ids;       // [B, ldo]
+    float *out_scores;      // [B, ldo]
+};
+
+// LDS a workgroup keeps for ranking its slice (nothing when it only scores)
+template <bool RANK>
+struct RankLds {
+    float score[RANK_MAX];
+    int64_t id[RANK_MAX];
+};
+template <>
+struct RankLds<false> {};
+
+// grid = (slices, B), WAVES * 64 threads: workgroup (x, b) takes candidates x * slice .. of query b
+template <int D, int WAVES, int P, int EB, bool RANK>
+__global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
+    const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err, int slice,
+    const RankOut ro)
 {
+    static_assert((D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 && P >= 1, "unsupported shape");
+    __shared__ int64_t s_row0[MAX_SLICE];
+    __shared__ int s_ntok[MAX_SLICE];
+    __shared__ float s_scale[EB == 1 ? MAX_SLICE : 1];
+    __shared__ int s_next;
+    __shared__ RankLds<RANK> s_rank;
+
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const uint16_t *__restrict__ q = bt.q;
     const int Q = bt.Q, K = bt.K;
-    static_assert((D == 32 || D == 128) && DOCS >= 1 && DOCS <= 64 && P >= 1, "unsupported shape");
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
     const int xor16 = (lane ^ 16) * 4, xor32 = (lane ^ 32) * 4;     // ds_bpermute addresses
-    const int ndoc = min(DOCS, K - j0);
+    const int b = blockIdx.y;
+    const int j_begin = blockIdx.x * slice;
+    const int n = min(slice, K - j_begin);  // >= 1 by construction of the grid
 
-    // per-lane document descriptors: lane i describes candidate j0 + i
-    int64_t row0 = 0;
-    int ntok = 0;
-    float doc_scale = 1.f;
-    if (lane < ndoc) {
-        const int64_t id = bt.cand[(size_t)b * bt.ldc + j0 + lane];
+    // descriptors of the slice's documents; a document with nothing to read has its score here
+    for (int i = threadIdx.x; i < n; i += WAVES * 64) {
+        const int64_t id = bt.cand[(size_t)b * bt.ldc + j_begin + i];
+        int64_t row0;
+        int ntok;
         locate_document(src, id, err, row0, ntok);
-        if (EB == 1 && ntok > 0) doc_scale = src.doc_scale[id];
+        s_row0[i] = row0;
+        s_ntok[i] = ntok;
+        if constexpr (EB == 1) s_scale[i] = ntok > 0 ? src.doc_scale[id] : 1.f;
+        if constexpr (RANK) s_rank.id[i] = id;
+        if (ntok == 0) {
+            const float none = with_prior(bt, b, j_begin + i, neg_inf());
+            scores[(size_t)b * K + j_begin + i] = none;
+            if constexpr (RANK) s_rank.score[i] = none;
+        }
     }
+    if (threadIdx.x == 0) s_next = 0;
 
     // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
     half8 qf[2][KS];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int n = r + 16 * h;
+        const int nq = r + 16 * h;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (n < Q)
-                v = *reinterpret_cast<const half8 *>(q + ((size_t)b * Q + n) * D + 8 * (KS * c + s));
+            if (nq < Q) v = *reinterpret_cast<const half8 *>(q + ((size_t)b * Q + nq) * D + 8 * (KS * c + s));
             qf[h][s] = v;
         }
     }
+    __syncthreads();
 
-    float result = neg_inf();                // lane i keeps the score of candidate j0 + i
-    const uint64_t nonempty = __ballot(ntok > 0);
-    if (nonempty) {
-        TileCursor ld;
-        ld.pending = nonempty;
-        ld.done = false;
-        ld.enter_next(ntok, row0);
-        TileCursor cs = ld;
+    // the next document of the slice that has rows, or -1 (wave-uniform)
+    auto grab = [&]() -> int {
+        while (true) {
+            int i = 0;
+            if (lane == 0) i = atomicAdd(&s_next, 1);
+            i = __builtin_amdgcn_readfirstlane(i);
+            if (i >= n) return -1;
+            if (__builtin_amdgcn_readfirstlane(s_ntok[i]) > 0) return i;
+        }
+    };
+    auto enter = [&](DocCursor &cur, int i) {
+        cur.idx = i;
+        cur.t = __builtin_amdgcn_readfirstlane(s_ntok[i]);
+        cur.row0 = readlane64(s_row0[i], 0);
+        cur.tile = 0;
+    };
+
+    // The load cursor runs P tiles ahead of the compute cursor; lane (s & 63) of `ring` remembers
+    // which document was the s-th one the wave took, for the compute cursor to follow.
+    int ring = 0, ld_seq = 0, cs_seq = 0;
+    DocCursor ld, cs;
+    ld.done = true;
+    {
+        const int i = grab();
+        if (i >= 0) {
+            enter(ld, i);
+            ld.done = false;
+            ring = i;
+            ld_seq = 1;
+        }
+    }
+    if (!ld.done) {
+        cs = ld;
+        cs_seq = 1;
+
+        auto ld_advance = [&]() {
+            if (ld.done) return;
+            if (!ld.last_tile()) { ld.tile += 16; return; }
+            const int i = grab();
+            if (i < 0) { ld.done = true; return; }
+            enter(ld, i);
+            if (lane == (ld_seq & 63)) ring = i;
+            ++ld_seq;
+        };
+        auto cs_advance = [&]() {
+            if (!cs.last_tile()) { cs.tile += 16; return; }
+            // the load cursor has left this document already: no further one means the end
+            if (cs_seq == ld_seq) { cs.done = true; return; }
+            enter(cs, __builtin_amdgcn_readlane(ring, cs_seq & 63));
+            ++cs_seq;
+        };
 
         TileBuf<D, EB> buf[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             issue_tile_load<D, EB>(buf[p], emb, ld, lane);
-            ld.advance(ntok, row0);
+            ld_advance();
         }
 
         float m0 = neg_inf(), m1 = neg_inf();
@@ -330,31 +410,91 @@ __device__ __forceinline__ void maxsim_mfma_wave(
                         m0 = max3(m0, from_lane(xor32, m0), m0);
                         m1 = max3(m1, from_lane(xor32, m1), m1);
                         // sum over the 32 query rows: rows r and r+16 in-lane, then across the 16 lanes
-                        const float sum = row16_sum(m0 + m1);
-                        if (lane == cs.doc) result = sum;
+                        float sum = row16_sum(m0 + m1);
+                        // one positive scale per document: max and sum commute with it
+                        if constexpr (EB == 1) sum *= s_scale[cs.idx];
+                        if (lane == 0) {
+                            const float total = with_prior(bt, b, j_begin + cs.idx, sum);
+                            scores[(size_t)b * K + j_begin + cs.idx] = total;
+                            if constexpr (RANK) s_rank.score[cs.idx] = total;
+                        }
                         m0 = neg_inf();
                         m1 = neg_inf();
                     }
-                    cs.advance(ntok, row0);
+                    cs_advance();
                 }
                 issue_tile_load<D, EB>(buf[p], emb, ld, lane);
-                ld.advance(ntok, row0);
+                ld_advance();
             }
         }
     }
-    if (EB == 1) result *= doc_scale;        // one positive scale per document: max and sum commute with it
-    if (lane < ndoc) scores[(size_t)b * K + j0 + lane] = with_prior(bt, b, j0 + lane, result);
-}
 
-// grid = (ceil(ceil(K / DOCS) / 4), B), 256 threads: wave w of workgroup x takes candidates
-// (4x + w) * DOCS .. of query blockIdx.y
-template <int D, int DOCS, int P, int EB>
-__global__ __launch_bounds__(256) void maxsim_mfma_kernel(
-    const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err)
-{
-    const int j0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * DOCS;
-    if (j0 >= bt.K) return;
-    maxsim_mfma_wave<D, DOCS, P, EB>(src, bt, blockIdx.y, j0, scores, err);
+    if constexpr (RANK) {
+        // gridDim.x == 1 and n <= RANK_MAX: the slice is the query's whole list.  Order: score
+        // descending, id ascending, position ascending; NaN scores (key 0) are never ranked.
+        __syncthreads();
+        constexpr int CH = RANK_MAX / 64;
+        unsigned key[CH];
+        int64_t idj[CH];
+        int rankable = 0;
+#pragma unroll
+        for (int x = 0; x < CH; ++x) {
+            const int j = x * 64 + lane;
+            key[x] = 0u;
+            idj[x] = 0;
+            if (x * 64 < n) {                // wave-uniform: chunks past the end cost nothing
+                if (j < n) {
+                    key[x] = order_key(s_rank.score[j]);
+                    idj[x] = s_rank.id[j];
+                }
+                rankable += __builtin_popcountll(__ballot(key[x] != 0u));
+            }
+        }
+        int64_t *oi = ro.out_ids + (size_t)b * ro.ldo;
+        float *os = ro.out_scores + (size_t)b * ro.ldo;
+        // wave w ranks entries w, w + WAVES, ... of every chunk; their keys and ids are already in
+        // registers (lane e % 64 of chunk e / 64).  The ids only matter among equal scores.
+#pragma unroll
+        for (int y = 0; y < CH; ++y) {
+            for (int l = threadIdx.x >> 6; l < 64 && y * 64 + l < n; l += WAVES) {
+                const int e = y * 64 + l;
+                const unsigned ke = (unsigned)__builtin_amdgcn_readlane((int)key[y], l);
+                if (ke == 0u) continue;
+                int rank = 0;
+                bool ties = false;
+#pragma unroll
+                for (int x = 0; x < CH; ++x) {
+                    if (x * 64 < n) {
+                        rank += __builtin_popcountll(__ballot(key[x] > ke));
+                        uint64_t equal = __ballot(key[x] == ke);
+                        if (x == y) equal &= ~(1ull << l);
+                        ties |= equal != 0;
+                    }
+                }
+                const int64_t ide = readlane64(idj[y], l);
+                if (ties) {
+#pragma unroll
+                    for (int x = 0; x < CH; ++x) {
+                        if (x * 64 < n) {
+                            const int j = x * 64 + lane;
+                            rank += __builtin_popcountll(
+                                __ballot(key[x] == ke && (idj[x] < ide || (idj[x] == ide && j < e))));
+                        }
+                    }
+                }
+                if (rank < ro.k && lane == 0) {
+                    oi[rank] = ide;
+                    os[rank] = key_to_score(ke);
+                }
+            }
+        }
+        // ranks nothing can fill
+        if (threadIdx.x < 64)
+            for (int rest = rankable + lane; rest < ro.k; rest += 64) {
+                oi[rest] = -1;
+                os[rest] = quiet_nan();
+            }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
