@@ -58,14 +58,15 @@ __device__ __forceinline__ float with_prior(const Batch &bt, int b, int j, float
     return bt.prior ? fmaf(bt.alpha, bt.prior[(size_t)b * bt.ldc + j], maxsim) : maxsim;
 }
 
-// (first row, row count) of document `id`; count 0 and an error flag if it cannot be read.
+// (first row, row count) of document `id`; count 0 and an error flag (if err is given) if it cannot
+// be read.
 __device__ __forceinline__ void locate_document(const DocSource &src, int64_t id, unsigned *err,
                                                 int64_t &row0, int &ntok)
 {
     row0 = 0;
     ntok = 0;
     if (id < 0 || id >= src.n_docs) {
-        atomicOr(err, ERR_ID_RANGE);
+        if (err) atomicOr(err, ERR_ID_RANGE);
         return;
     }
     const int64_t first = src.off[id];
@@ -77,7 +78,7 @@ __device__ __forceinline__ void locate_document(const DocSource &src, int64_t id
     }
     const int64_t staged = src.row_map[id];
     if (((src.staged_bits[id >> 5] >> (id & 31)) & 1u) == 0u || staged < 0) {
-        atomicOr(err, ERR_NOT_STAGED);
+        if (err) atomicOr(err, ERR_NOT_STAGED);
         return;
     }
     row0 = staged;
@@ -285,9 +286,36 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const int j_begin = blockIdx.x * slice;
     const int n = min(slice, K - j_begin);  // >= 1 by construction of the grid
 
+    // Wave w starts on the w-th document of the slice without waiting for anybody: it looks that
+    // document up itself and requests its first tile, so rows are on their way while the slice's
+    // descriptor table is still being filled (which ends with a barrier, i.e. with the slowest
+    // look-up of the workgroup).
+    const int wave = threadIdx.x >> 6;
+    const size_t cand0 = (size_t)b * bt.ldc + j_begin;
+    int64_t id_own = -1, id_fill = -1;
+    if (wave < n) id_own = bt.cand[cand0 + wave];
+    if ((int)threadIdx.x < n) id_fill = bt.cand[cand0 + threadIdx.x];
+    DocCursor ld, cs;
+    ld.done = true;
+    ld.idx = wave;
+    ld.tile = 0;
+    {
+        int64_t row0 = 0;
+        int ntok = 0;
+        if (wave < n) locate_document(src, id_own, nullptr, row0, ntok);   // flags are raised by the table fill
+        ld.t = __builtin_amdgcn_readfirstlane(ntok);
+        ld.row0 = readlane64(row0, 0);
+    }
+    const bool own_first = ld.t > 0;
+    TileBuf<D, EB> buf[P];
+    if (own_first) {
+        issue_tile_load<D, EB>(buf[0], emb, ld, lane);
+        ld.done = false;
+    }
+
     // descriptors of the slice's documents; a document with nothing to read has its score here
     for (int i = threadIdx.x; i < n; i += WAVES * 64) {
-        const int64_t id = bt.cand[(size_t)b * bt.ldc + j_begin + i];
+        const int64_t id = i == (int)threadIdx.x ? id_fill : bt.cand[cand0 + i];
         int64_t row0;
         int ntok;
         locate_document(src, id, err, row0, ntok);
@@ -301,7 +329,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
             if constexpr (RANK) s_rank.score[i] = none;
         }
     }
-    if (threadIdx.x == 0) s_next = 0;
+    if (threadIdx.x == 0) s_next = min(WAVES, n);      // the first WAVES documents are spoken for
 
     // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
     half8 qf[2][KS];
@@ -336,21 +364,19 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 
     // The load cursor runs P tiles ahead of the compute cursor; lane (s & 63) of `ring` remembers
     // which document was the s-th one the wave took, for the compute cursor to follow.
-    int ring = 0, ld_seq = 0, cs_seq = 0;
-    DocCursor ld, cs;
-    ld.done = true;
-    {
+    int ring = wave, ld_seq = 1, cs_seq = 1;
+    if (!own_first) {
+        // nothing of its own (an empty document, or fewer documents than waves): take one from the rest
         const int i = grab();
         if (i >= 0) {
             enter(ld, i);
             ld.done = false;
             ring = i;
-            ld_seq = 1;
+            issue_tile_load<D, EB>(buf[0], emb, ld, lane);
         }
     }
     if (!ld.done) {
         cs = ld;
-        cs_seq = 1;
 
         auto ld_advance = [&]() {
             if (ld.done) return;
@@ -369,9 +395,9 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
             ++cs_seq;
         };
 
-        TileBuf<D, EB> buf[P];
+        ld_advance();
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
+        for (int p = 1; p < P; ++p) {
             issue_tile_load<D, EB>(buf[p], emb, ld, lane);
             ld_advance();
         }
