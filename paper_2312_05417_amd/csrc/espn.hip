@@ -55,7 +55,11 @@ struct DeviceScope {
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxGridY = 65535;
-constexpr unsigned kGatherBlocks = 256;   // workgroups of the host-to-HBM copy kernel
+// Workgroups of the host-to-HBM copy kernel: 32 x 4 waves x 8 KiB = 1 MiB of reads in flight.  PCIe needs
+// about 64 GB/s x 5 us = 0.3 MiB to stay busy (measured: 8 workgroups reach 45 GB/s, 16 and more 56-57 GB/s),
+// and every host read that waits in the memory system's queues delays the HBM reads of the scoring kernel
+// running beside it (measured: with 256 workgroups a 2.7 ms scoring launch took 45 ms on average, with 32: 3.1 ms).
+constexpr unsigned kGatherBlocks = 32;
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -627,7 +631,6 @@ ESPN_API int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, in
         hipLaunchKernelGGL(espn::staging_mark_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, cand,
                            n_pairs, table->off_dev, table->n_docs, s.bits, s.row_map, s.uniq, s.counters,
                            table->capacity_rows, table->capacity_docs, table->err_dev);
-        // a modest grid: the copy is bound by PCIe, not by compute units, and shares the GPU with scoring
         hipLaunchKernelGGL(espn::staging_gather_kernel, dim3(kGatherBlocks), dim3(256), 0, st,
                            static_cast<const uint4 *>(table->emb), table->off_dev, s.uniq, s.row_map, s.counters,
                            table->capacity_docs, static_cast<uint4 *>(s.rows), table->dim * table->elem_bytes / 16);
