@@ -1,0 +1,97 @@
+"""Largest and oddest launch shapes of the scoring path, and what espn_rerank_plan says about them."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_05417_amd import binding as espn
+from tests.parity import assert_scores_close, assert_topk_matches
+from tests.test_gpu_parity import random_problem
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def test_largest_batch_and_one_beyond():
+    B, K, k = 65535, 3, 2
+    say("B = %d (the most queries one call takes), K = %d" % (B, K))
+    emb, off, q1, _ = random_problem(9, 500, 32, 1, 32, K, 1, 20)
+    rng = np.random.default_rng(4)
+    cand = rng.integers(0, 500, size=(B, K)).astype(np.int64)
+    # a few distinct queries, repeated: the expected scores of every query are then cheap to get
+    q_few = random_problem(10, 10, 32, 7, 32, 1, 1, 2)[2]
+    q = np.ascontiguousarray(q_few[np.arange(B) % 7])
+    emb_d, q_d, cand_d = torch.from_numpy(emb).to(DEV), torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
+    table = espn.espn_table_load(emb_d, off)
+    g_all = espn.espn_score(table, q_d, cand_d)
+    g_ids, g_sc = espn.espn_rerank(table, q_d, cand_d, k)
+    espn.espn_table_check(table)
+    sample = np.array([0, 1, 6, 7, 32767, 65533, 65534])
+    o_all = oracle.scores(emb, off, np.ascontiguousarray(q[sample]), np.ascontiguousarray(cand[sample]))
+    assert_scores_close(g_all[sample].cpu().numpy(), o_all, 32)
+    for n, b in enumerate(sample):
+        assert_topk_matches(g_ids[b].cpu().numpy(), g_sc[b].cpu().numpy(), o_all[n], cand[b], k, 32)
+    # every query against the two-launch path
+    t_ids, t_sc = espn.espn_topk(g_all, cand_d, k)
+    assert torch.equal(g_ids, t_ids) and torch.equal(g_sc.view(torch.int32), t_sc.view(torch.int32))
+    # one query more is refused before anything is launched
+    q_big = torch.zeros((B + 1, 32, 32), dtype=torch.float16, device=DEV)
+    c_big = torch.zeros((B + 1, K), dtype=torch.int64, device=DEV)
+    with pytest.raises(espn.EspnError) as err:
+        espn.espn_score(table, q_big, c_big)
+    assert err.value.status == espn.ESPN_ERR_UNSUPPORTED
+    table.free()
+
+
+@pytest.mark.parametrize("d", [32, 128])
+def test_one_query_with_a_very_long_list(d):
+    K, k = 70001, 25
+    say("B = 1, K = %d, d = %d: hundreds of slices of one query" % (K, d))
+    emb, off, q, _ = random_problem(3, 3000, d, 1, 32, 1, 1, 12)
+    cand = np.random.default_rng(8).integers(0, 3000, size=(1, K)).astype(np.int64)     # with repeats
+    emb_d, q_d, cand_d = torch.from_numpy(emb).to(DEV), torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
+    table = espn.espn_table_load(emb_d, off)
+    plan = espn.espn_rerank_plan(table, 1, 32, K, k)
+    assert plan["slices"] * plan["slice"] >= K > (plan["slices"] - 1) * plan["slice"] and plan["slice"] <= 1024
+    assert plan["launches"] == 2
+    g_all = espn.espn_score(table, q_d, cand_d).cpu().numpy()
+    g_ids, g_sc = espn.espn_rerank(table, q_d, cand_d, k)
+    espn.espn_table_check(table)
+    o_all = oracle.scores(emb, off, q, cand)
+    assert_scores_close(g_all, o_all, 32)
+    # 70 001 draws from 3000 documents: every score appears ~23 times, so the head is all exact ties
+    ids, sc = g_ids[0].cpu().numpy(), g_sc[0].cpu().numpy()
+    order = np.lexsort((cand[0], -g_all[0]))
+    assert np.array_equal(ids, cand[0][order[:k]]) and np.array_equal(sc, g_all[0][order[:k]])
+    table.free()
+
+
+def test_plan_of_typical_shapes():
+    say("espn_rerank_plan on the benchmark shapes")
+    emb = torch.zeros((64, 32), dtype=torch.float16, device=DEV)
+    t32 = espn.espn_table_load(emb, np.array([0, 64], dtype=np.int64))
+    emb128 = torch.zeros((64, 128), dtype=torch.float16, device=DEV)
+    t128 = espn.espn_table_load(emb128, np.array([0, 64], dtype=np.int64))
+    emb64 = torch.zeros((64, 64), dtype=torch.float16, device=DEV)
+    t64 = espn.espn_table_load(emb64, np.array([0, 64], dtype=np.int64))
+    for table, B, K, k in ((t32, 64, 1000, 10), (t32, 8, 100, 10), (t32, 1024, 64, 10), (t128, 256, 1000, 10),
+                           (t128, 2048, 1000, 10), (t128, 4096, 64, 10), (t32, 1, 1, 1), (t128, 3, 5000, 0)):
+        p = espn.espn_rerank_plan(table, B, 32, K, k)
+        assert 1 <= p["slice"] <= 1024 and p["slices"] * p["slice"] >= K > (p["slices"] - 1) * p["slice"], p
+        one_launch = p["slices"] == 1 and K <= 256 and k >= 1
+        assert p["launches"] == (1 if one_launch or k == 0 else 2), (B, K, k, p)
+    # a batch that fits the device at once is cut to fill it once: 64 queries x 8 slices = 512 workgroups
+    assert espn.espn_rerank_plan(t32, 64, 32, 1000, 10) == {"slices": 8, "slice": 125, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 1024, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
+    # shapes the matrix-core kernel does not take: one wave per candidate, a second launch ranks
+    assert espn.espn_rerank_plan(t64, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 5, 40, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 0, 32, 40, 3) == {"slices": 0, "slice": 0, "launches": 0}
+    with pytest.raises(espn.EspnError):
+        espn.espn_rerank_plan(t32, 4, 32, 10, 11)
+    for t in (t32, t128, t64):
+        t.free()
