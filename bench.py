@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, raw
-DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 6, "c2p64": 400, "c3p64": 100,
+DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 12, "c2p64": 400, "c3p64": 100,
                  "c2e4m3": 400, "c3e4m3": 100}
 DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4, "c2e4m3": 32, "c3e4m3": 8}
 
@@ -81,14 +81,15 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     uniq_rows = [int(counts[u].sum()) for u in uniq]
     cap_rows = int(max(uniq_rows) * 1.05) + 1024
     cap_docs = int(max(u.size for u in uniq) * 1.05) + 1024
-    espn.espn_staging_create(table, cap_rows, cap_docs)
+    n_slots = args.slots
+    espn.espn_staging_create_ring(table, n_slots, cap_rows, cap_docs)
     out_ids = [torch.empty((w.B, w.k), dtype=torch.int64, device=dev) for _ in range(n_sets)]
     out_sc = [torch.empty((w.B, w.k), dtype=torch.float32, device=dev) for _ in range(n_sets)]
     ws_bytes = espn.espn_workspace_bytes(w.B, w.K)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    log("inputs ready: %d sets; distinct docs per batch %.1f %%, %.2f GB over PCIe per batch, 2 slots x %.2f GB (%.1f s)" % (
+    log("inputs ready: %d sets; distinct docs per batch %.1f %%, %.2f GB per batch, %d slots x %.2f GB (%.1f s)" % (
         n_sets, 100.0 * np.mean([u.size for u in uniq]) / (w.B * w.K), np.mean(uniq_rows) * w.dim * 2 / 1e9,
-        cap_rows * w.dim * 2 / 1e9, time.time() - t_setup))
+        n_slots, cap_rows * w.dim * 2 / 1e9, time.time() - t_setup))
 
     # reference: a plain pinned-host -> device copy of 1 GiB
     ref_src = emb[: (1 << 30) // (w.dim * 2)]
@@ -107,13 +108,13 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
 
     def prefetch(n):
         s = n % n_sets
-        rc = lib.espn_prefetch(h, cands[s].data_ptr(), w.B, w.K, n % 2, st_side)
+        rc = lib.espn_prefetch(h, cands[s].data_ptr(), w.B, w.K, n % n_slots, st_side)
         if rc != 0:
             raise RuntimeError("espn_prefetch failed: " + espn.last_error())
 
     def rerank(n):
         s = n % n_sets
-        rc = lib.espn_rerank_staged(h, n % 2, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, w.k,
+        rc = lib.espn_rerank_staged(h, n % n_slots, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, w.k,
                                     out_ids[s].data_ptr(), out_sc[s].data_ptr(), ws.data_ptr(), ws_bytes, st_main)
         if rc != 0:
             raise RuntimeError("espn_rerank_staged failed: " + espn.last_error())
@@ -124,6 +125,10 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
             prefetch(n + 1)
             rerank(n)
 
+    # Batch numbers keep running through every leg below: batch n uses candidate set n % n_sets and slot
+    # n % n_slots, and with more sets than slots no slot ever holds the set that is being fetched.  The
+    # ring is warm (every slot filled once) before anything is timed.
+    warmup = max(warmup, n_slots)
     prefetch(0)
     pipeline(0, warmup)
     torch.cuda.synchronize()
@@ -133,27 +138,38 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     wall = time.perf_counter() - t0
     espn.espn_table_check(table)
     ms_per_step = wall * 1e3 / steps
+    nxt = warmup + steps + 1                # batches 0 .. warmup + steps have been prefetched
 
     # transfer alone and scoring alone, each timed with HIP events on its own stream
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(side_s)
-    for n in range(steps):
+    for n in range(nxt, nxt + steps):
         prefetch(n)
     e1.record(side_s)
     torch.cuda.synchronize()
     xfer_ms = e0.elapsed_time(e1) / steps
-    pcie_bytes = float(np.mean([uniq_rows[n % n_sets] for n in range(steps)])) * w.dim * 2
-    prefetch(0)
+    nxt += steps
+    # bytes that crossed PCIe, from the library's own counters: `steps` more prefetches, reading the
+    # counters after each (documents another slot already holds do not cross again)
+    crossed = []
+    for n in range(nxt, nxt + steps):
+        prefetch(n)
+        crossed.append(espn.espn_staging_counters(table, n % n_slots, side_s)["pcie_bytes"])
+    pcie_bytes = float(np.mean(crossed))
+    distinct_bytes = float(np.mean([uniq_rows[n % n_sets] for n in range(nxt, nxt + steps)])) * w.dim * 2
+    nxt += steps
+    last = nxt - 1                          # the batch its slot still holds
     torch.cuda.synchronize()
     e0.record(main_s)
     for _ in range(steps):
-        rerank(0)
+        rerank(last)
     e1.record(main_s)
     torch.cuda.synchronize()
     score_ms = e0.elapsed_time(e1) / steps
     achieved = pcie_bytes / (xfer_ms * 1e-3) / 1e9
-    log("wall %.2f ms/batch; prefetch alone %.2f ms (%.1f GB/s over PCIe; plain 1 GiB memcpy %.1f GB/s); "
-        "scoring alone %.2f ms" % (ms_per_step, xfer_ms, achieved, memcpy_gbs, score_ms))
+    log("wall %.2f ms/batch; prefetch alone %.2f ms (%.2f GB over PCIe of %.2f GB distinct: %.1f GB/s; plain 1 GiB "
+        "memcpy %.1f GB/s); scoring alone %.2f ms" % (ms_per_step, xfer_ms, pcie_bytes / 1e9, distinct_bytes / 1e9,
+                                                      achieved, memcpy_gbs, score_ms))
 
     logical = float(np.mean([(2 * w.dim * counts[c]).sum() for c in cands_np]))
     result = {
@@ -164,7 +180,8 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
             "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": rows, "table_gb": rows * w.dim * 2 / 1e9,
             "residency": "pinned host memory", "batch_queries": w.B, "query_tokens": w.Q,
             "candidates_per_query": w.K, "top_k": w.k, "candidate_law": "zipf(%.1f)" % w.zipf_alpha,
-            "rotating_sets": n_sets, "distinct_docs_per_batch": float(np.mean([u.size for u in uniq])),
+            "rotating_sets": n_sets, "staging_slots": n_slots,
+            "distinct_docs_per_batch": float(np.mean([u.size for u in uniq])),
             "accumulate": "f32", "seed": seed,
         },
         "roofline": {
@@ -175,7 +192,8 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         },
         "overlap": {"batch_ms": ms_per_step, "transfer_ms": xfer_ms, "score_ms": score_ms,
                     "batch_over_transfer": ms_per_step / xfer_ms,
-                    "logical_gb_per_batch": logical / 1e9, "pcie_gb_per_batch": pcie_bytes / 1e9},
+                    "logical_gb_per_batch": logical / 1e9, "distinct_gb_per_batch": distinct_bytes / 1e9,
+                    "pcie_gb_per_batch": pcie_bytes / 1e9},
     }
     if args.sweep_batch:
         # Eq. 4 with PCIe in the place of the SSD: the largest batch whose fetch fits a time budget.
@@ -189,17 +207,20 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         b = 16
         while b <= w.B:
             part = cands[0][:b].contiguous()
-            t_ms = []
+            prev = cands[1][:b].contiguous()
+            t_ms, moved = [], []
             for rep in range(3):
+                # slot 1 holds the first b queries of another batch, as it would in the running pipeline
+                rc = lib.espn_prefetch(h, prev.data_ptr(), b, w.K, 1, st_side)
                 e0.record(side_s)
-                rc = lib.espn_prefetch(h, part.data_ptr(), b, w.K, 0, st_side)
+                rc = rc or lib.espn_prefetch(h, part.data_ptr(), b, w.K, 0, st_side)
                 e1.record(side_s)
                 torch.cuda.synchronize()
                 if rc != 0:
                     raise RuntimeError("espn_prefetch failed: " + espn.last_error())
                 t_ms.append(e0.elapsed_time(e1))
-            u = np.unique(cands_np[0][:b])
-            sweep[b] = {"transfer_ms": min(t_ms), "pcie_mb": float(counts[u].sum()) * w.dim * 2 / 1e6,
+                moved.append(espn.espn_staging_counters(table, 0, side_s)["pcie_bytes"])
+            sweep[b] = {"transfer_ms": min(t_ms), "pcie_mb": float(np.mean(moved)) / 1e6,
                         "logical_mb": per_query * b / 1e6}
             b *= 2
         fits = [bb for bb, v in sweep.items() if v["transfer_ms"] <= args.budget_ms]
@@ -256,6 +277,9 @@ def main():
     ap.add_argument("--budget-ms", type=float, default=28.0, help="time budget for --sweep-batch")
     ap.add_argument("--host-docs", type=int, default=None,
                     help="c5 only: number of documents of the host-resident table (default 8.8 M = 156 GB pinned)")
+    ap.add_argument("--slots", type=int, default=2,
+                    help="c5 only: HBM staging slots (2 = double buffering; more slots also serve as a cache of "
+                         "recently fetched documents)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
@@ -294,6 +318,8 @@ def main():
     warmup = args.warmup if args.warmup is not None else max(3, steps // 10)
     n_sets = args.sets if args.sets is not None else DEFAULT_SETS[args.workload]
     if w.host_resident:
+        if n_sets <= args.slots:
+            n_sets = args.slots + 1        # a prefetch takes over what other slots hold: never the same batch again
         run_host_resident(args, w, seed, steps, args.warmup if args.warmup is not None else 1, n_sets)
         return
 

@@ -221,12 +221,16 @@ int espn_table_check(espn_table *table, void *stream);
  * re-ranking embeddings in a slower tier, Sec. 4); the documents a batch needs are copied to an HBM
  * staging slot ahead of scoring, on a side stream, while the previous batch is scored from the
  * other slot (Sec. 4.2: fetching overlapped with computation; Sec. 4.1: fetched straight into GPU
- * memory).  Typical loop, batch n:
+ * memory).  With more than two slots the slots form a ring that doubles as a cache of recently used
+ * documents: a prefetch takes a document from any other slot that still holds it instead of fetching it
+ * from host memory again.  Typical loop with two slots, batch n:
  *     espn_prefetch(t, cand[n+1], B, K, (n+1) % 2, side);            // returns at once
  *     espn_rerank_staged(t, n % 2, q[n], cand[n], ..., main);        // returns at once
  * Ordering between the two streams is handled inside with events: a staged re-rank waits for the
- * prefetch of its slot, and a prefetch waits for the last re-rank that read its slot.  No call here
- * blocks the host except espn_staging_create and espn_staging_counters.
+ * prefetch of its slot, and a prefetch waits for the last re-rank that read its slot and for the last
+ * prefetch into every other slot.  No call here blocks the host except espn_staging_create(_ring) and
+ * espn_staging_counters.  Calls on one table's staging slots must not be made from several host
+ * threads at once.
  * ------------------------------------------------------------------------------------------- */
 
 /*
@@ -241,10 +245,16 @@ int espn_table_check(espn_table *table, void *stream);
  */
 int espn_staging_create(espn_table *table, int64_t capacity_rows, int64_t capacity_docs);
 
+/* The same with n_slots slots, 2 <= n_slots <= 8, numbered 0 .. n_slots-1 (each of the given capacity). */
+int espn_staging_create_ring(espn_table *table, int32_t n_slots, int64_t capacity_rows, int64_t capacity_docs);
+
 /*
- * Copy every distinct document named in cand to staging slot `slot` (0 or 1): a document listed by
- * several queries crosses PCIe once.  Runs entirely on the GPU on `side_stream` (mark distinct ids,
- * reserve rows, copy rows out of pinned host memory).
+ * Copy every distinct document named in cand to staging slot `slot`: a document listed by several
+ * queries crosses PCIe once, and a document that the last prefetch into ANOTHER slot brought in is
+ * copied from there (HBM to HBM) instead of crossing PCIe again, so documents that stay popular from
+ * batch to batch are fetched from the slow tier once.  Runs entirely on the GPU on `side_stream` (mark
+ * distinct ids, reserve rows, copy rows).  The call waits (on the device) for the last prefetch into
+ * every other slot, whatever stream that ran on.
  *   cand  [B, K] int64, DEVICE; must stay unchanged until the prefetch has run.
  * Errors: ARG, HIP.  Ids out of range are flagged as in espn_score.
  */
@@ -264,7 +274,8 @@ int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, const int
 
 /*
  * Waits for `stream`, then reports what the last prefetch into `slot` did: out4[0] distinct documents,
- * out4[1] rows reserved, out4[2] bytes that crossed PCIe (rows * dim * 2), out4[3] slot capacity in rows.
+ * out4[1] rows reserved, out4[2] bytes that crossed PCIe (rows not taken from another slot, times the
+ * bytes of a row), out4[3] slot capacity in rows.
  * out4 is a HOST pointer to four uint64.
  */
 int espn_staging_counters(espn_table *table, int32_t slot, void *stream, uint64_t *out4);

@@ -44,6 +44,7 @@ SIGNATURES = {
     "espn_batch_threshold": (ctypes.c_double, [ctypes.c_double, ctypes.c_double, ctypes.c_double]),
     "espn_table_check": (ctypes.c_int, [_c_p, _c_p]),
     "espn_staging_create": (ctypes.c_int, [_c_p, _c_i64, _c_i64]),
+    "espn_staging_create_ring": (ctypes.c_int, [_c_p, _c_i32, _c_i64, _c_i64]),
     "espn_prefetch": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p]),
     "espn_rerank_staged": (ctypes.c_int, [_c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
                                           _c_p, _c_sz, _c_p]),
@@ -255,6 +256,10 @@ def espn_table_check(table: Table, stream=None) -> None:
 
 def espn_staging_create(table: Table, capacity_rows: int, capacity_docs: int) -> None:
     _check(lib().espn_staging_create(table.handle, capacity_rows, capacity_docs))
+
+
+def espn_staging_create_ring(table: Table, n_slots: int, capacity_rows: int, capacity_docs: int) -> None:
+    _check(lib().espn_staging_create_ring(table.handle, n_slots, capacity_rows, capacity_docs))
 
 
 def espn_prefetch(table: Table, cand: torch.Tensor, slot: int, side_stream=None) -> None:

@@ -70,7 +70,9 @@ struct StagingSlot {
     int64_t *row_map = nullptr;            // [n_docs] first staged row of a document (valid if its bit is set)
     unsigned *bits = nullptr;              // [ceil(n_docs / 32)] documents held by the slot
     int64_t *uniq = nullptr;               // [capacity_docs] distinct documents of the batch
-    unsigned long long *counters = nullptr;  // [4]: distinct documents, rows reserved
+    int64_t *other_row = nullptr;          // [capacity_docs] where each one's rows come from: a row of another slot, or -1 (host)
+    unsigned long long *counters = nullptr;  // [4]: distinct documents, rows reserved, rows taken from other slots
+    uint64_t filled_at = 0;                // sequence number of the last prefetch into the slot (0: never)
     hipEvent_t ready = nullptr;            // recorded when a prefetch into the slot has been enqueued
     hipEvent_t consumed = nullptr;         // recorded when a re-rank reading the slot has been enqueued
 };
@@ -87,7 +89,9 @@ struct espn_table {
     int32_t dim = 0;
     int32_t residency = 0;
     int32_t device = 0;
-    StagingSlot slot[2];
+    StagingSlot slot[espn::MAX_SLOTS];
+    int n_slots = 0;
+    uint64_t prefetches = 0;         // prefetches enqueued so far
     int64_t capacity_rows = 0;
     int64_t capacity_docs = 0;
     bool has_staging = false;
@@ -215,11 +219,13 @@ void free_staging(espn_table *t)
         (void)hipFree(s.row_map);
         (void)hipFree(s.bits);
         (void)hipFree(s.uniq);
+        (void)hipFree(s.other_row);
         (void)hipFree(s.counters);
         if (s.ready) (void)hipEventDestroy(s.ready);
         if (s.consumed) (void)hipEventDestroy(s.consumed);
         s = StagingSlot();
     }
+    t->n_slots = 0;
     t->has_staging = false;
 }
 }  // namespace
@@ -569,19 +575,30 @@ ESPN_API int espn_table_check(espn_table *table, void *stream)
 
 ESPN_API int espn_staging_create(espn_table *table, int64_t capacity_rows, int64_t capacity_docs)
 {
+    return espn_staging_create_ring(table, 2, capacity_rows, capacity_docs);
+}
+
+ESPN_API int espn_staging_create_ring(espn_table *table, int32_t n_slots, int64_t capacity_rows, int64_t capacity_docs)
+{
     if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (n_slots < 2 || n_slots > espn::MAX_SLOTS)
+        return fail(ESPN_ERR_ARG, "n_slots = %d outside [2, %d]", n_slots, espn::MAX_SLOTS);
     if (capacity_rows < 1 || capacity_docs < 1) return fail(ESPN_ERR_ARG, "capacities must be positive");
+    if (capacity_rows >= (int64_t)1 << espn::OTHER_SHIFT)
+        return fail(ESPN_ERR_UNSUPPORTED, "capacity_rows = %lld is beyond 2^%d", (long long)capacity_rows, espn::OTHER_SHIFT);
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     (void)hipDeviceSynchronize();
     free_staging(table);
     const size_t n_words = (size_t)(table->n_docs + 31) / 32 + 1;
     hipError_t e = hipSuccess;
-    for (StagingSlot &s : table->slot) {
+    for (int i = 0; i < n_slots; ++i) {
+        StagingSlot &s = table->slot[i];
         if (e == hipSuccess) e = hipMalloc(&s.rows, (size_t)capacity_rows * table->dim * table->elem_bytes);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.row_map), sizeof(int64_t) * (size_t)(table->n_docs + 1));
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.bits), sizeof(unsigned) * n_words);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.uniq), sizeof(int64_t) * (size_t)capacity_docs);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.other_row), sizeof(int64_t) * (size_t)capacity_docs);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.counters), kAlign);
         if (e == hipSuccess) e = hipMemset(s.bits, 0, sizeof(unsigned) * n_words);
         if (e == hipSuccess) e = hipMemset(s.counters, 0, kAlign);
@@ -597,6 +614,8 @@ ESPN_API int espn_staging_create(espn_table *table, int64_t capacity_rows, int64
     }
     table->capacity_rows = capacity_rows;
     table->capacity_docs = capacity_docs;
+    table->n_slots = n_slots;
+    table->prefetches = 0;
     table->has_staging = true;
     return ESPN_OK;
 }
@@ -606,7 +625,8 @@ int check_slot(const espn_table *table, int32_t slot)
 {
     if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
     if (!table->has_staging) return fail(ESPN_ERR_ARG, "espn_staging_create has not been called for this table");
-    if (slot < 0 || slot > 1) return fail(ESPN_ERR_ARG, "slot = %d, expected 0 or 1", slot);
+    if (slot < 0 || slot >= table->n_slots)
+        return fail(ESPN_ERR_ARG, "slot = %d outside [0, %d)", slot, table->n_slots);
     return ESPN_OK;
 }
 }  // namespace
@@ -621,19 +641,42 @@ ESPN_API int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, in
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     hipStream_t st = static_cast<hipStream_t>(side_stream);
     StagingSlot &s = table->slot[slot];
-    // the slot may still be read by the re-rank that used it last
+    // The slot may still be read by the re-rank that used it last.  The other slots, whose documents
+    // this prefetch may take over, must have been filled, and none of them may be refilled before
+    // this prefetch is through with it: every prefetch waits for the last prefetch into every other
+    // slot, which puts all prefetches of a table in one order (a no-op if they share a stream).
     HIP_TRY(hipStreamWaitEvent(st, s.consumed, 0));
+    espn::OtherSlots others{};
+    {
+        int order[espn::MAX_SLOTS];
+        int n = 0;
+        for (int i = 0; i < table->n_slots; ++i)
+            if (i != slot) {
+                HIP_TRY(hipStreamWaitEvent(st, table->slot[i].ready, 0));
+                if (table->slot[i].filled_at) order[n++] = i;
+            }
+        std::sort(order, order + n, [&](int a, int b) { return table->slot[a].filled_at > table->slot[b].filled_at; });
+        others.n = n;
+        for (int x = 0; x < n; ++x) {
+            const StagingSlot &o = table->slot[order[x]];
+            others.bits[x] = o.bits;
+            others.row_map[x] = o.row_map;
+            others.rows[x] = static_cast<const uint4 *>(o.rows);
+        }
+    }
+    s.filled_at = ++table->prefetches;
     const int64_t n_words = (table->n_docs + 31) / 32 + 1;
     const int64_t n_pairs = (int64_t)B * K;
     hipLaunchKernelGGL(espn::staging_clear_kernel, dim3((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024)),
                        dim3(256), 0, st, s.bits, n_words, s.counters);
     if (n_pairs > 0) {
         hipLaunchKernelGGL(espn::staging_mark_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, cand,
-                           n_pairs, table->off_dev, table->n_docs, s.bits, s.row_map, s.uniq, s.counters,
-                           table->capacity_rows, table->capacity_docs, table->err_dev);
+                           n_pairs, table->off_dev, table->n_docs, s.bits, s.row_map, s.uniq, s.other_row, others,
+                           s.counters, table->capacity_rows, table->capacity_docs, table->err_dev);
         hipLaunchKernelGGL(espn::staging_gather_kernel, dim3(kGatherBlocks), dim3(256), 0, st,
-                           static_cast<const uint4 *>(table->emb), table->off_dev, s.uniq, s.row_map, s.counters,
-                           table->capacity_docs, static_cast<uint4 *>(s.rows), table->dim * table->elem_bytes / 16);
+                           static_cast<const uint4 *>(table->emb), others, table->off_dev, s.uniq, s.other_row,
+                           s.row_map, s.counters, table->capacity_docs,
+                           static_cast<uint4 *>(s.rows), table->dim * table->elem_bytes / 16);
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s.ready, st));
@@ -671,7 +714,7 @@ ESPN_API int espn_staging_counters(espn_table *table, int32_t slot, void *stream
     HIP_TRY(hipStreamSynchronize(st));
     out4[0] = c[0];
     out4[1] = c[1];
-    out4[2] = c[1] * (uint64_t)table->dim * (uint64_t)table->elem_bytes;
+    out4[2] = (c[1] - c[2]) * (uint64_t)table->dim * (uint64_t)table->elem_bytes;
     out4[3] = (uint64_t)table->capacity_rows;
     return ESPN_OK;
 }

@@ -5,11 +5,14 @@
 //
 //   clear   zero the slot's document bitmap and its counters
 //   mark    one thread per (query, candidate): set the document's bit; the thread that sets it
-//           first reserves the document's rows in the slot (wave-aggregated atomic add) and appends
-//           the id to the slot's list of distinct documents.  A document listed by many queries
-//           is therefore copied once.
-//   gather  one wave per distinct document: copy its rows from pinned host memory (read across
-//           PCIe by the kernel itself, 16 bytes per lane, lane-linear) into the slot.
+//           first reserves the document's rows in the slot (wave-aggregated atomic add), appends
+//           the id to the slot's list of distinct documents and notes where the rows come from:
+//           ANOTHER slot if an earlier batch's prefetch left the document there (a popular
+//           document is fetched from the slow tier once and then handed from slot to slot), else
+//           the host table.  A document listed by many queries is copied once.
+//   gather  one wave per distinct document: copy its rows into the slot, from another slot
+//           (HBM to HBM) or from pinned host memory (read across PCIe by the kernel itself,
+//           16 bytes per lane, lane-linear).
 //
 // The order of documents inside a slot depends on the order in which atomics land; nothing that is
 // computed from the slot depends on it.
@@ -21,7 +24,19 @@
 
 namespace espn {
 
-// counters: [0] distinct documents, [1] rows reserved
+// What a prefetch may take from the table's other slots: the documents their last prefetches placed
+// there.  Listed most recently filled first (the likeliest holder of a popular document).
+constexpr int MAX_SLOTS = 8;
+struct OtherSlots {
+    int n;
+    const unsigned *bits[MAX_SLOTS - 1];
+    const int64_t *row_map[MAX_SLOTS - 1];
+    const uint4 *rows[MAX_SLOTS - 1];
+};
+// "row r of other slot x" as one word; -1 stands for the host table
+constexpr int OTHER_SHIFT = 48;
+
+// counters: [0] distinct documents, [1] rows reserved, [2] rows taken from other slots
 __global__ void staging_clear_kernel(unsigned *__restrict__ bits, int64_t n_words,
                                      unsigned long long *__restrict__ counters)
 {
@@ -33,6 +48,7 @@ __global__ void staging_clear_kernel(unsigned *__restrict__ bits, int64_t n_word
 __global__ __launch_bounds__(256) void staging_mark_kernel(
     const int64_t *__restrict__ cand, int64_t n_pairs, const int64_t *__restrict__ off, int64_t n_docs,
     unsigned *__restrict__ bits, int64_t *__restrict__ row_map, int64_t *__restrict__ uniq,
+    int64_t *__restrict__ other_row, const OtherSlots others,
     unsigned long long *__restrict__ counters, int64_t capacity_rows, int64_t capacity_docs,
     unsigned *__restrict__ err)
 {
@@ -77,17 +93,30 @@ __global__ __launch_bounds__(256) void staging_mark_kernel(
         // every list position below the capacity is written (the copy kernel reads them all);
         // a document that does not fit is listed with no rows
         const bool fits = r0 + len <= capacity_rows && slot_pos < capacity_docs;
-        if (slot_pos < capacity_docs) uniq[slot_pos] = id;
+        // where another slot holds the document, or -1: read it from the host table
+        int64_t from = -1;
+        for (int x = 0; x < others.n && from < 0; ++x)
+            if ((others.bits[x][id >> 5] >> (id & 31)) & 1u) {
+                const int64_t r = others.row_map[x][id];
+                if (r >= 0) from = ((int64_t)x << OTHER_SHIFT) | r;
+            }
+        if (slot_pos < capacity_docs) {
+            uniq[slot_pos] = id;
+            other_row[slot_pos] = from;
+        }
         row_map[id] = fits ? r0 : -1;
         if (!fits) atomicOr(err, ERR_STAGING_FULL);
+        else if (from >= 0 && len > 0) atomicAdd(&counters[2], (unsigned long long)len);
     }
 }
 
-// chunks_per_row = bytes of a row / 16.  host_emb is device-visible pinned host memory (or HBM).
+// chunks_per_row = bytes of a row / 16.  host_emb is device-visible pinned host memory (or HBM);
+// documents whose other_row entry is >= 0 are read from the slot it names instead.
 __global__ __launch_bounds__(256) void staging_gather_kernel(
-    const uint4 *__restrict__ host_emb, const int64_t *__restrict__ off, const int64_t *__restrict__ uniq,
-    const int64_t *__restrict__ row_map, const unsigned long long *__restrict__ counters, int64_t capacity_docs,
-    uint4 *__restrict__ slot, int chunks_per_row)
+    const uint4 *__restrict__ host_emb, const OtherSlots others, const int64_t *__restrict__ off,
+    const int64_t *__restrict__ uniq, const int64_t *__restrict__ other_row, const int64_t *__restrict__ row_map,
+    const unsigned long long *__restrict__ counters, int64_t capacity_docs, uint4 *__restrict__ slot,
+    int chunks_per_row)
 {
     const int lane = threadIdx.x & 63;
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -99,7 +128,10 @@ __global__ __launch_bounds__(256) void staging_gather_kernel(
         if (r0 < 0) continue;
         const int64_t first = off[id];
         const int64_t n_chunks = (off[id + 1] - first) * chunks_per_row;
+        const int64_t from = other_row[u];
         const uint4 *src = host_emb + (size_t)first * chunks_per_row;
+        if (from >= 0)
+            src = others.rows[from >> OTHER_SHIFT] + (size_t)(from & (((int64_t)1 << OTHER_SHIFT) - 1)) * chunks_per_row;
         uint4 *dst = slot + (size_t)r0 * chunks_per_row;
         int64_t x = lane;
         for (; x + 7 * 64 < n_chunks; x += 8 * 64) {           // 8 KiB in flight per wave

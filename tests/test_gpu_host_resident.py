@@ -60,13 +60,109 @@ def test_double_buffered_batches_match_the_oracle(key, changes):
         assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
         for b in range(w.B):
             assert_topk_matches(ids[b].cpu().numpy(), top[b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
-    # what the last prefetches moved: exactly the distinct documents of their batches, each once
+    # what the last prefetches moved: exactly the distinct documents of their batches, each once, and
+    # over PCIe only those that the batch before (which sat in the other slot) had not brought in already
     for n in (n_batches - 2, n_batches - 1):
         c = espn.espn_staging_counters(table, n % 2)
         uniq = np.unique(cands[n])
         rows = int((off[uniq + 1] - off[uniq]).sum())
-        assert c["distinct_docs"] == uniq.size and c["rows"] == rows and c["pcie_bytes"] == rows * w.dim * 2
+        fresh = np.setdiff1d(uniq, cands[n - 1])
+        fresh_rows = int((off[fresh + 1] - off[fresh]).sum())
+        assert c["distinct_docs"] == uniq.size and c["rows"] == rows
+        assert c["pcie_bytes"] == fresh_rows * w.dim * 2
         assert c["distinct_docs"] < cands[n].size          # the candidate law repeats documents
+        if w.cand_law == "zipf":
+            assert fresh_rows < rows                        # ... also from batch to batch
+    table.free()
+
+
+def test_documents_are_handed_from_slot_to_slot():
+    """A chain of batches in which every document of batch n+1 is also in batch n: after the first
+    prefetch nothing crosses PCIe any more, and the scores stay those of the table."""
+    w = synth.scaled(synth.WORKLOADS["c5"], n_docs=6_000, B=6, K=150)
+    say("slot-to-slot hand-over %s" % w.name)
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    espn.espn_staging_create(table, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    base = synth.candidates(w, batch=0)
+    rng = np.random.default_rng(2)
+    chain = [base]
+    for n in range(1, 4):                     # each batch re-draws its lists from the previous batch's documents
+        pool = np.unique(chain[-1])
+        chain.append(np.stack([rng.permutation(pool)[:w.K] for _ in range(w.B)]).astype(np.int64))
+    q = synth.queries(w)
+    q_d = q.to(DEV)
+    e = emb.numpy()
+    for n, cand in enumerate(chain):
+        cand_d = torch.from_numpy(cand).to(DEV)
+        espn.espn_prefetch(table, cand_d, n % 2)
+        ids, top, ws = espn.espn_rerank_staged(table, n % 2, q_d, cand_d, w.k)
+        c = espn.espn_staging_counters(table, n % 2)
+        uniq = np.unique(cand)
+        rows = int((off[uniq + 1] - off[uniq]).sum())
+        assert c["distinct_docs"] == uniq.size and c["rows"] == rows
+        assert c["pcie_bytes"] == (rows * w.dim * 2 if n == 0 else 0), (n, c)
+        o_all = oracle.scores(e, off, q.numpy(), cand)
+        assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
+    # slots too small for the batch: whatever fitted the other slot may be taken from it, whatever did
+    # not is read from the host again; every document the second slot holds must score right either way
+    cand = chain[0]
+    cand_d = torch.from_numpy(cand).to(DEV)
+    uniq = np.unique(cand)
+    rows = int((off[uniq + 1] - off[uniq]).sum())
+    espn.espn_staging_create(table, capacity_rows=rows // 2, capacity_docs=w.n_docs)
+    espn.espn_prefetch(table, cand_d, 0)
+    espn.espn_prefetch(table, cand_d, 1)
+    ids, top, ws = espn.espn_rerank_staged(table, 1, q_d, cand_d, w.k)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_table_check(table)
+    assert ei.value.status in (espn.ESPN_ERR_NOMEM, espn.ESPN_ERR_SHAPE)
+    g = scores_of(ws, w.B, w.K)
+    o_all = oracle.scores(e, off, q.numpy(), cand)
+    held = ~np.isneginf(g)
+    assert held.any() and (~held).any()
+    assert_scores_close(g[held], o_all[held], w.Q)
+    table.free()
+
+
+def test_a_ring_of_slots_serves_as_a_cache_of_recent_documents():
+    w = synth.scaled(synth.WORKLOADS["c5"], n_docs=30_000, B=12, K=250)
+    n_slots, n_batches = 4, 9
+    say("ring of %d slots, %s" % (n_slots, w.name))
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    espn.espn_staging_create_ring(table, n_slots, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    with pytest.raises(espn.EspnError):
+        espn.espn_prefetch(table, torch.zeros((1, 1), dtype=torch.int64, device=DEV), n_slots)
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    cands_d = [torch.from_numpy(c).to(DEV) for c in cands]
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    outs, moved = [], []
+    espn.espn_prefetch(table, cands_d[0], 0, side)
+    for n in range(n_batches):
+        if n + 1 < n_batches:
+            espn.espn_prefetch(table, cands_d[n + 1], (n + 1) % n_slots, side)
+        outs.append(espn.espn_rerank_staged(table, n % n_slots, qs[n].to(DEV), cands_d[n], w.k, stream=main))
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    e = emb.numpy()
+    for n in range(n_batches):
+        ids, top, ws = outs[n]
+        o_ids, o_top, o_all = oracle.rerank(e, off, qs[n].numpy(), cands[n], w.k)
+        assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
+        for b in range(w.B):
+            assert_topk_matches(ids[b].cpu().numpy(), top[b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+    # the last prefetches: over PCIe came only what none of the three batches before had brought in
+    for n in range(n_batches - n_slots + 1, n_batches):
+        c = espn.espn_staging_counters(table, n % n_slots)
+        uniq = np.unique(cands[n])
+        held = np.unique(np.concatenate([cands[m].ravel() for m in range(n - n_slots + 1, n)]))
+        fresh = np.setdiff1d(uniq, held)
+        assert c["distinct_docs"] == uniq.size
+        assert c["pcie_bytes"] == int((off[fresh + 1] - off[fresh]).sum()) * w.dim * 2
+        one_back = np.setdiff1d(uniq, cands[n - 1])
+        assert fresh.size < one_back.size          # more slots, more hits
     table.free()
 
 
@@ -85,6 +181,10 @@ def test_hbm_entry_points_refuse_a_host_table():
     with pytest.raises(espn.EspnError) as ei:
         espn.espn_prefetch(table, cand, 2)
     assert ei.value.status == espn.ESPN_ERR_ARG
+    for bad in (1, 9):
+        with pytest.raises(espn.EspnError) as ei:
+            espn.espn_staging_create_ring(table, bad, 100, 10)
+        assert ei.value.status == espn.ESPN_ERR_ARG
 
 
 def test_an_hbm_table_can_be_staged_too_as_a_standalone_gather():
