@@ -1,0 +1,88 @@
+"""Seeded random launch shapes through the whole path against the fp64 oracle: query length, list
+length, batch size, k, document-length law (with empty documents, single rows, tile-straddling
+lengths and a few very long documents), for both matrix-core row lengths and both codecs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_05417_amd import binding as espn
+from paper_2312_05417_amd import synth
+from tests.parity import assert_scores_close, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def draw_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([32, 128]))
+    Q = int(rng.choice([1, 2, 5, 15, 16, 17, 31, 32]))
+    B = int(rng.choice([1, 2, 3, 7, 33, 130, 600]))
+    K = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 127, 200, 256, 257, 511, 1000, 1500, 2049]))
+    if B * K > 300_000:
+        B = max(1, 300_000 // K)
+    k = int(rng.choice([0, 1, 2, 10, 64, 65, K]))
+    k = min(k, K)
+    N = int(rng.choice([1, 3, 50, 2000]))
+    law = int(rng.integers(0, 4))
+    if law == 0:
+        counts = rng.integers(0, 40, size=N)                       # short, some empty
+    elif law == 1:
+        counts = rng.choice([0, 1, 15, 16, 17, 31, 32, 33, 48, 64], size=N)   # around the 16-row tile
+    elif law == 2:
+        counts = np.clip(rng.lognormal(np.log(40) - 0.125, 0.5, size=N).round(), 4, 128).astype(np.int64)
+    else:
+        counts = rng.integers(1, 12, size=N)
+        counts[rng.integers(0, N, size=max(1, N // 50))] = rng.integers(300, 700)   # a few very long ones
+    counts = counts.astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    x = rng.normal(size=(int(off[-1]), d)).astype(np.float32) * rng.choice([0.05, 1.0, 7.0])
+    qq = rng.normal(size=(B, Q, d)).astype(np.float32) * rng.choice([0.1, 1.0, 3.0])
+    cand = rng.integers(0, N, size=(B, K)).astype(np.int64)        # with repeats
+    return d, Q, B, K, k, N, x.astype(np.float16), off, qq.astype(np.float16), cand
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shape(seed):
+    d, Q, B, K, k, N, emb, off, q, cand = draw_case(seed)
+    say("seed %d: d=%d Q=%d B=%d K=%d k=%d N=%d rows=%d" % (seed, d, Q, B, K, k, N, emb.shape[0]))
+    emb_d = torch.from_numpy(emb).to(DEV) if emb.shape[0] else torch.zeros((0, d), dtype=torch.float16, device=DEV)
+    q_d, cand_d = torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
+    table = espn.espn_table_load(emb_d, off)
+    g_all = espn.espn_score(table, q_d, cand_d)
+    g_ids, g_top = espn.espn_rerank(table, q_d, cand_d, k)
+    espn.espn_table_check(table)
+    # the whole path against scoring + the stand-alone ranking kernel: bit for bit, every query
+    t_ids, t_top = espn.espn_topk(g_all, cand_d, k)
+    assert torch.equal(g_ids, t_ids) and torch.equal(g_top.view(torch.int32), t_top.view(torch.int32))
+    # against the oracle: all scores; ranks on a sample of queries
+    o_all = oracle.scores(emb, off, q, cand)
+    assert_scores_close(g_all.cpu().numpy(), o_all, Q)
+    ids, top = g_ids.cpu().numpy(), g_top.cpu().numpy()
+    for b in sorted(set([0, B // 2, B - 1])):
+        assert_topk_matches(ids[b], top[b], o_all[b], cand[b], k, Q)
+    table.free()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shape_compressed(seed):
+    d, Q, B, K, k, N, emb, off, q, cand = draw_case(100 + seed)
+    if emb.shape[0] == 0:
+        pytest.skip("no rows to compress")
+    say("e4m3 seed %d: d=%d Q=%d B=%d K=%d k=%d N=%d" % (seed, d, Q, B, K, k, N))
+    codes, scale = synth.compress_e4m3(torch.from_numpy(emb), off)
+    table = espn.espn_table_load_e4m3(codes.to(DEV), scale, off)
+    q_d, cand_d = torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
+    g_all = espn.espn_score(table, q_d, cand_d)
+    g_ids, g_top = espn.espn_rerank(table, q_d, cand_d, k)
+    espn.espn_table_check(table)
+    t_ids, t_top = espn.espn_topk(g_all, cand_d, k)
+    assert torch.equal(g_ids, t_ids) and torch.equal(g_top.view(torch.int32), t_top.view(torch.int32))
+    o_all = oracle.scores_e4m3(codes.numpy(), scale, off, q, cand)
+    assert_scores_close(g_all.cpu().numpy(), o_all, Q)
+    table.free()
