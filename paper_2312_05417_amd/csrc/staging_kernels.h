@@ -36,7 +36,8 @@ struct OtherSlots {
 // "row r of other slot x" as one word; -1 stands for the host table
 constexpr int OTHER_SHIFT = 48;
 
-// counters: [0] distinct documents, [1] rows reserved, [2] rows taken from other slots
+// counters: [0] distinct documents, [1] rows reserved, [2] rows taken from other slots,
+//           [3] documents handed out to the copy kernel's waves
 __global__ void staging_clear_kernel(unsigned *__restrict__ bits, int64_t n_words,
                                      unsigned long long *__restrict__ counters)
 {
@@ -115,14 +116,20 @@ __global__ __launch_bounds__(256) void staging_mark_kernel(
 __global__ __launch_bounds__(256) void staging_gather_kernel(
     const uint4 *__restrict__ host_emb, const OtherSlots others, const int64_t *__restrict__ off,
     const int64_t *__restrict__ uniq, const int64_t *__restrict__ other_row, const int64_t *__restrict__ row_map,
-    const unsigned long long *__restrict__ counters, int64_t capacity_docs, uint4 *__restrict__ slot,
+    unsigned long long *__restrict__ counters, int64_t capacity_docs, uint4 *__restrict__ slot,
     int chunks_per_row)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int64_t n = min((int64_t)counters[0], capacity_docs);
-    for (int64_t u = wave; u < n; u += n_waves) {
+    // Waves draw documents from a shared counter (counters[3], zeroed by the clear kernel): a wave
+    // that draws documents held by another slot is through with them in no time and draws again, so
+    // the documents that have to cross PCIe are always spread over all waves and the link stays busy.
+    while (true) {
+        unsigned long long next = 0;
+        if (lane == 0) next = atomicAdd(&counters[3], 1ull);
+        const int64_t u = (int64_t)(((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(next >> 32)) << 32) |
+                                    (unsigned)__builtin_amdgcn_readfirstlane((int)next));
+        if (u >= n) break;
         const int64_t id = uniq[u];
         const int64_t r0 = row_map[id];
         if (r0 < 0) continue;
