@@ -283,8 +283,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--two-streams", action="store_true",
-                    help="also time the same batches issued alternately on two streams (reported beside value)")
+    ap.add_argument("--two-streams", nargs="?", type=int, const=2, default=0, metavar="N",
+                    help="also time the same batches issued in turn on N streams, default 2 (reported beside value)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-queries", type=int, default=None)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -452,15 +452,16 @@ def main():
     # Only with --two-streams: overlapped launches would blur the per-kernel averages of a profiler run.
     two_stream_wall = None
     if args.two_streams:
-        side = [torch.cuda.Stream(), torch.cuda.Stream()]
-        side_ws = [ws, torch.empty(ws_bytes, dtype=torch.uint8, device=dev)]
+        ns = args.two_streams
+        side = [torch.cuda.Stream() for _ in range(ns)]
+        side_ws = [ws] + [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(ns - 1)]
         side_st = [int(x.cuda_stream) for x in side]
-        for i in range(min(warmup, 4)):
-            rerank(i, side_st[i % 2], side_ws[i % 2])
+        for i in range(max(min(warmup, 8), ns)):
+            rerank(i, side_st[i % ns], side_ws[i % ns])
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            rerank(i, side_st[i % 2], side_ws[i % 2])
+            rerank(i, side_st[i % ns], side_ws[i % ns])
         torch.cuda.synchronize()
         two_stream_wall = time.perf_counter() - t0
         espn.espn_table_check(table)
@@ -472,8 +473,8 @@ def main():
             ms_per_step, plan["launches"], plan["slices"], plan["slice"], kern_avg_ms, achieved, score_only_ms,
             "n/a" if two_launch_ms is None else "%.4f" % two_launch_ms))
     if two_stream_wall is not None:
-        log("on two streams: %.4f ms/step = %.1f GB/s algorithmic" % (
-            two_stream_wall * 1e3 / steps, launch_bytes * steps / two_stream_wall / 1e9))
+        log("on %d streams: %.4f ms/step = %.1f GB/s algorithmic" % (
+            args.two_streams, two_stream_wall * 1e3 / steps, launch_bytes * steps / two_stream_wall / 1e9))
 
     result = {
         "metric": "candidate docs MaxSim-scored/sec",
@@ -500,7 +501,7 @@ def main():
         "two_streams": None if two_stream_wall is None else {
             "value": w.B * R * steps / two_stream_wall, "unit": "docs/s", "ms_per_step": two_stream_wall * 1e3 / steps,
             "algorithmic_gbs": launch_bytes * steps / two_stream_wall / 1e9,
-            "note": "the same batches issued alternately on two streams"},
+            "streams": args.two_streams, "note": "the same batches issued in turn on several streams"},
         "roofline": {
             "bound": "hbm",
             "kernel": "maxsim_slice_kernel<%d>%s" % (w.dim, " (ranks as well)" if plan["launches"] == 1 else ""),
