@@ -281,6 +281,9 @@ def main():
                     help="c5 only: HBM staging slots (2 = double buffering; more slots also serve as a cache of "
                          "recently fetched documents)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
+    ap.add_argument("--query-tokens", type=int, default=None,
+                    help="override the rows per query (more than 32 takes the plain-ALU kernel instead of the "
+                         "matrix-core kernel: a comparison point, not a workload of the paper)")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--two-streams", nargs="?", type=int, const=2, default=0, metavar="N",
@@ -313,6 +316,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.batch is not None:
         w = synth.scaled(w, B=args.batch, name="%s-B%d" % (w.name, args.batch))
+    if args.query_tokens is not None:
+        w = synth.scaled(w, Q=args.query_tokens, name="%s-Q%d" % (w.name, args.query_tokens))
     seed = synth.DEFAULT_SEED if args.seed is None else args.seed
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload]
     warmup = args.warmup if args.warmup is not None else max(3, steps // 10)
@@ -504,7 +509,8 @@ def main():
             "streams": args.two_streams, "note": "the same batches issued in turn on several streams"},
         "roofline": {
             "bound": "hbm",
-            "kernel": "maxsim_slice_kernel<%d>%s" % (w.dim, " (ranks as well)" if plan["launches"] == 1 else ""),
+            "kernel": ("maxsim_slice_kernel<%d>%s" % (w.dim, " (ranks as well)" if plan["launches"] == 1 else "")
+                       if w.dim in (32, 128) and w.Q <= 32 else "maxsim_generic_kernel (plain ALU)"),
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
             "algorithmic_bytes_per_launch": launch_bytes, "kernel_ms_avg": kern_avg_ms,
