@@ -63,8 +63,9 @@ const char *espn_last_error(void);
  *                keeps it alive and unchanged until espn_table_free.  Must be 16-byte aligned.
  *   offsets_host [n_docs + 1] int64 HOST pointer, in rows; offsets[0] = 0, non-decreasing
  *                (a document may be empty).  COPIED (to the device); may be freed after the call.
- *   dim          vector length; a positive multiple of 8.  32 and 128 (the two the paper's
- *                models use) run on the matrix-core kernel, other values on a slower generic one.
+ *   dim          vector length; a positive multiple of 8.  Multiples of 32 up to 256 run on the
+ *                matrix-core kernel (32 and 128, the two the paper's models use, are the tuned
+ *                ones), other values on a slower generic one.
  *   device       HIP device ordinal.
  *   out          receives the handle.
  *

@@ -268,6 +268,10 @@ int check_batch(const espn_table *table, const void *q, const int64_t *cand, int
     return ESPN_OK;
 }
 
+// Waves per workgroup of the matrix-core kernel: two workgroups fit a compute unit for the paper's two
+// row lengths (32: 40 VGPRs x 16 waves, 128: 112 VGPRs x 8 waves); longer rows hold more registers per wave.
+constexpr int waves_per_workgroup(int dim) { return dim == 32 ? 16 : dim <= 128 ? 8 : 4; }
+
 // How a batch is cut into workgroup slices, and whether the scoring kernel ranks as well.
 struct SlicePlan {
     int slice = 0;          // candidates per workgroup
@@ -283,12 +287,16 @@ struct SlicePlan {
 // The kernel ranks as well when that leaves one slice of at most RANK_MAX candidates per query.
 SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
 {
-    const int waves = t->dim == 32 ? 16 : 8;
+    const int waves = waves_per_workgroup(t->dim);
     const int slots = 2 * t->n_cu;
     const int one_round = (slots + B - 1) / B;
     int slices;
     if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, std::max(1, K / waves));
-    else slices = (K + (t->dim == 32 ? 125 : 63) - 1) / (t->dim == 32 ? 125 : 63);
+    else {
+        // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
+        const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);
+        slices = (K + per_slice - 1) / per_slice;
+    }
     slices = std::max(slices, (K + espn::MAX_SLICE - 1) / espn::MAX_SLICE);
     SlicePlan p;
     p.slice = (K + slices - 1) / slices;
@@ -301,7 +309,7 @@ template <int D, int EB, bool RANK>
 void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
                    float *scores, const espn::RankOut &ro, hipStream_t st)
 {
-    constexpr int WAVES = D == 32 ? 16 : 8;
+    constexpr int WAVES = waves_per_workgroup(D);
     constexpr int P = 4;                     // register pipeline depth in 16-row tiles
     hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK>), dim3(plan.slices, B), dim3(WAVES * 64), 0,
                        st, src, bt, scores, err, plan.slice, ro);
@@ -315,7 +323,7 @@ void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, con
     else launch_slices<D, EB, false>(src, bt, B, plan, err, scores, ro, st);
 }
 
-bool on_matrix_cores(const espn_table *t, int Q) { return (t->dim == 32 || t->dim == 128) && Q <= 32; }
+bool on_matrix_cores(const espn_table *t, int Q) { return t->dim % 32 == 0 && t->dim <= 256 && Q <= 32; }
 
 // Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot).
 // plan.rank: the kernel also writes the ranked top-k described by `ro`.
@@ -331,8 +339,16 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
             if (t->dim == 32) launch_slices<32, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);
             else launch_slices<128, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);
         } else {
-            if (t->dim == 32) launch_slices<32, 2>(src, bt, B, plan, t->err_dev, scores, ro, st);
-            else launch_slices<128, 2>(src, bt, B, plan, t->err_dev, scores, ro, st);
+            switch (t->dim) {
+                case 32: launch_slices<32, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 64: launch_slices<64, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 96: launch_slices<96, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 128: launch_slices<128, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 160: launch_slices<160, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 192: launch_slices<192, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 224: launch_slices<224, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                default: launch_slices<256, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+            }
         }
     } else {
         const size_t lds = (size_t)bt.Q * t->dim * 2;

@@ -3,7 +3,7 @@
 //   score[b,j] = sum_{i<Q} max_{r in doc(cand[b,j])} <q[b,i,:], emb[r,:]>
 //
 // Two kernels:
-//   maxsim_slice_kernel<D>  D in {32,128}: the Q x D x t contraction of each document runs on the
+//   maxsim_slice_kernel<D>  D = 32, 64, .. 256: the Q x D x t contraction of each document runs on the
 //                           matrix cores (v_mfma_f32_16x16x32_f16); document rows stream from HBM
 //                           through a register pipeline into the MFMA A operand, the query sits
 //                           in VGPRs.  Rows are binary16, or E4M3 codes widened exactly to binary16
@@ -142,8 +142,9 @@ __device__ __forceinline__ float row16_sum(float v)
 // row r); the query fragments are gathered once per wave with the same assignment.
 //
 // How the rows reach that layout differs with the row length:
-//   D = 128  a lane loads its 64 contiguous bytes directly (4 x global_load_dwordx4); measured, this
-//            access pattern streams ragged documents at the same rate as lane-linear loads.
+//   D >= 64  a lane loads its D/2 contiguous bytes directly (D = 128: 4 x global_load_dwordx4);
+//            measured, this access pattern streams ragged documents at the same rate as lane-linear
+//            loads.
 //   D = 32   a 16-row tile is 1 KiB; lane l loads bytes [16 l, 16 l + 16) of it (one fully
 //            coalesced instruction), then four ds_bpermute_b32 move chunk c of row r from lane
 //            4r + c to lane r + 16c.  Loading in the MFMA layout directly (16 B per lane at a 64 B
@@ -160,7 +161,7 @@ __device__ __forceinline__ float row16_sum(float v)
 // exhausted cursor re-reads its last tile) so that the number of loads in flight is static and the
 // waits the compiler inserts are exact.
 //
-// A partial last tile: rows beyond the document's end are replaced by its last row (D = 128: the
+// A partial last tile: rows beyond the document's end are replaced by its last row (D >= 64: the
 // load address is clamped; D = 32: the bpermute source is clamped).  A duplicated row cannot change
 // a maximum, so no masking is needed.  Rows of the query beyond Q are zero vectors: they add
 // max(0,..,0) = 0 to the sum.
@@ -215,7 +216,7 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
             buf.w[0] = v.x; buf.w[1] = v.y;
         }
     } else {
-        // lane (r, c) loads the c-th quarter of tile row r: 64 contiguous bytes (binary16) or 32 (E4M3)
+        // lane (r, c) loads the c-th quarter of tile row r: D/2 contiguous bytes (binary16) or D/4 (E4M3)
         const int r = lane & 15, c = lane >> 4;
         const int row = min(cur.tile + r, cur.t - 1);
         const uint4 *p = reinterpret_cast<const uint4 *>(emb + ((size_t)cur.row0 + row) * ROW + c * (ROW / 4));
@@ -268,7 +269,8 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err, int slice,
     const RankOut ro)
 {
-    static_assert((D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 && P >= 1, "unsupported shape");
+    static_assert(D % 32 == 0 && D >= 32 && D <= 256 && (EB == 2 || D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 &&
+                      P >= 1, "unsupported shape");
     __shared__ int64_t s_row0[MAX_SLICE];
     __shared__ int s_ntok[MAX_SLICE];
     __shared__ float s_scale[EB == 1 ? MAX_SLICE : 1];

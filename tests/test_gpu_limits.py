@@ -76,8 +76,8 @@ def test_plan_of_typical_shapes():
     t32 = espn.espn_table_load(emb, np.array([0, 64], dtype=np.int64))
     emb128 = torch.zeros((64, 128), dtype=torch.float16, device=DEV)
     t128 = espn.espn_table_load(emb128, np.array([0, 64], dtype=np.int64))
-    emb64 = torch.zeros((64, 64), dtype=torch.float16, device=DEV)
-    t64 = espn.espn_table_load(emb64, np.array([0, 64], dtype=np.int64))
+    emb72 = torch.zeros((64, 72), dtype=torch.float16, device=DEV)
+    t72 = espn.espn_table_load(emb72, np.array([0, 64], dtype=np.int64))
     for table, B, K, k in ((t32, 64, 1000, 10), (t32, 8, 100, 10), (t32, 1024, 64, 10), (t128, 256, 1000, 10),
                            (t128, 2048, 1000, 10), (t128, 4096, 64, 10), (t32, 1, 1, 1), (t128, 3, 5000, 0)):
         p = espn.espn_rerank_plan(table, B, 32, K, k)
@@ -88,10 +88,10 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t32, 64, 32, 1000, 10) == {"slices": 8, "slice": 125, "launches": 2}
     assert espn.espn_rerank_plan(t32, 1024, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
     # shapes the matrix-core kernel does not take: one wave per candidate, a second launch ranks
-    assert espn.espn_rerank_plan(t64, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
+    assert espn.espn_rerank_plan(t72, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
     assert espn.espn_rerank_plan(t32, 5, 40, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
     assert espn.espn_rerank_plan(t32, 0, 32, 40, 3) == {"slices": 0, "slice": 0, "launches": 0}
     with pytest.raises(espn.EspnError):
         espn.espn_rerank_plan(t32, 4, 32, 10, 11)
-    for t in (t32, t128, t64):
+    for t in (t32, t128, t72):
         t.free()

@@ -97,11 +97,21 @@ def test_candidate_count_shapes(K, k):
     run_both(emb, off, q, cand, k)
 
 
-@pytest.mark.parametrize("d,Q", [(8, 4), (64, 32), (96, 5), (32, 40), (128, 33), (256, 16)])
+@pytest.mark.parametrize("d,Q", [(8, 4), (40, 32), (72, 5), (32, 40), (128, 33), (264, 16)])
 def test_generic_kernel_shapes(d, Q):
     say("generic d=%d Q=%d" % (d, Q))
     emb, off, q, cand = random_problem(d + Q, 200, d, 2, Q, 61, 0, 70)
     run_both(emb, off, q, cand, 9)
+
+
+@pytest.mark.parametrize("d", [64, 96, 160, 192, 224, 256])
+@pytest.mark.parametrize("Q", [5, 32])
+def test_other_row_lengths_on_the_matrix_cores(d, Q):
+    # every multiple of 32 up to 256 takes the matrix-core kernel; lengths straddle the 16-row tile
+    counts = np.array([0, 1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 100, 127, 128, 129, 180] * 6)
+    say("matrix cores d=%d Q=%d" % (d, Q))
+    emb, off, q, cand = random_problem(3 * d + Q, counts.size, d, 3, Q, 117, 0, 0, counts=counts)
+    run_both(emb, off, q, cand, 10)
 
 
 @pytest.mark.parametrize("d", [32, 128, 64])

@@ -20,7 +20,7 @@ def say(msg):
 
 def draw_case(seed):
     rng = np.random.default_rng(1000 + seed)
-    d = int(rng.choice([32, 128]))
+    d = int(rng.choice([32, 128, 32, 128, 64, 192]))
     Q = int(rng.choice([1, 2, 5, 15, 16, 17, 31, 32]))
     B = int(rng.choice([1, 2, 3, 7, 33, 130, 600]))
     K = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 127, 200, 256, 257, 511, 1000, 1500, 2049]))
@@ -72,8 +72,8 @@ def test_random_shape(seed):
 @pytest.mark.parametrize("seed", range(8))
 def test_random_shape_compressed(seed):
     d, Q, B, K, k, N, emb, off, q, cand = draw_case(100 + seed)
-    if emb.shape[0] == 0:
-        pytest.skip("no rows to compress")
+    if emb.shape[0] == 0 or d not in (32, 128):
+        pytest.skip("nothing to compress, or a row length compressed tables do not take")
     say("e4m3 seed %d: d=%d Q=%d B=%d K=%d k=%d N=%d" % (seed, d, Q, B, K, k, N))
     codes, scale = synth.compress_e4m3(torch.from_numpy(emb), off)
     table = espn.espn_table_load_e4m3(codes.to(DEV), scale, off)
