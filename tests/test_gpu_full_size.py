@@ -32,7 +32,7 @@ def check_everything_cheap(scores, ids, top, cand, w):
     assert np.all((scores > kth).sum(axis=1) <= w.k - 1)
 
 
-@pytest.mark.parametrize("key,sample", [("c2", 16), ("c3", 8), ("c4", 8)])
+@pytest.mark.parametrize("key,sample", [("c2", 64), ("c3", 48), ("c4", 48)])
 def test_full_size_hbm_workloads(key, sample):
     w = synth.WORKLOADS[key]
     say("%s full size: N=%d d=%d B=%d K=%d" % (w.name, w.n_docs, w.dim, w.B, w.K))
