@@ -189,6 +189,7 @@ struct DocCursor {
 };
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 // Registers one lane holds of one 16-row tile: EB = bytes per component (2: binary16, 1: E4M3).
 template <int D, int EB>
@@ -209,7 +210,11 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
         const uint8_t *p = emb + ((size_t)cur.row0 + cur.tile) * ROW;
         const int piece = min(lane, npiece - 1);
         if constexpr (EB == 2) {
-            const uint4 v = reinterpret_cast<const uint4 *>(p)[piece];
+            // Every byte of the tile is asked for exactly once, by this one instruction: a non-temporal
+            // load (no claim on cache space the look-ups could use) is 1.5 % faster on a 32 us launch.
+            // The other load shapes below come back to their cache lines and must not use it
+            // (measured: the 256-byte-row kernel takes 1.8 times as long with it).
+            const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p) + piece);
             buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
         } else {
             const uint2 v = reinterpret_cast<const uint2 *>(p)[piece];
