@@ -24,6 +24,36 @@ def lib():
     return binding.lib()
 
 
+def test_header_is_plain_c_and_links_from_c(lib, tmp_path):
+    """The header compiles as strict C99 and as C++, and a C program that includes it links against the
+    library and gets sane answers from the calls that need no GPU."""
+    import subprocess
+    from paper_2312_05417_amd import binding
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c", HEADER])
+    subprocess.check_call(["g++", "-std=c++11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", HEADER])
+    src = tmp_path / "use_espn.c"
+    src.write_text('''
+#include <stdio.h>
+#include <string.h>
+#include "espn.h"
+int main(void) {
+    if (espn_workspace_bytes(64, 1000) != 256000u) return 1;
+    if (espn_batch_threshold(2.0e9, 0.5, 1.0e6) != 1000.0) return 2;
+    if (strcmp(espn_status_string(ESPN_ERR_SHAPE), "inconsistent sizes") != 0) return 3;
+    if (espn_topk(NULL, NULL, 1, 4, 5, NULL, NULL, NULL) != ESPN_ERR_SHAPE) return 4;
+    if (strstr(espn_last_error(), "k = 5") == NULL) return 5;
+    if (espn_table_free(NULL) != ESPN_OK) return 6;
+    puts("ok");
+    return 0;
+}
+''')
+    exe = tmp_path / "use_espn"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.dirname(HEADER), str(src), "-o", str(exe),
+                           "-L", libdir, "-l:libespn.so", "-Wl,-rpath," + libdir])
+    assert subprocess.check_output([str(exe)]).decode().strip() == "ok"
+
+
 def test_header_declares_the_path():
     names = declared_functions()
     for must in ("espn_table_load", "espn_table_free", "espn_score", "espn_topk", "espn_rerank"):
