@@ -153,8 +153,10 @@ __device__ __forceinline__ float row16_sum(float v)
 // Work split.  A workgroup of WAVES waves owns a SLICE of one query's candidate list (up to
 // MAX_SLICE consecutive candidates).  All its threads first look the slice's documents up
 // (candidate id -> offset pair) and leave the descriptors in LDS, so the two dependent memory
-// round trips are paid once per workgroup and not once per wave.  The waves then take documents
-// from the slice one at a time through an LDS counter, which keeps every wave busy until the slice
+// round trips are paid once per workgroup and not once per wave.  (Wave w also looks the w-th
+// document up itself and requests its first tile before the barrier that ends the table fill, so
+// that rows are on their way while the slowest look-up of the workgroup is still outstanding.)
+// The waves then take the other documents of the slice one at a time through an LDS counter, which keeps every wave busy until the slice
 // is exhausted however uneven the documents are.  The tiles of the documents a wave takes form one
 // sequence that is software-pipelined P deep through registers: the load for tile u+P is issued
 // right after tile u is consumed, across document boundaries.  Loads are unconditional (an
