@@ -156,8 +156,8 @@ __device__ __forceinline__ float row16_sum(float v)
 // round trips are paid once per workgroup and not once per wave.  (Wave w also looks the w-th
 // document up itself and requests its first tile before the barrier that ends the table fill, so
 // that rows are on their way while the slowest look-up of the workgroup is still outstanding.)
-// The waves then take the other documents of the slice one at a time through an LDS counter, which keeps every wave busy until the slice
-// is exhausted however uneven the documents are.  The tiles of the documents a wave takes form one
+// The waves then take the other documents of the slice one at a time through an LDS counter, which
+// keeps every wave busy until the slice is exhausted however uneven the documents are.  The tiles of the documents a wave takes form one
 // sequence that is software-pipelined P deep through registers: the load for tile u+P is issued
 // right after tile u is consumed, across document boundaries.  Loads are unconditional (an
 // exhausted cursor re-reads its last tile) so that the number of loads in flight is static and the
@@ -169,9 +169,12 @@ __device__ __forceinline__ float row16_sum(float v)
 // max(0,..,0) = 0 to the sum.
 //
 // Ranking (RANK = true; launches with one slice of at most RANK_MAX candidates per query, such as the
-// re-ranked prefix of partial re-ranking).  The workgroup also keeps its scores and ids in LDS and
-// ranks them when the slice is done: every wave takes some entries and counts, with one ballot per
-// 64 competitors, how many entries come before each; an entry whose count is below k writes itself
+// re-ranked prefix of partial re-ranking).  The workgroup also keeps the order keys of its scores
+// and the ids in LDS and ranks them when the slice is done: the threads split the (entry,
+// competitor) pairs among themselves and count, per entry, how many entries come before it (keys
+// are read from LDS at addresses a whole wave shares and compared in vector registers; counting
+// with one cross-lane vote per 64 competitors was measured slower, each vote stalling the wave
+// on a vector-to-scalar hand-over); an entry whose count is below k writes itself
 // to that rank.  No second launch.  Longer lists are ranked by the stand-alone kernel: it spreads
 // the ranking of all queries over the whole device at once, which beats ranking at the tail of
 // each workgroup, and slices of one query cannot meet cheaply (an agent-scope release / acquire
@@ -264,7 +267,8 @@ struct RankOut {
 // LDS a workgroup keeps for ranking its slice (nothing when it only scores)
 template <bool RANK>
 struct RankLds {
-    float score[RANK_MAX];
+    __attribute__((aligned(16))) unsigned key[RANK_MAX + 4];    // order_key of the scores, then zeros
+    unsigned count[RANK_MAX];       // entries ahead (low half) and entries of equal score, itself included (high half)
     int64_t id[RANK_MAX];
 };
 template <>
@@ -299,7 +303,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     // document up itself and requests its first tile, so rows are on their way while the slice's
     // descriptor table is still being filled (which ends with a barrier, i.e. with the slowest
     // look-up of the workgroup).
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));     // in a scalar register
     const size_t cand0 = (size_t)b * bt.ldc + j_begin;
     int64_t id_own = -1, id_fill = -1;
     if (wave < n) id_own = bt.cand[cand0 + wave];
@@ -335,10 +339,14 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         if (ntok == 0) {
             const float none = with_prior(bt, b, j_begin + i, neg_inf());
             scores[(size_t)b * K + j_begin + i] = none;
-            if constexpr (RANK) s_rank.score[i] = none;
+            if constexpr (RANK) s_rank.key[i] = order_key(none);
         }
     }
     if (threadIdx.x == 0) s_next = min(WAVES, n);      // the first WAVES documents are spoken for
+    if constexpr (RANK) {
+        if (threadIdx.x < 4) s_rank.key[n + threadIdx.x] = 0u;
+        if (threadIdx.x < RANK_MAX) s_rank.count[threadIdx.x] = 0u;
+    }
 
     // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
     half8 qf[2][KS];
@@ -451,7 +459,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                         if (lane == 0) {
                             const float total = with_prior(bt, b, j_begin + cs.idx, sum);
                             scores[(size_t)b * K + j_begin + cs.idx] = total;
-                            if constexpr (RANK) s_rank.score[cs.idx] = total;
+                            if constexpr (RANK) s_rank.key[cs.idx] = order_key(total);
                         }
                         m0 = neg_inf();
                         m1 = neg_inf();
@@ -465,70 +473,59 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     }
 
     if constexpr (RANK) {
-        // gridDim.x == 1 and n <= RANK_MAX: the slice is the query's whole list.  Order: score
-        // descending, id ascending, position ascending; NaN scores (key 0) are never ranked.
-        __syncthreads();
-        constexpr int CH = RANK_MAX / 64;
-        unsigned key[CH];
-        int64_t idj[CH];
-        int rankable = 0;
-#pragma unroll
-        for (int x = 0; x < CH; ++x) {
-            const int j = x * 64 + lane;
-            key[x] = 0u;
-            idj[x] = 0;
-            if (x * 64 < n) {                // wave-uniform: chunks past the end cost nothing
-                if (j < n) {
-                    key[x] = order_key(s_rank.score[j]);
-                    idj[x] = s_rank.id[j];
-                }
-                rankable += __builtin_popcountll(__ballot(key[x] != 0u));
-            }
+        // gridDim.x == 1 and n <= RANK_MAX <= blockDim.x: the slice is the query's whole list.
+        // Order: score descending, id ascending, position ascending; NaN scores (key 0) are never
+        // ranked.  An entry's rank is the number of entries ahead of it.  The threads form a
+        // (entries x parts) grid: thread (e, part) compares entry e with the part-th share of the
+        // list (keys read from LDS at addresses the whole wave shares, counts kept in vector
+        // registers, no cross-lane votes) and adds what it found to the entry's counter.
+        constexpr int T = WAVES * 64;
+        constexpr int LG_T = T == 1024 ? 10 : T == 512 ? 9 : T == 256 ? 8 : -1;
+        static_assert(LG_T > 0 && RANK_MAX == 256 && RANK_MAX <= T, "one thread per entry at least");
+        __syncthreads();                                      // every key is in LDS
+        const int lg = n <= 64 ? 6 : n <= 128 ? 7 : 8;        // entries rounded up to 64, 128 or 256 columns
+        const int e = threadIdx.x & ((1 << lg) - 1);
+        const int part = threadIdx.x >> lg;                   // wave-uniform
+        const int groups = (n + 3) >> 2;                      // keys are read four at a time; keys n .. n+3 are zero
+        const int per = (groups + (T >> lg) - 1) >> (LG_T - lg);
+        const int j_end = min(groups, (part + 1) * per) * 4;
+        const unsigned mine = e < n ? s_rank.key[e] : 0u;
+        int ahead = 0, same = 0;
+        for (int j = part * per * 4; j < j_end; j += 4) {
+            const uint4 kk = *reinterpret_cast<const uint4 *>(&s_rank.key[j]);
+            ahead += (kk.x > mine) + (kk.y > mine) + (kk.z > mine) + (kk.w > mine);
+            same += (kk.x == mine) + (kk.y == mine) + (kk.z == mine) + (kk.w == mine);
         }
+        if (mine != 0u && (ahead | same) != 0) atomicAdd(&s_rank.count[e], (unsigned)ahead | ((unsigned)same << 16));
+        __syncthreads();
         int64_t *oi = ro.out_ids + (size_t)b * ro.ldo;
         float *os = ro.out_scores + (size_t)b * ro.ldo;
-        // wave w ranks entries w, w + WAVES, ... of every chunk; their keys and ids are already in
-        // registers (lane e % 64 of chunk e / 64).  The ids only matter among equal scores.
-#pragma unroll
-        for (int y = 0; y < CH; ++y) {
-            for (int l = threadIdx.x >> 6; l < 64 && y * 64 + l < n; l += WAVES) {
-                const int e = y * 64 + l;
-                const unsigned ke = (unsigned)__builtin_amdgcn_readlane((int)key[y], l);
-                if (ke == 0u) continue;
-                int rank = 0;
-                bool ties = false;
-#pragma unroll
-                for (int x = 0; x < CH; ++x) {
-                    if (x * 64 < n) {
-                        rank += __builtin_popcountll(__ballot(key[x] > ke));
-                        uint64_t equal = __ballot(key[x] == ke);
-                        if (x == y) equal &= ~(1ull << l);
-                        ties |= equal != 0;
-                    }
+        if (part == 0 && mine != 0u) {
+            const unsigned found = s_rank.count[e];
+            int rank = (int)(found & 0xffffu);
+            const int64_t id = s_rank.id[e];
+            if ((found >> 16) > 1u) {                         // the ids only matter among equal scores
+                for (int j = 0; j < n; ++j) {
+                    if (s_rank.key[j] != mine) continue;
+                    const int64_t other = s_rank.id[j];
+                    rank += other < id || (other == id && j < e);
                 }
-                const int64_t ide = readlane64(idj[y], l);
-                if (ties) {
-#pragma unroll
-                    for (int x = 0; x < CH; ++x) {
-                        if (x * 64 < n) {
-                            const int j = x * 64 + lane;
-                            rank += __builtin_popcountll(
-                                __ballot(key[x] == ke && (idj[x] < ide || (idj[x] == ide && j < e))));
-                        }
-                    }
-                }
-                if (rank < ro.k && lane == 0) {
-                    oi[rank] = ide;
-                    os[rank] = key_to_score(ke);
-                }
+            }
+            if (rank < ro.k) {
+                oi[rank] = id;
+                os[rank] = key_to_score(mine);
             }
         }
         // ranks nothing can fill
-        if (threadIdx.x < 64)
+        if (wave == 0) {
+            int rankable = 0;
+            for (int j = 0; j < n; j += 64)
+                rankable += __builtin_popcountll(__ballot(j + lane < n && s_rank.key[min(j + lane, n - 1)] != 0u));
             for (int rest = rankable + lane; rest < ro.k; rest += 64) {
                 oi[rest] = -1;
                 os[rest] = quiet_nan();
             }
+        }
     }
 }
 

@@ -49,6 +49,22 @@ def test_one_launch_path_matches_oracle_and_two_launch_path(d, K, k):
         assert_topk_matches(g_ids[b], g_sc[b], o_all[n], cand[b], k, 32)
 
 
+@pytest.mark.parametrize("K,k", [(3, 2), (64, 10), (130, 130), (256, 7)])
+def test_one_launch_path_below_four_workgroups_per_compute_unit(K, k):
+    """600 single-slice queries: fewer than four workgroups per compute unit, so 64-byte rows run in
+    workgroups of 16 waves (the batches of B_MANY queries above run in workgroups of 8)."""
+    B = 600
+    say("one launch, wide workgroups: d=32 B=%d K=%d k=%d" % (B, K, k))
+    emb, off, q, cand = random_problem(17 * K + 1, max(K, 300), 32, B, 32, K, 1, 40)
+    cand[:, K // 2] = cand[:, 0]               # a duplicate candidate in every list: an exact tie
+    g_ids, g_sc, g_all = both_paths(emb, off, q, cand, k, expect_launches=1)
+    sample = sorted(set([0, 1, B // 2, B - 1] + list(range(5, B, 61))))
+    o_all = oracle.scores(emb, off, np.ascontiguousarray(q[sample]), np.ascontiguousarray(cand[sample]))
+    assert_scores_close(g_all[sample], o_all, 32)
+    for n, b in enumerate(sample):
+        assert_topk_matches(g_ids[b], g_sc[b], o_all[n], cand[b], k, 32)
+
+
 def test_longer_lists_take_two_launches():
     say("K = 257: two launches")
     emb, off, q, cand = random_problem(5, 400, 32, B_MANY, 32, 257, 1, 20)
