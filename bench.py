@@ -284,6 +284,7 @@ def main():
     ap.add_argument("--query-tokens", type=int, default=None,
                     help="override the rows per query (more than 32 takes the plain-ALU kernel instead of the "
                          "matrix-core kernel: a comparison point, not a workload of the paper)")
+    ap.add_argument("--top-k", type=int, default=None, help="override the number of ranks returned per query")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--two-streams", nargs="?", type=int, const=2, default=0, metavar="N",
@@ -316,6 +317,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.batch is not None:
         w = synth.scaled(w, B=args.batch, name="%s-B%d" % (w.name, args.batch))
+    if args.top_k is not None:
+        w = synth.scaled(w, k=args.top_k, name="%s-k%d" % (w.name, args.top_k))
     if args.query_tokens is not None:
         w = synth.scaled(w, Q=args.query_tokens, name="%s-Q%d" % (w.name, args.query_tokens))
     seed = synth.DEFAULT_SEED if args.seed is None else args.seed

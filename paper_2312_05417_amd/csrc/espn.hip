@@ -391,15 +391,26 @@ int enqueue_topk(const float *scores, const int64_t *cand, int ldc, int B, int K
 {
     using namespace espn;
     if (B == 0 || k == 0) return ESPN_OK;
-    if (k <= 64 && K <= 64 * 16)
+    // Few ranks: one wave per query keeps the list in registers and ranks the handful of entries
+    // that can reach the top k (5 us for 64 lists of 1000, k = 10; its cost grows with k and it
+    // falls back to k selection rounds once more than 64 entries survive its threshold).
+    // More ranks: the whole list is sorted, at a cost independent of k (11 us for the same lists).
+    // Lists beyond 4096 entries: k selection rounds over the list.
+    if (k <= 32 && K <= 64 * 16)
         hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
                            out_scores);
-    else if (k <= 64 && K <= 64 * 32)
+    else if (k <= 32 && K <= 64 * 32)
         hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
                            out_scores);
-    else if (K <= 256 * 4)
-        hipLaunchKernelGGL((topk_rounds_kernel<4>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
-                           out_scores);
+    else if (K <= 256)
+        hipLaunchKernelGGL((topk_sort_kernel<256, 64>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo,
+                           out_ids, out_scores);
+    else if (K <= 1024)
+        hipLaunchKernelGGL((topk_sort_kernel<1024, 256>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo,
+                           out_ids, out_scores);
+    else if (K <= 4096)
+        hipLaunchKernelGGL((topk_sort_kernel<4096, 512>), dim3(B), dim3(512), 0, st, scores, cand, ldc, K, k, ldo,
+                           out_ids, out_scores);
     else
         hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
                            out_scores);

@@ -311,6 +311,118 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
                         out_scores + (size_t)b * ldo, (int)threadIdx.x, lds);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Whole-list sort: one workgroup per query, K <= N, any k <= K, at a cost that does not depend on
+// k (the selection kernels above take time proportional to k).  Every entry becomes one 64-bit
+// word, order key in the upper half and 2^32 - 1 - slot in the lower, so that "larger word first"
+// is "score descending, slot ascending"; a bitonic network sorts the N words in LDS, two strides
+// per pass (a thread holds four words, i, i+h, i+2h, i+3h, and applies strides 2h and h in
+// registers).  Passes whose words all belong to the wave that handles them need no workgroup
+// barrier.  The required order among equal scores is by id, which the words do not carry: entries
+// of a run of equal keys count, at the end, how many entries of their run go before them (ids are
+// read through the slots; such runs are short unless many documents are identical or empty).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void order_pair(uint64_t &a, uint64_t &b, bool best_first)
+{
+    const bool swap = best_first ? a < b : a > b;
+    const uint64_t t = swap ? b : a;
+    b = swap ? a : b;
+    a = t;
+}
+
+template <int N, int T>
+__global__ __launch_bounds__(T) void topk_sort_kernel(
+    const float *__restrict__ scores, const int64_t *__restrict__ cand, int ldc, int K, int k, int ldo,
+    int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
+{
+    static_assert(N >= 256 && (N & (N - 1)) == 0 && T % 64 == 0 && N / 4 >= T, "four words per thread at least");
+    __shared__ uint64_t s[N];
+    constexpr int W = T / 64, OWN = N / W;              // waves; words of the range a wave handles
+    constexpr int QW = N / 4 / W, PW = N / 2 / W;       // groups of four / pairs per wave
+    const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const float *sc = scores + (size_t)b * K;
+    const int64_t *ids = cand + (size_t)b * ldc;
+    for (int i = tid; i < N; i += T) {
+        const unsigned key = i < K ? order_key(sc[i]) : 0u;      // slots past the list sort last
+        s[i] = ((uint64_t)key << 32) | (uint64_t)(0xffffffffu - (unsigned)i);
+    }
+    bool prev_local = false;
+    auto sync = [&](bool local) {
+        // local: every word this pass touches was last written by the same wave
+        if (local && prev_local) {
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        } else __syncthreads();
+        prev_local = local;
+    };
+    for (int size = 2; size <= N; size <<= 1) {
+        int stride = size >> 1;
+        while (stride >= 2) {
+            const int h = stride >> 1;
+            sync(4 * h <= OWN);
+#pragma unroll
+            for (int x = 0; x < QW / 64; ++x) {
+                const int g = wave * QW + x * 64 + lane;
+                const int i = ((g & ~(h - 1)) << 2) | (g & (h - 1));
+                const bool best_first = (i & size) == 0;
+                uint64_t e0 = s[i], e1 = s[i + h], e2 = s[i + 2 * h], e3 = s[i + 3 * h];
+                order_pair(e0, e2, best_first);
+                order_pair(e1, e3, best_first);
+                order_pair(e0, e1, best_first);
+                order_pair(e2, e3, best_first);
+                s[i] = e0; s[i + h] = e1; s[i + 2 * h] = e2; s[i + 3 * h] = e3;
+            }
+            stride >>= 2;
+        }
+        if (stride == 1) {
+            sync(true);
+#pragma unroll
+            for (int x = 0; x < PW / 64; ++x) {
+                const int i = 2 * (wave * PW + x * 64 + lane);
+                uint64_t e0 = s[i], e1 = s[i + 1];
+                order_pair(e0, e1, (i & size) == 0);
+                s[i] = e0; s[i + 1] = e1;
+            }
+        }
+    }
+    __syncthreads();
+    // s[r] is the r-th best (key, slot)
+    for (int r = tid; r < K; r += T) {
+        const uint64_t e = s[r];
+        const unsigned key = (unsigned)(e >> 32);
+        const int slot = (int)(0xffffffffu - (unsigned)e);
+        const bool tie_left = r > 0 && (unsigned)(s[r - 1] >> 32) == key;
+        const bool tie_right = r + 1 < K && (unsigned)(s[r + 1] >> 32) == key;
+        if (r >= k && !tie_left) continue;               // nothing can bring it to the front
+        if (key == 0u) {                                  // NaN: never ranked
+            if (r < k) {
+                out_ids[(size_t)b * ldo + r] = -1;
+                out_scores[(size_t)b * ldo + r] = quiet_nan();
+            }
+            continue;
+        }
+        const int64_t id = ids[slot];
+        int pos = r;
+        if (tie_left || tie_right) {
+            int first = r;
+            while (first > 0 && (unsigned)(s[first - 1] >> 32) == key) --first;
+            if (first >= k) continue;
+            pos = first;
+            for (int j = first; j < K; ++j) {
+                const uint64_t o = s[j];
+                if ((unsigned)(o >> 32) != key) break;
+                const int oslot = (int)(0xffffffffu - (unsigned)o);
+                const int64_t oid = ids[oslot];
+                pos += oid < id || (oid == id && oslot < slot);
+            }
+        }
+        if (pos < k) {
+            out_ids[(size_t)b * ldo + pos] = id;
+            out_scores[(size_t)b * ldo + pos] = key_to_score(key);
+        }
+    }
+}
+
 // Partial re-ranking (Sec. 4.4): ranks R .. k-1 of every query are the candidates that were not
 // re-ranked, in the order the first stage listed them; they carry no MaxSim score (NaN).
 __global__ void append_unranked_kernel(const int64_t *__restrict__ cand, int ldc, int R, int k,

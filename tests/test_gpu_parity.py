@@ -242,7 +242,9 @@ def test_binding_rejects_wrong_shapes_before_launching():
 
 
 # ------------------------------------------------------------------ top-k on its own
-@pytest.mark.parametrize("K,k", [(1000, 10), (1000, 1000), (64, 64), (5000, 33), (257, 256)])
+@pytest.mark.parametrize("K,k", [(1000, 10), (1000, 1000), (64, 64), (5000, 33), (257, 256), (1, 1), (2, 2), (100, 40),
+                                 (256, 256), (300, 33), (1000, 32), (1024, 500), (1025, 1025), (2048, 20),
+                                 (3000, 100), (4096, 4096), (4097, 50)])
 def test_topk_alone_with_many_exact_ties(K, k):
     say("topk alone K=%d k=%d" % (K, k))
     rng = np.random.default_rng(K + k)
@@ -254,4 +256,22 @@ def test_topk_alone_with_many_exact_ties(K, k):
     o_ids, o_top = oracle.topk(sc.astype(np.float64), cand, k)
     g_ids, g_top = espn.espn_topk(torch.from_numpy(sc).to(DEV), torch.from_numpy(cand).to(DEV), k)
     assert np.array_equal(g_ids.cpu().numpy(), o_ids)       # scores are exact in fp32: everything is pinned
+    assert np.array_equal(g_top.cpu().numpy().astype(np.float64), o_top)
+
+
+@pytest.mark.parametrize("K,k", [(1000, 1000), (1000, 100), (200, 200), (4000, 64)])
+def test_topk_alone_when_all_scores_are_equal(K, k):
+    """Every score is the same (all documents empty, or identical): the ranking is by id alone, and
+    duplicate ids stay next to each other."""
+    say("topk alone, all scores equal, K=%d k=%d" % (K, k))
+    rng = np.random.default_rng(K * 7 + k)
+    B = 4
+    sc = np.empty((B, K), dtype=np.float32)
+    sc[0], sc[1], sc[2], sc[3] = -np.inf, 3.25, 0.0, -1.5
+    sc[2, ::2] = -0.0                                      # -0 and +0 are the same score
+    cand = np.stack([rng.permutation(3 * K)[:K] for _ in range(B)]).astype(np.int64) - K
+    cand[3, K // 2:] = cand[3, : K - K // 2]             # every id of the last list twice
+    o_ids, o_top = oracle.topk(sc.astype(np.float64), cand, k)
+    g_ids, g_top = espn.espn_topk(torch.from_numpy(sc).to(DEV), torch.from_numpy(cand).to(DEV), k)
+    assert np.array_equal(g_ids.cpu().numpy(), o_ids)
     assert np.array_equal(g_top.cpu().numpy().astype(np.float64), o_top)
