@@ -385,6 +385,26 @@ espn::DocSource hbm_source(const espn_table *t)
     return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs, t->scale_dev};
 }
 
+// Whole-list sort of n <= kSortMax entries per query (one list, or two taken together).
+constexpr int kSortMax = 4096;
+template <typename Lists>
+void launch_sort(const Lists &lists, int B, int n, int k, int ldo, int64_t *out_ids, float *out_scores, hipStream_t st)
+{
+    using namespace espn;
+    if (n <= 256)
+        hipLaunchKernelGGL((topk_sort_kernel<256, 64, Lists>), dim3(B), dim3(64), 0, st, lists, k, ldo, out_ids,
+                           out_scores);
+    else if (n <= 1024)
+        hipLaunchKernelGGL((topk_sort_kernel<1024, 256, Lists>), dim3(B), dim3(256), 0, st, lists, k, ldo, out_ids,
+                           out_scores);
+    else if (n <= 2048)
+        hipLaunchKernelGGL((topk_sort_kernel<2048, 512, Lists>), dim3(B), dim3(512), 0, st, lists, k, ldo, out_ids,
+                           out_scores);
+    else
+        hipLaunchKernelGGL((topk_sort_kernel<4096, 512, Lists>), dim3(B), dim3(512), 0, st, lists, k, ldo, out_ids,
+                           out_scores);
+}
+
 // Ranks the first k of K scored candidates per query; cand rows have leading dimension ldc, output rows ldo.
 int enqueue_topk(const float *scores, const int64_t *cand, int ldc, int B, int K, int k, int ldo, int64_t *out_ids,
                  float *out_scores, hipStream_t st)
@@ -402,15 +422,8 @@ int enqueue_topk(const float *scores, const int64_t *cand, int ldc, int B, int K
     else if (k <= 32 && K <= 64 * 32)
         hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
                            out_scores);
-    else if (K <= 256)
-        hipLaunchKernelGGL((topk_sort_kernel<256, 64>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo,
-                           out_ids, out_scores);
-    else if (K <= 1024)
-        hipLaunchKernelGGL((topk_sort_kernel<1024, 256>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo,
-                           out_ids, out_scores);
-    else if (K <= 4096)
-        hipLaunchKernelGGL((topk_sort_kernel<4096, 512>), dim3(B), dim3(512), 0, st, scores, cand, ldc, K, k, ldo,
-                           out_ids, out_scores);
+    else if (K <= kSortMax)
+        launch_sort(OneList{scores, cand, ldc, K}, B, K, k, ldo, out_ids, out_scores, st);
     else
         hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
                            out_scores);
@@ -577,8 +590,13 @@ ESPN_API int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_
     if (B == 0 || k == 0) return ESPN_OK;
     if ((ka > 0 && (!ids_a || !scores_a)) || (kb > 0 && (!ids_b || !scores_b)) || !out_ids || !out_scores)
         return fail(ESPN_ERR_ARG, "NULL pointer");
-    hipLaunchKernelGGL(espn::merge_topk_kernel, dim3(B), dim3(64), 0, static_cast<hipStream_t>(stream), ids_a,
-                       scores_a, ka, ids_b, scores_b, kb, k, out_ids, out_scores);
+    // up to 4096 entries per query: sorted as one list (cost independent of k); beyond: k selection rounds
+    if ((int64_t)ka + kb <= kSortMax)
+        launch_sort(espn::TwoLists{ids_a, scores_a, ka, ids_b, scores_b, kb}, B, ka + kb, k, k, out_ids, out_scores,
+                    static_cast<hipStream_t>(stream));
+    else
+        hipLaunchKernelGGL(espn::merge_topk_kernel, dim3(B), dim3(64), 0, static_cast<hipStream_t>(stream), ids_a,
+                           scores_a, ka, ids_b, scores_b, kb, k, out_ids, out_scores);
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }

@@ -312,7 +312,7 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Whole-list sort: one workgroup per query, K <= N, any k <= K, at a cost that does not depend on
+// Whole-list sort: one workgroup per query, K <= N entries, any k <= K, at a cost that does not depend on
 // k (the selection kernels above take time proportional to k).  Every entry becomes one 64-bit
 // word, order key in the upper half and 2^32 - 1 - slot in the lower, so that "larger word first"
 // is "score descending, slot ascending"; a bitonic network sorts the N words in LDS, two strides
@@ -330,20 +330,46 @@ __device__ __forceinline__ void order_pair(uint64_t &a, uint64_t &b, bool best_f
     a = t;
 }
 
-template <int N, int T>
+// What the sort kernel ranks: one scored list per query ...
+struct OneList {
+    const float *scores;        // [B, K]
+    const int64_t *cand;        // rows of leading dimension ldc
+    int ldc, K;
+    __device__ int size() const { return K; }
+    __device__ float score(int b, int i) const { return scores[(size_t)b * K + i]; }
+    __device__ int64_t id(int b, int i) const { return cand[(size_t)b * ldc + i]; }
+};
+// ... or two of them, taken as list a followed by list b (Sec. 4.3)
+struct TwoLists {
+    const int64_t *ids_a;
+    const float *sc_a;
+    int ka;
+    const int64_t *ids_b;
+    const float *sc_b;
+    int kb;
+    __device__ int size() const { return ka + kb; }
+    __device__ float score(int b, int i) const
+    {
+        return i < ka ? sc_a[(size_t)b * ka + i] : sc_b[(size_t)b * kb + (i - ka)];
+    }
+    __device__ int64_t id(int b, int i) const
+    {
+        return i < ka ? ids_a[(size_t)b * ka + i] : ids_b[(size_t)b * kb + (i - ka)];
+    }
+};
+
+template <int N, int T, typename Lists>
 __global__ __launch_bounds__(T) void topk_sort_kernel(
-    const float *__restrict__ scores, const int64_t *__restrict__ cand, int ldc, int K, int k, int ldo,
-    int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
+    const Lists lists, int k, int ldo, int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
 {
     static_assert(N >= 256 && (N & (N - 1)) == 0 && T % 64 == 0 && N / 4 >= T, "four words per thread at least");
     __shared__ uint64_t s[N];
     constexpr int W = T / 64, OWN = N / W;              // waves; words of the range a wave handles
     constexpr int QW = N / 4 / W, PW = N / 2 / W;       // groups of four / pairs per wave
     const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const float *sc = scores + (size_t)b * K;
-    const int64_t *ids = cand + (size_t)b * ldc;
+    const int K = lists.size();
     for (int i = tid; i < N; i += T) {
-        const unsigned key = i < K ? order_key(sc[i]) : 0u;      // slots past the list sort last
+        const unsigned key = i < K ? order_key(lists.score(b, i)) : 0u;      // slots past the list sort last
         s[i] = ((uint64_t)key << 32) | (uint64_t)(0xffffffffu - (unsigned)i);
     }
     bool prev_local = false;
@@ -401,7 +427,7 @@ __global__ __launch_bounds__(T) void topk_sort_kernel(
             }
             continue;
         }
-        const int64_t id = ids[slot];
+        const int64_t id = lists.id(b, slot);
         int pos = r;
         if (tie_left || tie_right) {
             int first = r;
@@ -412,7 +438,7 @@ __global__ __launch_bounds__(T) void topk_sort_kernel(
                 const uint64_t o = s[j];
                 if ((unsigned)(o >> 32) != key) break;
                 const int oslot = (int)(0xffffffffu - (unsigned)o);
-                const int64_t oid = ids[oslot];
+                const int64_t oid = lists.id(b, oslot);
                 pos += oid < id || (oid == id && oslot < slot);
             }
         }

@@ -77,7 +77,9 @@ def test_score_aggregation_with_a_prior(key, changes, alpha):
     table.free()
 
 
-@pytest.mark.parametrize("ka,kb,k", [(10, 10, 10), (64, 1000, 10), (0, 5, 5), (7, 0, 3), (200, 300, 500), (3, 3, 0)])
+@pytest.mark.parametrize("ka,kb,k", [(10, 10, 10), (64, 1000, 10), (0, 5, 5), (7, 0, 3), (200, 300, 500), (3, 3, 0),
+                                      (100, 156, 256), (1000, 1000, 1000), (1000, 1000, 2000), (2000, 2096, 100),
+                                      (3000, 1097, 64), (1, 0, 1)])
 def test_merge_of_scored_lists(ka, kb, k):
     say("merge ka=%d kb=%d k=%d" % (ka, kb, k))
     rng = np.random.default_rng(ka * 1000 + kb)
