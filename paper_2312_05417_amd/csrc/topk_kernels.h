@@ -316,15 +316,15 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
 // k (the selection kernels above take time proportional to k).  Every entry becomes one 64-bit
 // word, order key in the upper half and 2^32 - 1 - slot in the lower, so that "larger word first"
 // is "score descending, slot ascending"; a bitonic network sorts the N words in LDS, two strides
-// per pass (a thread holds four words, i, i+h, i+2h, i+3h, and applies strides 2h and h in
-// registers).  Passes whose words all belong to the wave that handles them need no workgroup
-// barrier.  The required order among equal scores is by id, which the words do not carry: entries
+// per pass (a thread holds four words and applies strides 2h and h to them in registers).
+// Passes whose words all belong to the wave that handles them need no workgroup barrier.  The required order among equal scores is by id, which the words do not carry: entries
 // of a run of equal keys count, at the end, how many entries of their run go before them (ids are
 // read through the slots; such runs are short unless many documents are identical or empty).
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void order_pair(uint64_t &a, uint64_t &b, bool best_first)
+// the larger word goes to a
+__device__ __forceinline__ void order_pair(uint64_t &a, uint64_t &b)
 {
-    const bool swap = best_first ? a < b : a > b;
+    const bool swap = a < b;
     const uint64_t t = swap ? b : a;
     b = swap ? a : b;
     a = t;
@@ -381,32 +381,45 @@ __global__ __launch_bounds__(T) void topk_sort_kernel(
         } else __syncthreads();
         prev_local = local;
     };
+    // Merging two sorted halves of `size` words starts by comparing word o of the block with word
+    // size-1-o (the mirror image), after which both halves only need strides size/4 .. 1, all in the
+    // same direction: no comparison depends on where in the list it happens.
     for (int size = 2; size <= N; size <<= 1) {
         int stride = size >> 1;
+        bool mirrored = true;                   // the first stride of a merge
         while (stride >= 2) {
-            const int h = stride >> 1;
+            const int h = stride >> 1;          // this pass applies strides 2h and h
             sync(4 * h <= OWN);
 #pragma unroll
             for (int x = 0; x < QW / 64; ++x) {
                 const int g = wave * QW + x * 64 + lane;
-                const int i = ((g & ~(h - 1)) << 2) | (g & (h - 1));
-                const bool best_first = (i & size) == 0;
-                uint64_t e0 = s[i], e1 = s[i + h], e2 = s[i + 2 * h], e3 = s[i + 3 * h];
-                order_pair(e0, e2, best_first);
-                order_pair(e1, e3, best_first);
-                order_pair(e0, e1, best_first);
-                order_pair(e2, e3, best_first);
-                s[i] = e0; s[i + h] = e1; s[i + 2 * h] = e2; s[i + 3 * h] = e3;
+                const int o = g & (h - 1);
+                const int block = (g & ~(h - 1)) << 2;
+                const int i0 = block + o, i1 = i0 + h;
+                const int i2 = mirrored ? block + 3 * h - 1 - o : i0 + 2 * h;
+                const int i3 = mirrored ? block + 4 * h - 1 - o : i0 + 3 * h;
+                uint64_t e0 = s[i0], e1 = s[i1], e2 = s[i2], e3 = s[i3];
+                if (mirrored) {                 // o with 4h-1-o, o+h with 3h-1-o
+                    order_pair(e0, e3);
+                    order_pair(e1, e2);
+                } else {                        // stride 2h
+                    order_pair(e0, e2);
+                    order_pair(e1, e3);
+                }
+                order_pair(e0, e1);             // stride h
+                order_pair(e2, e3);
+                s[i0] = e0; s[i1] = e1; s[i2] = e2; s[i3] = e3;
             }
+            mirrored = false;
             stride >>= 2;
         }
-        if (stride == 1) {
+        if (stride == 1) {                      // size 2: its own mirror image
             sync(true);
 #pragma unroll
             for (int x = 0; x < PW / 64; ++x) {
                 const int i = 2 * (wave * PW + x * 64 + lane);
                 uint64_t e0 = s[i], e1 = s[i + 1];
-                order_pair(e0, e1, (i & size) == 0);
+                order_pair(e0, e1);
                 s[i] = e0; s[i + 1] = e1;
             }
         }
