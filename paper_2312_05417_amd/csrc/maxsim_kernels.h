@@ -295,8 +295,17 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
     const int xor16 = (lane ^ 16) * 4, xor32 = (lane ^ 32) * 4;     // ds_bpermute addresses
-    const int b = blockIdx.y;
-    const int j_begin = blockIdx.x * slice;
+    // Workgroups are handed to the eight XCDs (each with an L2 of its own) in turn, by linear index.
+    // With a multiple of eight queries, the slices of a query are given linear indices that are
+    // equal modulo 8, so that they run on one XCD and share its copy of the query matrix.
+    int b = blockIdx.y, slice_index = blockIdx.x;
+    if ((gridDim.y & 7u) == 0u) {
+        const unsigned linear = blockIdx.x + gridDim.x * blockIdx.y;
+        const unsigned within = linear >> 3;                    // position among the XCD's workgroups
+        b = (int)((linear & 7u) + 8u * (within / gridDim.x));
+        slice_index = (int)(within % gridDim.x);
+    }
+    const int j_begin = slice_index * slice;
     const int n = min(slice, K - j_begin);  // >= 1 by construction of the grid
 
     // Wave w starts on the w-th document of the slice without waiting for anybody: it looks that
