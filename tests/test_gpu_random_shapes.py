@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2312_05417_amd import binding as espn
 from paper_2312_05417_amd import synth
-from tests.parity import assert_scores_close, assert_topk_matches
+from tests.parity import assert_scores_close, assert_topk_matches, cancellation_floor
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -62,10 +62,12 @@ def test_random_shape(seed):
     assert torch.equal(g_ids, t_ids) and torch.equal(g_top.view(torch.int32), t_top.view(torch.int32))
     # against the oracle: all scores; ranks on a sample of queries
     o_all = oracle.scores(emb, off, q, cand)
-    assert_scores_close(g_all.cpu().numpy(), o_all, Q)
+    # short queries against short documents: maxima of both signs can cancel (see cancellation_floor)
+    floor = cancellation_floor(oracle.scores(np.abs(emb), off, np.abs(q), cand), d, Q)
+    assert_scores_close(g_all.cpu().numpy(), o_all, Q, floor=floor)
     ids, top = g_ids.cpu().numpy(), g_top.cpu().numpy()
     for b in sorted(set([0, B // 2, B - 1])):
-        assert_topk_matches(ids[b], top[b], o_all[b], cand[b], k, Q)
+        assert_topk_matches(ids[b], top[b], o_all[b], cand[b], k, Q, floor=floor[b])
     table.free()
 
 
@@ -84,5 +86,6 @@ def test_random_shape_compressed(seed):
     t_ids, t_top = espn.espn_topk(g_all, cand_d, k)
     assert torch.equal(g_ids, t_ids) and torch.equal(g_top.view(torch.int32), t_top.view(torch.int32))
     o_all = oracle.scores_e4m3(codes.numpy(), scale, off, q, cand)
-    assert_scores_close(g_all.cpu().numpy(), o_all, Q)
+    magnitude = oracle.scores_e4m3(codes.numpy() & 0x7F, scale, off, np.abs(q), cand)     # sign bits cleared
+    assert_scores_close(g_all.cpu().numpy(), o_all, Q, floor=cancellation_floor(magnitude, d, Q))
     table.free()

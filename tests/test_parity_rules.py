@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from tests.parity import assert_scores_close, assert_topk_matches, tol_of
+from tests.parity import assert_scores_close, assert_topk_matches, cancellation_floor, tol_of
 
 
 def problem(seed=0, K=60, Q=8, d=16):
@@ -67,3 +67,33 @@ def test_near_ties_may_swap_but_exact_ties_must_follow_the_id_rule():
     # an id returned twice although listed once
     with pytest.raises(AssertionError):
         assert_topk_matches([10, 20, 20], [5.0, 4.0, 4.0], allsc, cand, 3, 32)
+
+
+def test_cancelling_terms_get_the_floor_binary32_accumulation_can_keep():
+    # a two-row query against one-row documents: the two maxima are dot products of either sign
+    rng = np.random.default_rng(5)
+    d, Q, n = 192, 2, 4000
+    emb = (rng.normal(size=(n, d)) * 7).astype(np.float16)
+    off = np.arange(n + 1, dtype=np.int64)
+    q = (rng.normal(size=(1, Q, d)) * 3).astype(np.float16)
+    cand = np.arange(n, dtype=np.int64)[None]
+    exact = oracle.scores(emb, off, q, cand)
+    magnitude = oracle.scores(np.abs(emb), off, np.abs(q), cand)
+    assert np.all(magnitude >= np.abs(exact))
+    floor = cancellation_floor(magnitude, d, Q)
+    # the same scores accumulated in binary32, row by row
+    e32, q32 = emb.astype(np.float32), q[0].astype(np.float32)
+    approx = np.array([[np.float32((q32 @ e32[j]).sum(dtype=np.float32)) for j in range(n)]], dtype=np.float64)
+    worst = np.abs(approx - exact).max()
+    assert worst > 0 and np.all(np.abs(approx - exact) <= floor)          # the bound holds, with room
+    assert_scores_close(approx, exact, Q, floor=floor)
+    small = np.argmin(np.abs(exact[0]) / magnitude[0])                      # the pair that cancels most
+    assert abs(exact[0, small]) < 1e-3 * magnitude[0, small]
+    # ordinary pairs are still held to the relative tolerance: the floor is far below it there
+    ordinary = np.abs(exact[0]) > 0.1 * magnitude[0]
+    assert ordinary.sum() > 100 and np.all(floor[0, ordinary] < 0.2 * 1e-3 * np.abs(exact[0, ordinary]))
+    # and a mistake of the size of one dropped component is caught even at the cancelling pair
+    g = approx.copy()
+    g[0, small] += float(q32[0, 0] * e32[small, 0])
+    with pytest.raises(AssertionError):
+        assert_scores_close(g, exact, Q, floor=floor)
