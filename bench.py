@@ -22,8 +22,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, raw
 DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 12, "c2p64": 400, "c3p64": 100,
-                 "c2e4m3": 400, "c3e4m3": 100}
-DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4, "c2e4m3": 32, "c3e4m3": 8}
+                 "c2e4m3": 400, "c3e4m3": 100, "c5e4m3": 12}
+DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4, "c2e4m3": 32, "c3e4m3": 8,
+                "c5e4m3": 3}
 
 # HBM bytes per score-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
@@ -52,27 +53,39 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     if args.host_docs is not None:
         w = synth.scaled(w, n_docs=args.host_docs)
     t_setup = time.time()
-    # the full table is 156 GB; if the machine refuses to pin that much, shrink the document count by 20 %
-    # until it fits (the PCIe rate does not depend on it once the table is far larger than any cache)
+    e4m3 = w.codec == "e4m3"
+    row_bytes = w.dim * (1 if e4m3 else 2)
+    doc_scale = None
+    # the full table is 156 GB (78 GB compressed); if the machine refuses to pin that much, shrink the document
+    # count by 20 % until it fits (the PCIe rate does not depend on it once the table is far larger than any cache)
     while True:
         counts = synth.token_counts(w, seed)
         off = synth.offsets_from_counts(counts)
         rows = int(off[-1])
         try:
-            emb = torch.empty((rows, w.dim), dtype=torch.float16, pin_memory=True)
+            emb = torch.empty((rows, w.dim), dtype=torch.uint8 if e4m3 else torch.float16, pin_memory=True)
             break
         except RuntimeError as exc:
-            log("cannot pin %.1f GB for %d docs (%s); shrinking by 20 %%" % (rows * w.dim * 2 / 1e9, w.n_docs,
+            log("cannot pin %.1f GB for %d docs (%s); shrinking by 20 %%" % (rows * row_bytes / 1e9, w.n_docs,
                                                                    str(exc).splitlines()[0]))
             if w.n_docs < 200_000:
                 raise
             w = synth.scaled(w, n_docs=int(w.n_docs * 0.8))
-    log("%s: pinned %.1f GB of host memory for %d docs (%.1f s)" % (w.name, rows * w.dim * 2 / 1e9, w.n_docs,
+    log("%s: pinned %.1f GB of host memory for %d docs (%.1f s)" % (w.name, rows * row_bytes / 1e9, w.n_docs,
                                                                      time.time() - t_setup))
-    synth.table(w, seed, device=dev, out=emb)          # drawn on the GPU chunk by chunk, copied to the host
+    if e4m3:
+        # drawn and compressed in HBM (binary16 table + codes: 1.5 x 158 GB fit the 288 GB), codes copied to the host
+        full, _ = synth.table(w, seed, device=dev)
+        codes, doc_scale = synth.compress_e4m3(full, off)
+        del full
+        emb.copy_(codes)
+        del codes
+        torch.cuda.empty_cache()
+    else:
+        synth.table(w, seed, device=dev, out=emb)      # drawn on the GPU chunk by chunk, copied to the host
     torch.cuda.synchronize()
     log("table filled (%.1f s)" % (time.time() - t_setup))
-    table = espn.espn_table_load(emb, off)
+    table = espn.espn_table_load_e4m3(emb, doc_scale, off) if e4m3 else espn.espn_table_load(emb, off)
 
     cands_np = [synth.candidates(w, seed, s) for s in range(n_sets)]
     cands = [torch.from_numpy(c).to(dev) for c in cands_np]
@@ -88,11 +101,11 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     ws_bytes = espn.espn_workspace_bytes(w.B, w.K)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     log("inputs ready: %d sets; distinct docs per batch %.1f %%, %.2f GB per batch, %d slots x %.2f GB (%.1f s)" % (
-        n_sets, 100.0 * np.mean([u.size for u in uniq]) / (w.B * w.K), np.mean(uniq_rows) * w.dim * 2 / 1e9,
-        n_slots, cap_rows * w.dim * 2 / 1e9, time.time() - t_setup))
+        n_sets, 100.0 * np.mean([u.size for u in uniq]) / (w.B * w.K), np.mean(uniq_rows) * row_bytes / 1e9,
+        n_slots, cap_rows * row_bytes / 1e9, time.time() - t_setup))
 
     # reference: a plain pinned-host -> device copy of 1 GiB
-    ref_src = emb[: (1 << 30) // (w.dim * 2)]
+    ref_src = emb[: (1 << 30) // row_bytes]
     ref_dst = torch.empty_like(ref_src, device=dev)
     ref_dst.copy_(ref_src, non_blocking=True)
     torch.cuda.synchronize()
@@ -100,7 +113,7 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     for _ in range(3):
         ref_dst.copy_(ref_src, non_blocking=True)
     torch.cuda.synchronize()
-    memcpy_gbs = 3 * ref_src.numel() * 2 / (time.perf_counter() - t0) / 1e9
+    memcpy_gbs = 3 * ref_src.numel() * ref_src.element_size() / (time.perf_counter() - t0) / 1e9
     del ref_dst
 
     main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
@@ -156,7 +169,7 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         prefetch(n)
         crossed.append(espn.espn_staging_counters(table, n % n_slots, side_s)["pcie_bytes"])
     pcie_bytes = float(np.mean(crossed))
-    distinct_bytes = float(np.mean([uniq_rows[n % n_sets] for n in range(nxt, nxt + steps)])) * w.dim * 2
+    distinct_bytes = float(np.mean([uniq_rows[n % n_sets] for n in range(nxt, nxt + steps)])) * row_bytes
     nxt += steps
     last = nxt - 1                          # the batch its slot still holds
     torch.cuda.synchronize()
@@ -171,14 +184,14 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         "memcpy %.1f GB/s); scoring alone %.2f ms" % (ms_per_step, xfer_ms, pcie_bytes / 1e9, distinct_bytes / 1e9,
                                                       achieved, memcpy_gbs, score_ms))
 
-    logical = float(np.mean([(2 * w.dim * counts[c]).sum() for c in cands_np]))
+    logical = float(np.mean([(row_bytes * counts[c]).sum() for c in cands_np]))
     result = {
         "metric": "candidate docs MaxSim-scored/sec", "value": w.B * w.K * steps / wall, "unit": "docs/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {
-            "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": rows, "table_gb": rows * w.dim * 2 / 1e9,
-            "residency": "pinned host memory", "batch_queries": w.B, "query_tokens": w.Q,
+            "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": rows, "table_gb": rows * row_bytes / 1e9,
+            "codec": w.codec, "residency": "pinned host memory", "batch_queries": w.B, "query_tokens": w.Q,
             "candidates_per_query": w.K, "top_k": w.k, "candidate_law": "zipf(%.1f)" % w.zipf_alpha,
             "rotating_sets": n_sets, "staging_slots": n_slots,
             "distinct_docs_per_batch": float(np.mean([u.size for u in uniq])),
@@ -201,7 +214,7 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         # sharing between queries, as in the paper); the measurement is the prefetch of the first b
         # queries of batch 0, which benefits from documents shared between queries.
         budget_s = args.budget_ms * 1e-3
-        per_query = float(np.mean([(2 * w.dim * counts[c]).sum() for c in cands_np])) / w.B
+        per_query = float(np.mean([(row_bytes * counts[c]).sum() for c in cands_np])) / w.B
         predicted = lib.espn_batch_threshold(achieved * 1e9, budget_s, per_query)
         sweep = {}
         b = 16
@@ -246,7 +259,10 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         sub, loc_off, loc_cand, ids = synth.subtable(emb, off, cands_np[0][:nq])
         q_np = qs[0][:nq].cpu().numpy()
         t1 = time.perf_counter()
-        o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k)
+        if e4m3:
+            o_all = oracle.scores_e4m3(sub, doc_scale[ids], loc_off, q_np, loc_cand)
+        else:
+            o_all = oracle.scores(sub, loc_off, q_np, loc_cand)
         cpu_s = time.perf_counter() - t1
         prefetch(0)
         rerank(0)
@@ -270,7 +286,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2p64", "c3p64", "c2e4m3", "c3e4m3"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2p64", "c3p64", "c2e4m3", "c3e4m3", "c5e4m3"])
     ap.add_argument("--sweep-batch", action="store_true",
                     help="c5 only: also time the prefetch for smaller batches and compare the batch size at which "
                          "it outgrows a time budget with Eq. 4's prediction")

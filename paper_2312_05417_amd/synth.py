@@ -74,6 +74,9 @@ WORKLOADS = {
                        codec="e4m3"),
     "c3e4m3": Workload("c3-e4m3-d128", 2_000_000, 128, "lognormal", 8, 180, 70.0, 256, 32, 1000, 10, "uniform",
                        codec="e4m3"),
+    # ... and the host-resident table compressed: half the bytes per query cross PCIe (Sec. 6 with Eq. 4)
+    "c5e4m3": Workload("c5-host-e4m3-d128", 8_800_000, 128, "lognormal", 8, 180, 70.0, 1024, 32, 1000, 10, "zipf",
+                       host_resident=True, codec="e4m3"),
 }
 
 
