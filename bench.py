@@ -119,11 +119,17 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
     st_main, st_side, h = int(main_s.cuda_stream), int(side_s.cuda_stream), table.handle
 
+    packed = args.engine == "packed"
+    cands_host = [torch.from_numpy(c) for c in cands_np] if packed else None
+
     def prefetch(n):
         s = n % n_sets
-        rc = lib.espn_prefetch(h, cands[s].data_ptr(), w.B, w.K, n % n_slots, st_side)
+        if packed:       # the host finds the distinct documents and packs them; blocks while it does
+            rc = lib.espn_prefetch_packed(h, cands_host[s].data_ptr(), w.B, w.K, n % n_slots, st_side)
+        else:
+            rc = lib.espn_prefetch(h, cands[s].data_ptr(), w.B, w.K, n % n_slots, st_side)
         if rc != 0:
-            raise RuntimeError("espn_prefetch failed: " + espn.last_error())
+            raise RuntimeError("prefetch failed: " + espn.last_error())
 
     def rerank(n):
         s = n % n_sets
@@ -135,8 +141,12 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     def pipeline(first, count):
         # batch n is scored while batch n+1 is fetched; batch `first` must already be on its way
         for n in range(first, first + count):
-            prefetch(n + 1)
-            rerank(n)
+            if packed:                  # the blocking call second, so that the scoring is already enqueued
+                rerank(n)
+                prefetch(n + 1)
+            else:
+                prefetch(n + 1)
+                rerank(n)
 
     # Batch numbers keep running through every leg below: batch n uses candidate set n % n_sets and slot
     # n % n_slots, and with more sets than slots no slot ever holds the set that is being fetched.  The
@@ -194,11 +204,12 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
             "codec": w.codec, "residency": "pinned host memory", "batch_queries": w.B, "query_tokens": w.Q,
             "candidates_per_query": w.K, "top_k": w.k, "candidate_law": "zipf(%.1f)" % w.zipf_alpha,
             "rotating_sets": n_sets, "staging_slots": n_slots,
+            "prefetch_engine": "host packs into pinned buffers, plain copies" if packed else "gather kernel reading pinned host memory",
             "distinct_docs_per_batch": float(np.mean([u.size for u in uniq])),
             "accumulate": "f32", "seed": seed,
         },
         "roofline": {
-            "bound": "pcie", "kernel": "staging_gather_kernel", "achieved": achieved, "peak": PCIE_PEAK_GBS,
+            "bound": "pcie", "kernel": "hipMemcpyAsync of packed buffers" if packed else "staging_gather_kernel", "achieved": achieved, "peak": PCIE_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / PCIE_PEAK_GBS, "traffic": None,
             "algorithmic_bytes_per_launch": pcie_bytes, "kernel_ms_avg": xfer_ms,
             "plain_memcpy_h2d_gbs": memcpy_gbs,
@@ -296,6 +307,8 @@ def main():
     ap.add_argument("--slots", type=int, default=2,
                     help="c5 only: HBM staging slots (2 = double buffering; more slots also serve as a cache of "
                          "recently fetched documents)")
+    ap.add_argument("--engine", default="gather", choices=["gather", "packed"],
+                    help="c5 only: which prefetch engine fills the staging slots (espn_prefetch / espn_prefetch_packed)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
     ap.add_argument("--query-tokens", type=int, default=None,
                     help="override the rows per query (more than 32 takes the plain-ALU kernel instead of the "

@@ -229,8 +229,8 @@ int espn_table_check(espn_table *table, void *stream);
  *     espn_rerank_staged(t, n % 2, q[n], cand[n], ..., main);        // returns at once
  * Ordering between the two streams is handled inside with events: a staged re-rank waits for the
  * prefetch of its slot, and a prefetch waits for the last re-rank that read its slot and for the last
- * prefetch into every other slot.  No call here blocks the host except espn_staging_create(_ring) and
- * espn_staging_counters.  Calls on one table's staging slots must not be made from several host
+ * prefetch into every other slot.  No call here blocks the host except espn_staging_create(_ring),
+ * espn_staging_counters and espn_prefetch_packed.  Calls on one table's staging slots must not be made from several host
  * threads at once.
  * ------------------------------------------------------------------------------------------- */
 
@@ -260,6 +260,23 @@ int espn_staging_create_ring(espn_table *table, int32_t n_slots, int64_t capacit
  * Errors: ARG, HIP.  Ids out of range are flagged as in espn_score.
  */
 int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, int32_t K, int32_t slot, void *side_stream);
+
+/*
+ * The same prefetch done the other way round (the second of the two ways to bring a batch's documents
+ * from the slow tier into GPU memory ahead of scoring, Sec. 4.1 / 4.2): the HOST finds the distinct
+ * documents, packs their rows back to back into pinned buffers (16 threads, two buffers of 64 MiB) and
+ * sends each buffer with one plain copy on `side_stream`, packing the next buffer meanwhile.  Nothing is
+ * taken from other slots.  The slot ends up in the same state as after espn_prefetch (espn_rerank_staged,
+ * espn_staging_counters and later espn_prefetch calls into other slots work on it unchanged).
+ *   cand_host  [B, K] int64, HOST; read before the call returns.
+ * Unlike espn_prefetch this call BLOCKS the host until all but the last two buffers have been sent, and
+ * its first call on a table allocates the pinned buffers (freed with the staging slots).  Its errors
+ * are found on the host before anything is enqueued: ID_RANGE (an id outside the table), NOMEM (the
+ * batch does not fit the slot, or no pinned memory), UNSUPPORTED (the table is HBM-resident, or a
+ * document is larger than a buffer), ARG, HIP.
+ */
+int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, int32_t B, int32_t K, int32_t slot,
+                         void *side_stream);
 
 /*
  * espn_rerank for a host-resident table: scores cand against the rows held by `slot` (which must have

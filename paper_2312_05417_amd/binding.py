@@ -46,6 +46,7 @@ SIGNATURES = {
     "espn_staging_create": (ctypes.c_int, [_c_p, _c_i64, _c_i64]),
     "espn_staging_create_ring": (ctypes.c_int, [_c_p, _c_i32, _c_i64, _c_i64]),
     "espn_prefetch": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p]),
+    "espn_prefetch_packed": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p]),
     "espn_rerank_staged": (ctypes.c_int, [_c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
                                           _c_p, _c_sz, _c_p]),
     "espn_staging_counters": (ctypes.c_int, [_c_p, _c_i32, _c_p, ctypes.POINTER(ctypes.c_uint64)]),
@@ -267,6 +268,16 @@ def espn_prefetch(table: Table, cand: torch.Tensor, slot: int, side_stream=None)
         raise ValueError("cand must be [B,K]")
     _check(lib().espn_prefetch(table.handle, _dev(cand, torch.int64, "cand"), cand.shape[0], cand.shape[1], slot,
                                _stream_ptr(side_stream)))
+
+
+def espn_prefetch_packed(table: Table, cand_host: torch.Tensor, slot: int, side_stream=None) -> None:
+    """The host-side engine: cand_host is a contiguous int64 CPU tensor [B,K]; blocks while it packs."""
+    if cand_host.dim() != 2:
+        raise ValueError("cand_host must be [B,K]")
+    if cand_host.is_cuda or cand_host.dtype != torch.int64 or not cand_host.is_contiguous():
+        raise ValueError("cand_host must be a contiguous int64 tensor in host memory")
+    _check(lib().espn_prefetch_packed(table.handle, cand_host.data_ptr(), cand_host.shape[0], cand_host.shape[1], slot,
+                                      _stream_ptr(side_stream)))
 
 
 def espn_rerank_staged(table: Table, slot: int, q: torch.Tensor, cand: torch.Tensor, k: int,

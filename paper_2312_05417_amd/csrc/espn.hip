@@ -8,6 +8,8 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <thread>
+#include <vector>
 
 #include "../../include/espn.h"
 #include "maxsim_kernels.h"
@@ -77,8 +79,23 @@ struct StagingSlot {
     hipEvent_t consumed = nullptr;         // recorded when a re-rank reading the slot has been enqueued
 };
 
+// Host side of the packing prefetch engine (espn_prefetch_packed), made on its first call.
+struct PackState {
+    void *buf[2] = {nullptr, nullptr};          // pinned, kPackBytes each: rows on their way to a slot
+    hipEvent_t sent[2] = {nullptr, nullptr};    // recorded after the copy out of buf[i] has been enqueued
+    bool in_flight[2] = {false, false};
+    int64_t *uniq = nullptr;                    // pinned, [capacity_docs]: distinct documents of the batch
+    int64_t *row0 = nullptr;                    // pinned, [capacity_docs]: first slot row of each
+    hipEvent_t lists_sent = nullptr;            // the copies out of uniq / row0 have been enqueued
+    bool lists_in_flight = false;
+    std::vector<uint64_t> seen;                 // one bit per document of the table
+};
+
 struct espn_table {
     const void *emb = nullptr;       // borrowed; the device-visible address if the table is in host memory
+    const uint8_t *emb_host = nullptr;   // borrowed; the host address of a host-resident table
+    int64_t *off_host = nullptr;     // owned copy of the offsets of a host-resident table, [n_docs + 1]
+    PackState *pack = nullptr;       // owned
     float *scale_dev = nullptr;      // owned, [n_docs] document scales of an E4M3 table, else nullptr
     int32_t elem_bytes = 2;          // 2: binary16 rows, 1: E4M3 codes
     int64_t *off_dev = nullptr;      // owned, [n_docs + 1]
@@ -176,6 +193,15 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
                         hipGetErrorString(he));
         }
         t->emb = dev_view;
+        t->emb_host = static_cast<const uint8_t *>(emb);
+    }
+    if (residency == ESPN_RESIDENT_HOST_PINNED) {
+        t->off_host = new (std::nothrow) int64_t[(size_t)n_docs + 1];
+        if (!t->off_host) {
+            delete t;
+            return fail(ESPN_ERR_NOMEM, "host allocation failed");
+        }
+        std::memcpy(t->off_host, offsets_host, sizeof(int64_t) * ((size_t)n_docs + 1));
     }
     t->n_docs = n_docs;
     t->total_rows = total;
@@ -202,6 +228,7 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
         (void)hipFree(t->off_dev);
         (void)hipFree(t->err_dev);
         (void)hipFree(t->scale_dev);
+        delete[] t->off_host;
         delete t;
         return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "table set-up failed: %s",
                     hipGetErrorString(e));
@@ -212,8 +239,24 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
 }  // namespace
 
 namespace {
+void free_pack_state(espn_table *t)
+{
+    PackState *p = t->pack;
+    if (!p) return;
+    for (int i = 0; i < 2; ++i) {
+        if (p->buf[i]) (void)hipHostFree(p->buf[i]);
+        if (p->sent[i]) (void)hipEventDestroy(p->sent[i]);
+    }
+    if (p->uniq) (void)hipHostFree(p->uniq);
+    if (p->row0) (void)hipHostFree(p->row0);
+    if (p->lists_sent) (void)hipEventDestroy(p->lists_sent);
+    delete p;
+    t->pack = nullptr;
+}
+
 void free_staging(espn_table *t)
 {
+    free_pack_state(t);                 // its lists are sized by the slots' capacity
     for (StagingSlot &s : t->slot) {
         (void)hipFree(s.rows);
         (void)hipFree(s.row_map);
@@ -239,6 +282,7 @@ ESPN_API int espn_table_free(espn_table *table)
     (void)hipFree(table->off_dev);
     (void)hipFree(table->err_dev);
     (void)hipFree(table->scale_dev);
+    delete[] table->off_host;
     delete table;
     return ESPN_OK;
 }
@@ -737,6 +781,171 @@ ESPN_API int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, in
                            static_cast<uint4 *>(s.rows), table->dim * table->elem_bytes / 16);
     }
     HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(s.ready, st));
+    return ESPN_OK;
+}
+
+namespace {
+constexpr size_t kPackBytes = (size_t)64 << 20;     // one pinned pack buffer
+constexpr int kPackThreads = 16;
+
+int make_pack_state(espn_table *t)
+{
+    if (t->pack) return ESPN_OK;
+    PackState *p = new (std::nothrow) PackState;
+    if (!p) return fail(ESPN_ERR_NOMEM, "host allocation failed");
+    t->pack = p;                        // freed with the staging slots whatever happens below
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+        e = hipHostMalloc(&p->buf[i], kPackBytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&p->sent[i], hipEventDisableTiming);
+    }
+    const size_t list_bytes = sizeof(int64_t) * (size_t)t->capacity_docs;
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&p->uniq), list_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&p->row0), list_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->lists_sent, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        free_pack_state(t);
+        (void)hipGetLastError();
+        return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "pack buffers: %s", hipGetErrorString(e));
+    }
+    try {
+        p->seen.assign(((size_t)t->n_docs + 63) / 64, 0);
+    } catch (const std::bad_alloc &) {
+        free_pack_state(t);
+        return fail(ESPN_ERR_NOMEM, "host allocation failed");
+    }
+    return ESPN_OK;
+}
+
+// Copies documents uniq[first .. last) of the table into `dst` back to back, on several threads.
+void pack_documents(const espn_table *t, const int64_t *uniq, int64_t first, int64_t last, uint8_t *dst)
+{
+    const size_t row_bytes = (size_t)t->dim * t->elem_bytes;
+    const int64_t n = last - first;
+    const int n_threads = (int)std::min<int64_t>(kPackThreads, std::max<int64_t>(1, n / 64));
+    // thread x takes documents [cut[x], cut[x + 1]); where its part starts in dst follows from the lengths
+    std::vector<int64_t> cut(n_threads + 1);
+    std::vector<size_t> at(n_threads + 1, 0);
+    for (int x = 0; x <= n_threads; ++x) cut[x] = first + n * x / n_threads;
+    for (int x = 0; x < n_threads; ++x) {
+        size_t bytes = 0;
+        for (int64_t u = cut[x]; u < cut[x + 1]; ++u) bytes += (size_t)(t->off_host[uniq[u] + 1] - t->off_host[uniq[u]]);
+        at[x + 1] = at[x] + bytes * row_bytes;
+    }
+    auto work = [&](int x) {
+        uint8_t *out = dst + at[x];
+        for (int64_t u = cut[x]; u < cut[x + 1]; ++u) {
+            const int64_t id = uniq[u];
+            const size_t bytes = (size_t)(t->off_host[id + 1] - t->off_host[id]) * row_bytes;
+            std::memcpy(out, t->emb_host + (size_t)t->off_host[id] * row_bytes, bytes);
+            out += bytes;
+        }
+    };
+    std::vector<std::thread> pool;
+    for (int x = 1; x < n_threads; ++x) pool.emplace_back(work, x);
+    work(0);
+    for (std::thread &th : pool) th.join();
+}
+}  // namespace
+
+ESPN_API int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, int32_t B, int32_t K, int32_t slot,
+                                  void *side_stream)
+{
+    if (int rc = check_slot(table, slot)) return rc;
+    if (B < 0 || K < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d: negative size", B, K);
+    if (B > 0 && K > 0 && !cand_host) return fail(ESPN_ERR_ARG, "cand_host is NULL");
+    if (!table->emb_host && table->total_rows > 0)
+        return fail(ESPN_ERR_UNSUPPORTED, "the packing engine reads the table on the host: the table is HBM-resident");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    if (int rc = make_pack_state(table)) return rc;
+    PackState &p = *table->pack;
+    hipStream_t st = static_cast<hipStream_t>(side_stream);
+    StagingSlot &s = table->slot[slot];
+    const int64_t *off = table->off_host;
+    const size_t row_bytes = (size_t)table->dim * table->elem_bytes;
+
+    // the lists of the previous call may still be on their way to the device
+    if (p.lists_in_flight) {
+        HIP_TRY(hipEventSynchronize(p.lists_sent));
+        p.lists_in_flight = false;
+    }
+    // distinct documents in order of first appearance, and the slot row each will start at
+    const int64_t n_pairs = (int64_t)B * K;
+    int64_t n_uniq = 0, rows = 0;
+    int status = ESPN_OK;
+    for (int64_t i = 0; i < n_pairs; ++i) {
+        const int64_t id = cand_host[i];
+        if (id < 0 || id >= table->n_docs) {
+            status = fail(ESPN_ERR_ID_RANGE, "candidate %lld of the batch is %lld, outside [0, %lld)", (long long)i,
+                          (long long)id, (long long)table->n_docs);
+            break;
+        }
+        uint64_t &word = p.seen[(size_t)id >> 6];
+        const uint64_t bit = 1ull << (id & 63);
+        if (word & bit) continue;
+        const int64_t len = off[id + 1] - off[id];
+        if ((size_t)len * row_bytes > kPackBytes) {
+            status = fail(ESPN_ERR_UNSUPPORTED, "document %lld holds %zu bytes, more than a pack buffer", (long long)id,
+                          (size_t)len * row_bytes);
+            break;
+        }
+        if (n_uniq >= table->capacity_docs || rows + len > table->capacity_rows) {
+            status = fail(ESPN_ERR_NOMEM, "the batch needs more than the %lld rows / %lld documents a staging slot holds",
+                          (long long)table->capacity_rows, (long long)table->capacity_docs);
+            break;
+        }
+        word |= bit;
+        p.uniq[n_uniq] = id;
+        p.row0[n_uniq] = rows;
+        ++n_uniq;
+        rows += len;
+    }
+    for (int64_t u = 0; u < n_uniq; ++u) p.seen[(size_t)p.uniq[u] >> 6] = 0;     // leave the bitmap clear
+    if (status != ESPN_OK) return status;                                         // nothing has been enqueued
+
+    // same ordering as espn_prefetch: after the last re-rank that read the slot, and after the last
+    // prefetch into every other slot (which may be reading this one)
+    HIP_TRY(hipStreamWaitEvent(st, s.consumed, 0));
+    for (int i = 0; i < table->n_slots; ++i)
+        if (i != slot) HIP_TRY(hipStreamWaitEvent(st, table->slot[i].ready, 0));
+    s.filled_at = ++table->prefetches;
+    const int64_t n_words = (table->n_docs + 31) / 32 + 1;
+    hipLaunchKernelGGL(espn::staging_clear_kernel, dim3((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024)),
+                       dim3(256), 0, st, s.bits, n_words, s.counters);
+    if (n_uniq > 0) {
+        HIP_TRY(hipMemcpyAsync(s.uniq, p.uniq, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemcpyAsync(s.other_row, p.row0, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipEventRecord(p.lists_sent, st));
+        p.lists_in_flight = true;
+        hipLaunchKernelGGL(espn::staging_publish_kernel, dim3((unsigned)((n_uniq + 255) / 256)), dim3(256), 0, st,
+                           s.uniq, s.other_row, n_uniq, (unsigned long long)rows, s.bits, s.row_map, s.counters);
+        HIP_TRY(hipGetLastError());
+    }
+    // rows: whole documents are packed into a pinned buffer while the previous buffer is on its way
+    int64_t u = 0;
+    int which = 0;
+    while (u < n_uniq) {
+        int64_t last = u;
+        size_t bytes = 0;
+        while (last < n_uniq) {
+            const size_t len = (size_t)(off[p.uniq[last] + 1] - off[p.uniq[last]]) * row_bytes;
+            if (bytes + len > kPackBytes) break;
+            bytes += len;
+            ++last;
+        }
+        if (p.in_flight[which]) HIP_TRY(hipEventSynchronize(p.sent[which]));      // the buffer is free again
+        pack_documents(table, p.uniq, u, last, static_cast<uint8_t *>(p.buf[which]));
+        if (bytes > 0) {
+            HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(s.rows) + (size_t)p.row0[u] * row_bytes, p.buf[which], bytes,
+                                   hipMemcpyHostToDevice, st));
+            HIP_TRY(hipEventRecord(p.sent[which], st));
+            p.in_flight[which] = true;
+        }
+        u = last;
+        which ^= 1;
+    }
     HIP_TRY(hipEventRecord(s.ready, st));
     return ESPN_OK;
 }

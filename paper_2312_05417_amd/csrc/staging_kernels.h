@@ -16,6 +16,11 @@
 //
 // The order of documents inside a slot depends on the order in which atomics land; nothing that is
 // computed from the slot depends on it.
+//
+// The other engine (espn_prefetch_packed) finds the distinct documents and packs their rows on the
+// host and sends them with plain copies; of the kernels here it uses clear and `publish`, which
+// writes the host's findings (distinct ids and the slot row each document starts at) into the
+// slot's bitmap and row map.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -108,6 +113,25 @@ __global__ __launch_bounds__(256) void staging_mark_kernel(
         row_map[id] = fits ? r0 : -1;
         if (!fits) atomicOr(err, ERR_STAGING_FULL);
         else if (from >= 0 && len > 0) atomicAdd(&counters[2], (unsigned long long)len);
+    }
+}
+
+// uniq[i] is a distinct document of the batch and row0[i] the slot row its rows were copied to
+__global__ void staging_publish_kernel(const int64_t *__restrict__ uniq, const int64_t *__restrict__ row0, int64_t n,
+                                       unsigned long long rows, unsigned *__restrict__ bits,
+                                       int64_t *__restrict__ row_map, unsigned long long *__restrict__ counters)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const int64_t id = uniq[i];
+        atomicOr(&bits[id >> 5], 1u << (id & 31));
+        row_map[id] = row0[i];
+    }
+    if (i == 0) {
+        counters[0] = (unsigned long long)n;
+        counters[1] = rows;
+        counters[2] = 0ull;         // nothing is taken from other slots
+        counters[3] = (unsigned long long)n;
     }
 }
 

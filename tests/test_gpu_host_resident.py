@@ -240,3 +240,113 @@ def test_slot_overflow_and_foreign_candidates_are_flagged_not_read():
     assert np.all(np.isneginf(g[~staged]))
     assert_scores_close(g[staged], o[staged], w.Q)
     table.free()
+
+
+@pytest.mark.parametrize("key,changes", [
+    ("c5", dict(n_docs=20_000, B=16, K=300)),                  # d=128, Zipf: heavy repeats across queries
+    ("c2", dict(n_docs=5_000, B=8, K=200, cand_law="zipf")),   # d=32
+    ("c1", dict(dim=40, n_docs=2_000, B=4, K=50)),             # generic kernel
+])
+def test_the_packing_engine_fills_a_slot_like_the_gather_engine(key, changes):
+    """espn_prefetch_packed (host finds the distinct documents, packs rows into pinned buffers, plain
+    copies) against the oracle, and bit for bit against a slot filled by espn_prefetch; the two
+    engines alternate in one pipeline on two streams."""
+    w = synth.scaled(synth.WORKLOADS[key], **changes)
+    say("packing engine %s d=%d N=%d B=%d K=%d" % (w.name, w.dim, w.n_docs, w.B, w.K))
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    espn.espn_staging_create(table, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    n_batches = 6
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    cands_h = [torch.from_numpy(c) for c in cands]
+    cands_d = [c.to(DEV) for c in cands_h]
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    qs_d = [x.to(DEV) for x in qs]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+
+    def prefetch(n):
+        if n % 3 == 2:                                       # every third batch through the GPU engine
+            espn.espn_prefetch(table, cands_d[n], n % 2, side)
+        else:
+            espn.espn_prefetch_packed(table, cands_h[n], n % 2, side)
+
+    outs = []
+    prefetch(0)
+    for n in range(n_batches):
+        if n + 1 < n_batches:
+            prefetch(n + 1)
+        outs.append(espn.espn_rerank_staged(table, n % 2, qs_d[n], cands_d[n], w.k, stream=main))
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    e = emb.numpy()
+    for n in range(n_batches):
+        ids, top, ws = outs[n]
+        o_ids, o_top, o_all = oracle.rerank(e, off, qs[n].numpy(), cands[n], w.k)
+        assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
+        for b in range(w.B):
+            assert_topk_matches(ids[b].cpu().numpy(), top[b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+    # the same batch through both engines: identical scores and ranks; the packing engine moves every
+    # distinct document over PCIe (it takes nothing from the other slot)
+    n = n_batches - 1
+    espn.espn_prefetch(table, cands_d[n], 0)
+    a_ids, a_top, a_ws = espn.espn_rerank_staged(table, 0, qs_d[n], cands_d[n], w.k)
+    a_scores = scores_of(a_ws, w.B, w.K)
+    espn.espn_prefetch_packed(table, cands_h[n], 1)
+    b_ids, b_top, b_ws = espn.espn_rerank_staged(table, 1, qs_d[n], cands_d[n], w.k)
+    assert np.array_equal(a_scores.view(np.int32), scores_of(b_ws, w.B, w.K).view(np.int32))
+    assert torch.equal(a_ids, b_ids) and torch.equal(a_top.view(torch.int32), b_top.view(torch.int32))
+    c = espn.espn_staging_counters(table, 1)
+    uniq = np.unique(cands[n])
+    rows = int((off[uniq + 1] - off[uniq]).sum())
+    assert c["distinct_docs"] == uniq.size and c["rows"] == rows and c["pcie_bytes"] == rows * w.dim * 2
+    espn.espn_table_check(table)
+    table.free()
+
+
+def test_the_packing_engine_reports_its_errors_before_enqueuing_anything():
+    w = synth.scaled(synth.WORKLOADS["c1"], n_docs=500, B=4, K=40)
+    say("packing engine: errors")
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    cand = synth.candidates(w)
+    cand_h = torch.from_numpy(cand)
+    q_d = synth.queries(w).to(DEV)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch_packed(table, cand_h, 0)          # no staging yet
+    assert ei.value.status == espn.ESPN_ERR_ARG
+    espn.espn_staging_create(table, capacity_rows=int(off[-1]), capacity_docs=500)
+    bad = cand_h.clone()
+    bad[2, 7] = 500                                          # one past the last document
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch_packed(table, bad, 0)
+    assert ei.value.status == espn.ESPN_ERR_ID_RANGE
+    bad[2, 7] = -1
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch_packed(table, bad, 0)
+    assert ei.value.status == espn.ESPN_ERR_ID_RANGE
+    with pytest.raises(ValueError):
+        espn.espn_prefetch_packed(table, cand_h.to(DEV), 0)  # a device tensor is not what it takes
+    # a refused call leaves the engine usable: the next one works and scores right
+    espn.espn_prefetch_packed(table, cand_h, 0)
+    ids, top, ws = espn.espn_rerank_staged(table, 0, q_d, cand_h.to(DEV), w.k)
+    o = oracle.scores(emb.numpy(), off, synth.queries(w).numpy(), cand)
+    assert_scores_close(scores_of(ws, w.B, w.K), o, w.Q)
+    espn.espn_table_check(table)
+    # a slot too small for the batch is refused on the host
+    espn.espn_staging_create(table, capacity_rows=600, capacity_docs=500)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch_packed(table, cand_h, 0)
+    assert ei.value.status == espn.ESPN_ERR_NOMEM
+    espn.espn_staging_create(table, capacity_rows=int(off[-1]), capacity_docs=3)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch_packed(table, cand_h, 0)
+    assert ei.value.status == espn.ESPN_ERR_NOMEM
+    table.free()
+    # an HBM-resident table has no host copy to pack from
+    emb_d, off2 = synth.table(w)
+    hbm = espn.espn_table_load(emb_d.to(DEV), off2)
+    espn.espn_staging_create(hbm, int(off2[-1]), w.n_docs)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch_packed(hbm, cand_h, 0)
+    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+    hbm.free()
