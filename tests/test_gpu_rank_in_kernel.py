@@ -65,6 +65,21 @@ def test_one_launch_path_below_four_workgroups_per_compute_unit(K, k):
         assert_topk_matches(g_ids[b], g_sc[b], o_all[n], cand[b], k, 32)
 
 
+@pytest.mark.parametrize("K,k", [(40, 10), (200, 200)])
+def test_one_launch_path_at_eight_workgroups_per_compute_unit(K, k):
+    """2100 single-slice queries of 256-byte binary16 rows: from eight workgroups per compute unit on,
+    these rows run in workgroups of 4 waves (of 8 below), here with the ranking in the same launch."""
+    B = 2100
+    say("one launch, 4-wave workgroups: d=128 B=%d K=%d k=%d" % (B, K, k))
+    emb, off, q, cand = random_problem(7 * K + 3, max(K, 300), 128, B, 32, K, 1, 40)
+    g_ids, g_sc, g_all = both_paths(emb, off, q, cand, k, expect_launches=1)
+    sample = sorted(set([0, 1, B // 2, B - 1] + list(range(11, B, 173))))
+    o_all = oracle.scores(emb, off, np.ascontiguousarray(q[sample]), np.ascontiguousarray(cand[sample]))
+    assert_scores_close(g_all[sample], o_all, 32)
+    for n, b in enumerate(sample):
+        assert_topk_matches(g_ids[b], g_sc[b], o_all[n], cand[b], k, 32)
+
+
 def test_longer_lists_take_two_launches():
     say("K = 257: two launches")
     emb, off, q, cand = random_problem(5, 400, 32, B_MANY, 32, 257, 1, 20)
