@@ -113,6 +113,7 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
  * An empty document scores -infinity (empty max).  An id outside [0, n_docs) scores
  * -infinity and raises the table's error flag (see espn_table_check); nothing is read for it.
  * B = 0 or K = 0 is a no-op.  The table must be HBM-resident (ESPN_ERR_UNSUPPORTED otherwise).
+ * One call takes up to 2^31 - 1 (query, candidate) pairs (ESPN_ERR_UNSUPPORTED beyond).
  * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
  */
 int espn_score(espn_table *table, const void *q, const int64_t *cand,

@@ -56,7 +56,6 @@ struct DeviceScope {
 };
 
 constexpr size_t kAlign = 256;
-constexpr int kMaxGridY = 65535;
 // Workgroups of the host-to-HBM copy kernel: 32 x 4 waves x 8 KiB = 1 MiB of reads in flight.  PCIe needs
 // about 64 GB/s x 5 us = 0.3 MiB to stay busy (measured: 8 workgroups reach 45 GB/s, 16 and more 56-57 GB/s),
 // and every host read that waits in the memory system's queues delays the HBM reads of the scoring kernel
@@ -306,7 +305,10 @@ int check_batch(const espn_table *table, const void *q, const int64_t *cand, int
     if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
     if (B < 0 || K < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d: negative size", B, K);
     if (Q < 1) return fail(ESPN_ERR_ARG, "Q = %d: a query needs at least one row", Q);
-    if (B > kMaxGridY) return fail(ESPN_ERR_UNSUPPORTED, "B = %d exceeds %d queries per call", B, kMaxGridY);
+    // one workgroup per candidate at most (the generic kernel: four candidates per workgroup), in a
+    // one-dimensional grid
+    if ((int64_t)B * std::max(K, 1) > (int64_t)0x7fffffff)
+        return fail(ESPN_ERR_UNSUPPORTED, "B * K = %lld exceeds 2^31 - 1 pairs per call", (long long)B * K);
     if (B > 0 && K > 0 && (!q || !cand)) return fail(ESPN_ERR_ARG, "q or cand is NULL");
     if (!aligned16(q)) return fail(ESPN_ERR_ARG, "q is not 16-byte aligned");
     return ESPN_OK;
@@ -370,19 +372,19 @@ void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, con
     constexpr int P = 4;                     // register pipeline depth in 16-row tiles
     if constexpr (D == 128 && EB == 2) {
         if (plan.waves == kNarrowWaves128) {
-            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves128, P, EB, RANK>), dim3(plan.slices, B),
+            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves128, P, EB, RANK>), dim3((unsigned)plan.slices * B),
                                dim3(kNarrowWaves128 * 64), 0, st, src, bt, scores, err, plan.slice, ro);
             return;
         }
     }
     if constexpr (D == 32) {
         if (plan.waves == kNarrowWaves) {
-            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves, P, EB, RANK>), dim3(plan.slices, B),
+            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves, P, EB, RANK>), dim3((unsigned)plan.slices * B),
                                dim3(kNarrowWaves * 64), 0, st, src, bt, scores, err, plan.slice, ro);
             return;
         }
     }
-    hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK>), dim3(plan.slices, B), dim3(WAVES * 64), 0,
+    hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK>), dim3((unsigned)plan.slices * B), dim3(WAVES * 64), 0,
                        st, src, bt, scores, err, plan.slice, ro);
 }
 
@@ -425,7 +427,7 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
         const size_t lds = (size_t)bt.Q * t->dim * 2;
         if (lds > 64 * 1024)
             return fail(ESPN_ERR_UNSUPPORTED, "Q * dim * 2 = %zu bytes exceeds the 64 KiB the generic kernel holds", lds);
-        const dim3 grid((bt.K + 3) / 4, B), block(256);
+        const dim3 grid((unsigned)((bt.K + 3) / 4) * B), block(256);
         hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim, bt, scores, t->err_dev);
     }
     HIP_TRY(hipGetLastError());
@@ -616,7 +618,7 @@ ESPN_API int espn_rerank_partial(espn_table *table, const void *q, const int64_t
     if (int rc = enqueue_rerank(table, hbm_source(table), bt, B, std::min(k, R), k, out_ids, out_scores, workspace, st))
         return rc;
     if (B > 0 && k > R) {
-        hipLaunchKernelGGL(espn::append_unranked_kernel, dim3((k - R + 255) / 256, B), dim3(256), 0, st, cand, K, R, k,
+        hipLaunchKernelGGL(espn::append_unranked_kernel, dim3(B, (k - R + 255) / 256), dim3(256), 0, st, cand, K, R, k,
                            out_ids, out_scores);
         HIP_TRY(hipGetLastError());
     }

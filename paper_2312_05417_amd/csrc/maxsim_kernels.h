@@ -274,7 +274,7 @@ struct RankLds {
 template <>
 struct RankLds<false> {};
 
-// grid = (slices, B), WAVES * 64 threads: workgroup (x, b) takes candidates x * slice .. of query b
+// grid = B * slices workgroups of WAVES * 64 threads: a workgroup takes one slice of one query's list
 template <int D, int WAVES, int P, int EB, bool RANK>
 __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err, int slice,
@@ -295,15 +295,17 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
     const int xor16 = (lane ^ 16) * 4, xor32 = (lane ^ 32) * 4;     // ds_bpermute addresses
-    // Workgroups are handed to the eight XCDs (each with an L2 of its own) in turn, by linear index.
-    // With a multiple of eight queries, the slices of a query are given linear indices that are
-    // equal modulo 8, so that they run on one XCD and share its copy of the query matrix.
-    int b = blockIdx.y, slice_index = blockIdx.x;
-    if ((gridDim.y & 7u) == 0u) {
-        const unsigned linear = blockIdx.x + gridDim.x * blockIdx.y;
-        const unsigned within = linear >> 3;                    // position among the XCD's workgroups
-        b = (int)((linear & 7u) + 8u * (within / gridDim.x));
-        slice_index = (int)(within % gridDim.x);
+    // A one-dimensional grid of B * slices workgroups (slices = workgroups per query).  Workgroups are
+    // handed to the eight XCDs (each with an L2 of its own) in turn, by linear index.  With a multiple of
+    // eight queries, the slices of a query are given linear indices that are equal modulo 8, so that they
+    // run on one XCD and share its copy of the query matrix.
+    const unsigned slices = (unsigned)((K + slice - 1) / slice);
+    const unsigned n_queries = gridDim.x / slices;
+    int b = (int)(blockIdx.x / slices), slice_index = (int)(blockIdx.x % slices);
+    if ((n_queries & 7u) == 0u) {
+        const unsigned within = blockIdx.x >> 3;                // position among the XCD's workgroups
+        b = (int)((blockIdx.x & 7u) + 8u * (within / slices));
+        slice_index = (int)(within % slices);
     }
     const int j_begin = slice_index * slice;
     const int n = min(slice, K - j_begin);  // >= 1 by construction of the grid
@@ -482,7 +484,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     }
 
     if constexpr (RANK) {
-        // gridDim.x == 1 and n <= RANK_MAX <= blockDim.x: the slice is the query's whole list.
+        // one slice per query and n <= RANK_MAX <= blockDim.x: the slice is the query's whole list.
         // Order: score descending, id ascending, position ascending; NaN scores (key 0) are never
         // ranked.  An entry's rank is the number of entries ahead of it.  The threads form a
         // (entries x parts) grid: thread (e, part) compares entry e with the part-th share of the
@@ -558,13 +560,14 @@ __global__ __launch_bounds__(256) void maxsim_generic_kernel(
     extern __shared__ uint4 q_lds[];         // [Q][D/8] chunks of 8 binary16
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int b = blockIdx.y;
+    const unsigned per_query = (unsigned)((K + 3) / 4);     // one-dimensional grid: B * ceil(K / 4) workgroups
+    const int b = (int)(blockIdx.x / per_query);
     const int chunks = D / 8;
     const uint4 *qsrc = reinterpret_cast<const uint4 *>(q + (size_t)b * Q * D);
     for (int x = threadIdx.x; x < Q * chunks; x += blockDim.x) q_lds[x] = qsrc[x];
     __syncthreads();
 
-    const int j = blockIdx.x * 4 + wave;
+    const int j = (int)(blockIdx.x % per_query) * 4 + wave;
     if (j >= K) return;
     int64_t s0;
     int t;

@@ -474,8 +474,8 @@ __global__ __launch_bounds__(T) void topk_sort_kernel(
 __global__ void append_unranked_kernel(const int64_t *__restrict__ cand, int ldc, int R, int k,
                                        int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
 {
-    const int b = blockIdx.y;
-    const int j = R + blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = blockIdx.x;                                   // grid = (B, chunks of 256 ranks)
+    const int j = R + blockIdx.y * blockDim.x + threadIdx.x;
     if (j < k) {
         out_ids[(size_t)b * k + j] = cand[(size_t)b * ldc + j];
         out_scores[(size_t)b * k + j] = quiet_nan();

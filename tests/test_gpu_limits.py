@@ -16,21 +16,25 @@ def say(msg):
     print("[case] " + msg, flush=True)
 
 
-def test_largest_batch_and_one_beyond():
-    B, K, k = 65535, 3, 2
-    say("B = %d (the most queries one call takes), K = %d" % (B, K))
-    emb, off, q1, _ = random_problem(9, 500, 32, 1, 32, K, 1, 20)
+@pytest.mark.parametrize("d,B", [(32, 65535), (32, 70003), (128, 66000), (40, 70003)])
+def test_very_many_queries_in_one_call(d, B):
+    """More queries than a grid dimension other than the first can count (65535): the grids are
+    one-dimensional.  d = 40 takes the plain-ALU kernel."""
+    K, k = 3, 2
+    say("B = %d, K = %d, d = %d" % (B, K, d))
+    emb, off, q1, _ = random_problem(9, 500, d, 1, 32, K, 1, 20)
     rng = np.random.default_rng(4)
     cand = rng.integers(0, 500, size=(B, K)).astype(np.int64)
     # a few distinct queries, repeated: the expected scores of every query are then cheap to get
-    q_few = random_problem(10, 10, 32, 7, 32, 1, 1, 2)[2]
+    q_few = random_problem(10, 10, d, 7, 32, 1, 1, 2)[2]
     q = np.ascontiguousarray(q_few[np.arange(B) % 7])
     emb_d, q_d, cand_d = torch.from_numpy(emb).to(DEV), torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
     table = espn.espn_table_load(emb_d, off)
     g_all = espn.espn_score(table, q_d, cand_d)
     g_ids, g_sc = espn.espn_rerank(table, q_d, cand_d, k)
+    p_ids, p_sc = espn.espn_rerank_partial(table, q_d, cand_d, 2, 3)       # two ranked, the third appended
     espn.espn_table_check(table)
-    sample = np.array([0, 1, 6, 7, 32767, 65533, 65534])
+    sample = np.array([0, 1, 6, 7, 32767, 65533, 65534, B - 2, B - 1])
     o_all = oracle.scores(emb, off, np.ascontiguousarray(q[sample]), np.ascontiguousarray(cand[sample]))
     assert_scores_close(g_all[sample].cpu().numpy(), o_all, 32)
     for n, b in enumerate(sample):
@@ -38,12 +42,22 @@ def test_largest_batch_and_one_beyond():
     # every query against the two-launch path
     t_ids, t_sc = espn.espn_topk(g_all, cand_d, k)
     assert torch.equal(g_ids, t_ids) and torch.equal(g_sc.view(torch.int32), t_sc.view(torch.int32))
-    # one query more is refused before anything is launched
-    q_big = torch.zeros((B + 1, 32, 32), dtype=torch.float16, device=DEV)
-    c_big = torch.zeros((B + 1, K), dtype=torch.int64, device=DEV)
-    with pytest.raises(espn.EspnError) as err:
-        espn.espn_score(table, q_big, c_big)
-    assert err.value.status == espn.ESPN_ERR_UNSUPPORTED
+    # partial re-ranking: the appended rank is the third candidate of every list, unscored
+    assert torch.equal(p_ids[:, 2], cand_d[:, 2]) and bool(torch.isnan(p_sc[:, 2]).all())
+    h_ids, h_sc = espn.espn_topk(g_all[:, :2].contiguous(), cand_d[:, :2].contiguous(), 2)
+    assert torch.equal(p_ids[:, :2], h_ids) and torch.equal(p_sc[:, :2].view(torch.int32), h_sc.view(torch.int32))
+    table.free()
+
+
+def test_more_pairs_than_a_grid_can_count_are_refused():
+    """B * K beyond 2^31 - 1 is refused before anything is launched (the pointers are never read)."""
+    emb, off, q1, _ = random_problem(9, 50, 32, 1, 32, 1, 1, 5)
+    table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
+    B, K = 70000, 40000
+    lib = espn.lib()
+    dummy = torch.zeros(16, dtype=torch.int64, device=DEV)
+    rc = lib.espn_score(table.handle, dummy.data_ptr(), dummy.data_ptr(), B, 32, K, dummy.data_ptr(), None)
+    assert rc == espn.ESPN_ERR_UNSUPPORTED, espn.last_error()
     table.free()
 
 
