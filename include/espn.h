@@ -108,8 +108,8 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
  *   q       [B, Q, dim] binary16, DEVICE, 16-byte aligned.
  *   cand    [B, K] int64 document ids, DEVICE.
  *   scores  [B, K] binary32, DEVICE, written.
- *   Q       1 .. 32 on the matrix-core kernel; the generic kernel takes any Q with
- *           Q * dim * 2 bytes <= 64 KiB.
+ *   Q       1 .. 64 on the matrix-core kernel (1 .. 32 for rows of more than 128 components); the
+ *           generic kernel takes any Q with Q * dim * 2 bytes <= 64 KiB.
  * An empty document scores -infinity (empty max).  An id outside [0, n_docs) scores
  * -infinity and raises the table's error flag (see espn_table_check); nothing is read for it.
  * B = 0 or K = 0 is a no-op.  The table must be HBM-resident (ESPN_ERR_UNSUPPORTED otherwise).

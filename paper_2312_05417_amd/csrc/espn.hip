@@ -360,43 +360,62 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     const int64_t workgroups = (int64_t)B * p.slices;
     p.waves = waves;
     if (t->dim == 32 && workgroups >= 4 * (int64_t)t->n_cu) p.waves = kNarrowWaves;
-    if (t->dim == 128 && t->elem_bytes == 2 && workgroups >= 8 * (int64_t)t->n_cu) p.waves = kNarrowWaves128;
+    if (t->dim == 128 && t->elem_bytes == 2 && workgroups >= 8 * (int64_t)t->n_cu) p.waves = kNarrowWaves128;     // Q <= 32 only
     return p;
 }
 
-template <int D, int EB, bool RANK>
+// QG = groups of 16 query rows the kernel holds in registers: 2 (Q <= 32) or 4 (Q <= 64, rows up to 256 bytes)
+template <int D, int EB, bool RANK, int QG>
 void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
                    float *scores, const espn::RankOut &ro, hipStream_t st)
 {
-    constexpr int WAVES = waves_per_workgroup(D);
+    // 64 query rows of 192 or 256 bytes take 122-154 VGPRs per lane: in workgroups of 4 waves three of them
+    // share a compute unit, in workgroups of 8 only one would fit
+    constexpr int WAVES = (QG == 4 && D > 64) ? 4 : waves_per_workgroup(D);
     constexpr int P = 4;                     // register pipeline depth in 16-row tiles
-    if constexpr (D == 128 && EB == 2) {
+    const dim3 grid((unsigned)plan.slices * B);
+    if constexpr (D == 128 && EB == 2 && QG == 2) {
         if (plan.waves == kNarrowWaves128) {
-            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves128, P, EB, RANK>), dim3((unsigned)plan.slices * B),
+            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves128, P, EB, RANK, QG>), grid,
                                dim3(kNarrowWaves128 * 64), 0, st, src, bt, scores, err, plan.slice, ro);
             return;
         }
     }
     if constexpr (D == 32) {
         if (plan.waves == kNarrowWaves) {
-            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves, P, EB, RANK>), dim3((unsigned)plan.slices * B),
+            hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves, P, EB, RANK, QG>), grid,
                                dim3(kNarrowWaves * 64), 0, st, src, bt, scores, err, plan.slice, ro);
             return;
         }
     }
-    hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK>), dim3((unsigned)plan.slices * B), dim3(WAVES * 64), 0,
-                       st, src, bt, scores, err, plan.slice, ro);
+    hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK, QG>), grid, dim3(WAVES * 64), 0, st, src, bt,
+                       scores, err, plan.slice, ro);
 }
+
+// rows longer than 256 bytes are held for 32 query rows only (their fragments would not fit the registers)
+constexpr bool takes_long_queries(int D) { return D <= 128; }
 
 template <int D, int EB>
 void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
                    float *scores, const espn::RankOut &ro, hipStream_t st)
 {
-    if (plan.rank) launch_slices<D, EB, true>(src, bt, B, plan, err, scores, ro, st);
-    else launch_slices<D, EB, false>(src, bt, B, plan, err, scores, ro, st);
+    if constexpr (takes_long_queries(D)) {
+        if (bt.Q > 32) {
+            if (plan.rank) launch_slices<D, EB, true, 4>(src, bt, B, plan, err, scores, ro, st);
+            else launch_slices<D, EB, false, 4>(src, bt, B, plan, err, scores, ro, st);
+            return;
+        }
+    }
+    if (plan.rank) launch_slices<D, EB, true, 2>(src, bt, B, plan, err, scores, ro, st);
+    else launch_slices<D, EB, false, 2>(src, bt, B, plan, err, scores, ro, st);
 }
 
-bool on_matrix_cores(const espn_table *t, int Q) { return t->dim % 32 == 0 && t->dim <= 256 && Q <= 32; }
+// 16-row query groups in registers: up to 32 query rows for every row length that is a multiple of 32
+// up to 256 components, up to 64 for rows of up to 128 components
+bool on_matrix_cores(const espn_table *t, int Q)
+{
+    return t->dim % 32 == 0 && t->dim <= 256 && (Q <= 32 || (Q <= 64 && takes_long_queries(t->dim)));
+}
 
 // Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot).
 // plan.rank: the kernel also writes the ranked top-k described by `ro`.
@@ -405,8 +424,8 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
 {
     using namespace espn;
     if (B == 0 || bt.K == 0) return ESPN_OK;
-    if (t->elem_bytes == 1 && bt.Q > 32)
-        return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables take at most 32 query rows, got %d", bt.Q);
+    if (t->elem_bytes == 1 && bt.Q > 64)
+        return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables take at most 64 query rows, got %d", bt.Q);
     if (on_matrix_cores(t, bt.Q)) {
         if (t->elem_bytes == 1) {
             if (t->dim == 32) launch_slices<32, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);

@@ -275,13 +275,13 @@ template <>
 struct RankLds<false> {};
 
 // grid = B * slices workgroups of WAVES * 64 threads: a workgroup takes one slice of one query's list
-template <int D, int WAVES, int P, int EB, bool RANK>
+template <int D, int WAVES, int P, int EB, bool RANK, int QG = 2>
 __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err, int slice,
     const RankOut ro)
 {
     static_assert(D % 32 == 0 && D >= 32 && D <= 256 && (EB == 2 || D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 &&
-                      P >= 1, "unsupported shape");
+                      P >= 1 && (QG == 2 || (QG == 4 && D <= 128)), "unsupported shape");
     __shared__ int64_t s_row0[MAX_SLICE];
     __shared__ int s_ntok[MAX_SLICE];
     __shared__ float s_scale[EB == 1 ? MAX_SLICE : 1];
@@ -359,10 +359,10 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         if (threadIdx.x < RANK_MAX) s_rank.count[threadIdx.x] = 0u;
     }
 
-    // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h
-    half8 qf[2][KS];
+    // query fragments: qf[h][s] = components 8*(KS*c+s) .. +7 of query row r + 16h (QG groups of 16 rows)
+    half8 qf[QG][KS];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < QG; ++h) {
         const int nq = r + 16 * h;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -430,7 +430,9 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
             ld_advance();
         }
 
-        float m0 = neg_inf(), m1 = neg_inf();
+        float m[QG];
+#pragma unroll
+        for (int h = 0; h < QG; ++h) m[h] = neg_inf();
         while (!cs.done) {
 #pragma unroll
             for (int p = 0; p < P; ++p) {
@@ -449,22 +451,31 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 #pragma unroll
                         for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&buf[p].w[2 * EB * s]);
                     }
-                    floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+                    floatx4 acc[QG];
+#pragma unroll
+                    for (int h = 0; h < QG; ++h) acc[h] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s = 0; s < KS; ++s) {
-                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[0][s], acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[1][s], acc1, 0, 0, 0);
+#pragma unroll
+                        for (int h = 0; h < QG; ++h)
+                            acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[h][s], acc[h], 0, 0, 0);
                     }
-                    m0 = max_into(m0, acc0);
-                    m1 = max_into(m1, acc1);
+#pragma unroll
+                    for (int h = 0; h < QG; ++h) m[h] = max_into(m[h], acc[h]);
                     if (cs.last_tile()) {
                         // max over the four row groups (lanes l, l^16, l^32, l^48 hold the same query row)
-                        m0 = max3(m0, from_lane(xor16, m0), m0);
-                        m1 = max3(m1, from_lane(xor16, m1), m1);
-                        m0 = max3(m0, from_lane(xor32, m0), m0);
-                        m1 = max3(m1, from_lane(xor32, m1), m1);
-                        // sum over the 32 query rows: rows r and r+16 in-lane, then across the 16 lanes
-                        float sum = row16_sum(m0 + m1);
+#pragma unroll
+                        for (int h = 0; h < QG; ++h) {
+                            m[h] = max3(m[h], from_lane(xor16, m[h]), m[h]);
+                            m[h] = max3(m[h], from_lane(xor32, m[h]), m[h]);
+                        }
+                        // sum over the query rows: rows r, r+16, ... in-lane, then across the 16 lanes
+                        float in_lane = m[0];
+#pragma unroll
+                        for (int h = 1; h < QG; ++h) in_lane += m[h];
+                        float sum = row16_sum(in_lane);
+#pragma unroll
+                        for (int h = 0; h < QG; ++h) m[h] = neg_inf();
                         // one positive scale per document: max and sum commute with it
                         if constexpr (EB == 1) sum *= s_scale[cs.idx];
                         if (lane == 0) {
@@ -472,8 +483,6 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                             scores[(size_t)b * K + j_begin + cs.idx] = total;
                             if constexpr (RANK) s_rank.key[cs.idx] = order_key(total);
                         }
-                        m0 = neg_inf();
-                        m1 = neg_inf();
                     }
                     cs_advance();
                 }

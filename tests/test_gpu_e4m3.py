@@ -71,7 +71,7 @@ def test_compressed_workloads_match_the_oracle(key, changes):
     assert np.abs(o_all - plain).max() < 0.6 and np.corrcoef(o_all.ravel(), plain.ravel())[0, 1] > 0.98
 
 
-@pytest.mark.parametrize("d,Q", [(32, 1), (32, 17), (128, 7), (128, 32)])
+@pytest.mark.parametrize("d,Q", [(32, 1), (32, 17), (128, 7), (128, 32), (32, 33), (32, 64), (128, 48), (128, 64)])
 def test_ragged_documents_scales_and_empty_documents(d, Q):
     say("E4M3 ragged d=%d Q=%d" % (d, Q))
     rng = np.random.default_rng(d + Q)

@@ -103,7 +103,9 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t32, 1024, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
     # shapes the matrix-core kernel does not take: one wave per candidate, a second launch ranks
     assert espn.espn_rerank_plan(t72, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
-    assert espn.espn_rerank_plan(t32, 5, 40, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 5, 65, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
+    # up to 64 query rows run on the matrix cores
+    assert espn.espn_rerank_plan(t32, 5, 64, 40, 3) == espn.espn_rerank_plan(t32, 5, 32, 40, 3)
     assert espn.espn_rerank_plan(t32, 0, 32, 40, 3) == {"slices": 0, "slice": 0, "launches": 0}
     with pytest.raises(espn.EspnError):
         espn.espn_rerank_plan(t32, 4, 32, 10, 11)

@@ -74,7 +74,7 @@ def test_c1_tiny_every_pair():
 
 
 @pytest.mark.parametrize("d", [32, 128])
-@pytest.mark.parametrize("Q", [1, 7, 16, 17, 32])
+@pytest.mark.parametrize("Q", [1, 7, 16, 17, 32, 33, 47, 48, 49, 64])
 def test_query_lengths_and_ragged_documents(d, Q):
     # token counts straddle the 16-row tile: 1, 15, 16, 17, 31, 32, 33 ... and up to 180
     counts = np.array([1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 100, 127, 128, 129, 179, 180] * 8)
@@ -97,17 +97,18 @@ def test_candidate_count_shapes(K, k):
     run_both(emb, off, q, cand, k)
 
 
-@pytest.mark.parametrize("d,Q", [(8, 4), (40, 32), (72, 5), (32, 40), (128, 33), (264, 16)])
+@pytest.mark.parametrize("d,Q", [(8, 4), (40, 32), (72, 5), (32, 65), (128, 100), (160, 33), (264, 16)])
 def test_generic_kernel_shapes(d, Q):
     say("generic d=%d Q=%d" % (d, Q))
     emb, off, q, cand = random_problem(d + Q, 200, d, 2, Q, 61, 0, 70)
     run_both(emb, off, q, cand, 9)
 
 
-@pytest.mark.parametrize("d", [64, 96, 160, 192, 224, 256])
-@pytest.mark.parametrize("Q", [5, 32])
+@pytest.mark.parametrize("d,Q", [(d, Q) for d in (64, 96, 160, 192, 224, 256) for Q in (5, 32)] +
+                         [(64, 33), (64, 64), (96, 50), (96, 64)])
 def test_other_row_lengths_on_the_matrix_cores(d, Q):
-    # every multiple of 32 up to 256 takes the matrix-core kernel; lengths straddle the 16-row tile
+    # every multiple of 32 up to 256 takes the matrix-core kernel (up to 64 query rows for rows of up to 128
+    # components, 32 beyond); lengths straddle the 16-row tile
     counts = np.array([0, 1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 100, 127, 128, 129, 180] * 6)
     say("matrix cores d=%d Q=%d" % (d, Q))
     emb, off, q, cand = random_problem(3 * d + Q, counts.size, d, 3, Q, 117, 0, 0, counts=counts)
