@@ -71,6 +71,34 @@ def test_random_shape(seed):
     table.free()
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shape_with_long_queries(seed):
+    """The same shapes with 33 to 64 query rows (rows of up to 128 components keep them on the matrix cores, 192
+    sends them to the plain-ALU kernel)."""
+    d, _, B, K, k, N, emb, off, _, cand = draw_case(200 + seed)
+    rng = np.random.default_rng(5000 + seed)
+    Q = int(rng.choice([33, 40, 47, 48, 49, 63, 64]))
+    B = min(B, 40)
+    cand = np.ascontiguousarray(cand[:B])
+    q = (rng.normal(size=(B, Q, d)) * rng.choice([0.1, 1.0, 3.0])).astype(np.float16)
+    say("long query, seed %d: d=%d Q=%d B=%d K=%d k=%d N=%d rows=%d" % (seed, d, Q, B, K, k, N, emb.shape[0]))
+    emb_d = torch.from_numpy(emb).to(DEV) if emb.shape[0] else torch.zeros((0, d), dtype=torch.float16, device=DEV)
+    q_d, cand_d = torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
+    table = espn.espn_table_load(emb_d, off)
+    g_all = espn.espn_score(table, q_d, cand_d)
+    g_ids, g_top = espn.espn_rerank(table, q_d, cand_d, k)
+    espn.espn_table_check(table)
+    t_ids, t_top = espn.espn_topk(g_all, cand_d, k)
+    assert torch.equal(g_ids, t_ids) and torch.equal(g_top.view(torch.int32), t_top.view(torch.int32))
+    o_all = oracle.scores(emb, off, q, cand)
+    floor = cancellation_floor(oracle.scores(np.abs(emb), off, np.abs(q), cand), d, Q)
+    assert_scores_close(g_all.cpu().numpy(), o_all, Q, floor=floor)
+    ids, top = g_ids.cpu().numpy(), g_top.cpu().numpy()
+    for b in sorted(set([0, B // 2, B - 1])):
+        assert_topk_matches(ids[b], top[b], o_all[b], cand[b], k, Q, floor=floor[b])
+    table.free()
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_shape_compressed(seed):
     d, Q, B, K, k, N, emb, off, q, cand = draw_case(100 + seed)
