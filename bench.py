@@ -30,10 +30,10 @@ DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p
 # (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
 MEASURED_TRAFFIC_BYTES = {
     # (FETCH_SIZE KiB x 2.0 calibration + WRITE_SIZE KiB x 1.0) x 1024, MaxSim kernel, per launch
-    "c2": (88958.03 * 2.0 + 252.54) * 1024,          # profiles/maxsim_d32_c2_pmc.md
-    "c3": (2261332.18 * 2.0 + 2310.83) * 1024,       # profiles/maxsim_d128_c3_pmc.md
-    "c3e4m3": (1148700.57 * 2.0 + 1401.23) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
-    "c4": (17567425.37 * 2.0 + 19670.05) * 1024,     # profiles/maxsim_d128_c4_pmc.md
+    "c2": (88965.12 * 2.0 + 252.42) * 1024,          # profiles/maxsim_d32_c2_pmc.md
+    "c3": (2261199.31 * 2.0 + 2302.28) * 1024,       # profiles/maxsim_d128_c3_pmc.md
+    "c3e4m3": (1148644.78 * 2.0 + 1394.73) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
+    "c4": (17564741.61 * 2.0 + 19769.98) * 1024,     # profiles/maxsim_d128_c4_pmc.md
 }
 
 
