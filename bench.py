@@ -507,8 +507,34 @@ def main():
         two_stream_wall = time.perf_counter() - t0
         espn.espn_table_check(table)
 
+    # ---- a measuring stick: a plain contiguous read (nothing depends on what is read) of as many bytes as one
+    # launch of the scoring kernel reads, over successive windows of the table (the last-level cache never holds
+    # the window that comes next), `steps` launches back to back, timed like the scoring kernel
+    window = min(int(launch_bytes) // 4096 * 4096, emb.numel() * elem_bytes // 4096 * 4096)
+    flat = emb.view(torch.uint8).view(-1)
+    n_windows = max(1, min(64, flat.numel() // window))
+    sink = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def plain_read(i):
+        o = (i % n_windows) * window
+        rc = lib.espn_stream_read_probe(flat.data_ptr() + o, window, sink.data_ptr(), st)
+        if rc != 0:
+            raise RuntimeError("read probe failed: " + espn.last_error())
+
+    for i in range(min(warmup, 8)):
+        plain_read(i)
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    p0.record(stream)
+    for i in range(steps):
+        plain_read(i)
+    p1.record(stream)
+    torch.cuda.synchronize()
+    plain_read_gbs = window / (p0.elapsed_time(p1) / steps * 1e-3) / 1e9
+
     kern_avg_ms = path_ms if plan["launches"] == 1 else score_only_ms
     achieved = launch_bytes / (kern_avg_ms * 1e-3) / 1e9
+    log("plain read of %.1f MB windows: %.1f GB/s (%d windows)" % (window / 1e6, plain_read_gbs, n_windows))
     log("wall %.4f ms/step (%d launch(es), %d slice(s) of %d per query); MaxSim kernel avg %.4f ms = %.1f GB/s "
         "algorithmic; scoring without ranking %.4f ms; score + stand-alone ranking %s ms" % (
             ms_per_step, plan["launches"], plan["slices"], plan["slice"], kern_avg_ms, achieved, score_only_ms,
@@ -554,6 +580,7 @@ def main():
             "whole_path_ms_by_events": path_ms, "scoring_without_ranking_ms": score_only_ms,
             "score_then_standalone_ranking_ms": two_launch_ms,
             "mfma_tflops": flops / (kern_avg_ms * 1e-3) / 1e12,
+            "plain_read_same_bytes_gbs": plain_read_gbs, "achieved_over_plain_read": achieved / plain_read_gbs,
         },
     }
 

@@ -213,6 +213,18 @@ int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_t ka,
 double espn_batch_threshold(double bandwidth_bytes_per_s, double budget_s, double bytes_per_query);
 
 /*
+ * A measuring stick, not a step of the method: read `bytes` bytes starting at `src` once, contiguously,
+ * with nothing that depends on what is read (16 bytes per lane, non-temporal loads, every workgroup
+ * walks its own contiguous part: the fastest plain read found on this machine).  bench.py times it over windows of the table as large as one batch's reads, as the
+ * rate a dependency-free kernel reaches on the same machine next to the gather + MaxSim kernel (whose
+ * reads hang on two dependent look-ups per document, Sec. 4).
+ *   src    DEVICE (or device-visible pinned HOST) memory, 16-byte aligned; bytes a multiple of 16.
+ *   sink   DEVICE, 8 bytes, written only if the xor of everything read is all ones (keeps the loads alive).
+ * Errors: ARG, HIP.
+ */
+int espn_stream_read_probe(const void *src, size_t bytes, uint64_t *sink, void *stream);
+
+/*
  * Wait for `stream` and report errors kernels recorded for this table since the last check:
  * returns ESPN_ERR_ID_RANGE if any candidate id was out of range, else ESPN_OK; clears the flag.
  */

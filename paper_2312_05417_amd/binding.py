@@ -42,6 +42,7 @@ SIGNATURES = {
                                          _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "espn_merge_topk": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
     "espn_batch_threshold": (ctypes.c_double, [ctypes.c_double, ctypes.c_double, ctypes.c_double]),
+    "espn_stream_read_probe": (ctypes.c_int, [_c_p, _c_sz, _c_p, _c_p]),
     "espn_table_check": (ctypes.c_int, [_c_p, _c_p]),
     "espn_staging_create": (ctypes.c_int, [_c_p, _c_i64, _c_i64]),
     "espn_staging_create_ring": (ctypes.c_int, [_c_p, _c_i32, _c_i64, _c_i64]),
@@ -362,6 +363,14 @@ def espn_merge_topk(ids_a: torch.Tensor, scores_a: torch.Tensor, ids_b: torch.Te
                                  _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
                                  _stream_ptr(stream)))
     return out_ids, out_scores
+
+
+def espn_stream_read_probe(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Enqueue one plain read of all of `src` (a contiguous tensor); sink: an int64 device tensor of one element."""
+    if not src.is_contiguous():
+        raise ValueError("src must be contiguous")
+    _check(lib().espn_stream_read_probe(src.data_ptr(), src.numel() * src.element_size(), _dev(sink, torch.int64, "sink"),
+                                        _stream_ptr(stream)))
 
 
 def espn_batch_threshold(bandwidth_bytes_per_s: float, budget_s: float, bytes_per_query: float) -> float:

@@ -686,6 +686,24 @@ ESPN_API double espn_batch_threshold(double bandwidth_bytes_per_s, double budget
     return bandwidth_bytes_per_s * budget_s / bytes_per_query;
 }
 
+ESPN_API int espn_stream_read_probe(const void *src, size_t bytes, uint64_t *sink, void *stream)
+{
+    if (bytes == 0) return ESPN_OK;
+    if (!src || !sink) return fail(ESPN_ERR_ARG, "NULL pointer");
+    if (!aligned16(src) || bytes % 16 != 0) return fail(ESPN_ERR_ARG, "src and bytes must be multiples of 16");
+    int dev = 0, n_cu = 256;
+    HIP_TRY(hipGetDevice(&dev));
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
+    const size_t n = bytes / 16;
+    // eight workgroups per compute unit, each at least one full round of its 256 lanes' 8 loads
+    const size_t blocks = std::max<size_t>(1, std::min<size_t>((size_t)n_cu * 8, n / (8 * 256)));
+    const size_t per = (n + blocks - 1) / blocks;
+    hipLaunchKernelGGL(espn::stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const espn::uint4v *>(src), n, per, reinterpret_cast<unsigned long long *>(sink));
+    HIP_TRY(hipGetLastError());
+    return ESPN_OK;
+}
+
 ESPN_API int espn_table_check(espn_table *table, void *stream)
 {
     if (!table) return fail(ESPN_ERR_ARG, "table is NULL");

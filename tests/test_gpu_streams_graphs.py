@@ -87,3 +87,23 @@ def test_two_tables_and_two_streams_do_not_disturb_each_other():
         assert torch.equal(b[0], ref_b[0]) and torch.equal(b[1], ref_b[1])
     ta.free()
     tb.free()
+
+
+def test_read_probe_reads_whatever_it_is_given_and_stores_nothing():
+    """The measuring stick of the benchmark: any 16-byte-multiple size, sizes smaller than one round of a
+    workgroup included; its sink is written only if the xor of everything read is all ones."""
+    say("read probe")
+    buf = torch.arange(0, 1 << 22, dtype=torch.int32, device=DEV)              # 16 MiB, xor of the words is 0
+    sink = torch.full((1,), 7, dtype=torch.int64, device=DEV)
+    for n_words in (4, 8, 1 << 10, (1 << 22) - 4, 1 << 22):
+        espn.espn_stream_read_probe(buf[:n_words], sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 7
+    ones = torch.full((4,), -1, dtype=torch.int32, device=DEV)                 # one chunk of all ones: stored
+    espn.espn_stream_read_probe(ones, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == -1
+    with pytest.raises(espn.EspnError):
+        espn.espn_stream_read_probe(buf[:3], sink)                             # 12 bytes
+    with pytest.raises(espn.EspnError):
+        espn.espn_stream_read_probe(buf[1:5], sink)                            # not 16-byte aligned
