@@ -31,8 +31,8 @@ DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p
 MEASURED_TRAFFIC_BYTES = {
     # (FETCH_SIZE KiB x 2.0 calibration + WRITE_SIZE KiB x 1.0) x 1024, MaxSim kernel, per launch
     "c2": (88965.12 * 2.0 + 252.42) * 1024,          # profiles/maxsim_d32_c2_pmc.md
-    "c3": (2261199.31 * 2.0 + 2302.28) * 1024,       # profiles/maxsim_d128_c3_pmc.md
-    "c3e4m3": (1148644.78 * 2.0 + 1394.73) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
+    "c3": (2262175.08 * 2.0 + 1173.36) * 1024,       # profiles/maxsim_d128_c3_pmc.md
+    "c3e4m3": (1161113.45 * 2.0 + 1056.75) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
     "c4": (17564741.61 * 2.0 + 19769.98) * 1024,     # profiles/maxsim_d128_c4_pmc.md
 }
 
@@ -356,7 +356,12 @@ def main():
     # steps still run at the clocks of an idle device (measured on c2: 38.3 us per step after 40 warm-up steps,
     # 37.4 us after 400 or 2000)
     short_steps = args.workload in ("c1", "c2", "c2p64", "c2e4m3")
-    warmup = args.warmup if args.warmup is not None else (steps if short_steps else max(3, steps // 10))
+    if args.warmup is not None:
+        warmup = args.warmup
+    elif short_steps:
+        warmup = steps
+    else:       # about 20-30 ms of warm-up for the steps of 0.4-5 ms as well (c3 after 10 steps: 0.70 ms per launch
+        warmup = max(4, (steps * 2) // 5)       # in the first timed loop, 0.68 ms in the later ones)
     n_sets = args.sets if args.sets is not None else DEFAULT_SETS[args.workload]
     if w.host_resident:
         if n_sets <= args.slots:

@@ -142,13 +142,23 @@ __device__ __forceinline__ float row16_sum(float v)
 // row r); the query fragments are gathered once per wave with the same assignment.
 //
 // How the rows reach that layout differs with the row length:
-//   D >= 64  a lane loads its D/2 contiguous bytes directly (D = 128: 4 x global_load_dwordx4);
-//            measured, this access pattern streams ragged documents at the same rate as lane-linear
-//            loads.
 //   D = 32   a 16-row tile is 1 KiB; lane l loads bytes [16 l, 16 l + 16) of it (one fully
-//            coalesced instruction), then four ds_bpermute_b32 move chunk c of row r from lane
-//            4r + c to lane r + 16c.  Loading in the MFMA layout directly (16 B per lane at a 64 B
-//            stride) was measured ~30 % slower on the same gather.
+//            coalesced, non-temporal instruction), then four ds_bpermute_b32 move chunk c of row r
+//            from lane 4r + c to lane r + 16c.  Loading in the MFMA layout directly (16 B per lane at
+//            a 64 B stride) was measured ~30 % slower on the same gather.
+//   D >= 64  two ways (template argument LINEAR), chosen per launch by the host:
+//            LINEAR  the tile, 16 * D * EB contiguous bytes, is loaded lane-linearly, 1 KiB per
+//            instruction, so that every cache line is asked for exactly once and by one
+//            instruction: such loads can be non-temporal, which this machine streams 13 % faster
+//            (256-byte rows: 761 -> 673 us per 4.5 GB launch).  The wave then writes the tile to an
+//            LDS scratch of its own (rows padded by 16 bytes against bank conflicts) and reads it
+//            back in the MFMA layout: 2 x NW/4 LDS instructions per tile, 7 us of the launch.
+//            otherwise  a lane loads its D/2 contiguous bytes directly (D = 128: 4 x
+//            global_load_dwordx4): no transpose, but the four instructions come back to every
+//            line, so the loads have to be ordinary ones (non-temporal: 1.8 times slower).  They
+//            leave the rows in the caches, which is what a batch wants whose queries share
+//            documents (2048 queries with Zipf-distributed lists: 0.98 of the HBM peak this way,
+//            0.85 with non-temporal loads).
 //
 // Work split.  A workgroup of WAVES waves owns a SLICE of one query's candidate list (up to
 // MAX_SLICE consecutive candidates).  All its threads first look the slice's documents up
@@ -195,6 +205,7 @@ struct DocCursor {
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 
 // Registers one lane holds of one 16-row tile: EB = bytes per component (2: binary16, 1: E4M3).
 template <int D, int EB>
@@ -203,26 +214,36 @@ struct TileBuf {
     unsigned w[NW];
 };
 
-template <int D, int EB>
+template <int D, int EB, bool LINEAR>
 __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8_t *__restrict__ emb,
                                                 const DocCursor &cur, int lane)
 {
     constexpr int ROW = D * EB;                    // bytes per row
-    if constexpr (D == 32) {
+    if constexpr (D > 32 && LINEAR) {
+        // lane-linear: the tile is 16 * ROW contiguous bytes; instruction x takes its x-th KiB, lane l the
+        // l-th 16-byte piece of that.  Every byte is asked for exactly once, whole cache lines by one
+        // instruction each: non-temporal loads.  Past the document's end: the last valid piece.
+        const int npiece = min(16, cur.t - cur.tile) * (ROW / 16);
+        const uint4v *p = reinterpret_cast<const uint4v *>(emb + ((size_t)cur.row0 + cur.tile) * ROW);
+#pragma unroll
+        for (int x = 0; x < TileBuf<D, EB>::NW / 4; ++x) {
+            const uint4v v = __builtin_nontemporal_load(p + min(64 * x + lane, npiece - 1));
+            buf.w[4 * x] = v.x; buf.w[4 * x + 1] = v.y; buf.w[4 * x + 2] = v.z; buf.w[4 * x + 3] = v.w;
+        }
+    } else if constexpr (D == 32) {
         // lane-linear: piece `lane` of the 64 pieces of the 16-row tile (16 B each for binary16 rows,
         // 8 B for E4M3 rows); past the document's end: the last valid piece
         const int npiece = min(16, cur.t - cur.tile) * 4;
         const uint8_t *p = emb + ((size_t)cur.row0 + cur.tile) * ROW;
         const int piece = min(lane, npiece - 1);
+        // Every byte of the tile is asked for exactly once, by this one instruction: a non-temporal load
+        // (no claim on cache space the look-ups could use) is 1.5 % faster on a 32 us launch of binary16
+        // rows, and with 1024 queries per batch, a third of whose documents repeat, still 1.9 %.
         if constexpr (EB == 2) {
-            // Every byte of the tile is asked for exactly once, by this one instruction: a non-temporal
-            // load (no claim on cache space the look-ups could use) is 1.5 % faster on a 32 us launch.
-            // The other load shapes below come back to their cache lines and must not use it
-            // (measured: the 256-byte-row kernel takes 1.8 times as long with it).
             const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p) + piece);
             buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
         } else {
-            const uint2 v = reinterpret_cast<const uint2 *>(p)[piece];
+            const uint2v v = __builtin_nontemporal_load(reinterpret_cast<const uint2v *>(p) + piece);
             buf.w[0] = v.x; buf.w[1] = v.y;
         }
     } else {
@@ -275,18 +296,23 @@ template <>
 struct RankLds<false> {};
 
 // grid = B * slices workgroups of WAVES * 64 threads: a workgroup takes one slice of one query's list
-template <int D, int WAVES, int P, int EB, bool RANK, int QG = 2>
+template <int D, int WAVES, int P, int EB, bool RANK, int QG = 2, bool LINEAR = false>
 __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err, int slice,
     const RankOut ro)
 {
     static_assert(D % 32 == 0 && D >= 32 && D <= 256 && (EB == 2 || D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 &&
-                      P >= 1 && (QG == 2 || (QG == 4 && D <= 128)), "unsupported shape");
+                      P >= 1 && (QG == 2 || (QG == 4 && D <= 128)) && (!LINEAR || D > 32), "unsupported shape");
     __shared__ int64_t s_row0[MAX_SLICE];
     __shared__ int s_ntok[MAX_SLICE];
     __shared__ float s_scale[EB == 1 ? MAX_SLICE : 1];
     __shared__ int s_next;
     __shared__ RankLds<RANK> s_rank;
+    // LINEAR: where a wave turns a tile from the order it was loaded in into the order the MFMA wants;
+    // rows are one piece apart from a multiple of the bank period, so that the 16 rows a read touches
+    // fall on different banks
+    constexpr int ROW_PIECES = D * EB / 16;
+    __shared__ uint4 s_tile[LINEAR && D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : 1];
 
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const uint16_t *__restrict__ q = bt.q;
@@ -333,7 +359,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const bool own_first = ld.t > 0;
     TileBuf<D, EB> buf[P];
     if (own_first) {
-        issue_tile_load<D, EB>(buf[0], emb, ld, lane);
+        issue_tile_load<D, EB, LINEAR>(buf[0], emb, ld, lane);
         ld.done = false;
     }
 
@@ -400,7 +426,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
             enter(ld, i);
             ld.done = false;
             ring = i;
-            issue_tile_load<D, EB>(buf[0], emb, ld, lane);
+            issue_tile_load<D, EB, LINEAR>(buf[0], emb, ld, lane);
         }
     }
     if (!ld.done) {
@@ -426,7 +452,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         ld_advance();
 #pragma unroll
         for (int p = 1; p < P; ++p) {
-            issue_tile_load<D, EB>(buf[p], emb, ld, lane);
+            issue_tile_load<D, EB, LINEAR>(buf[p], emb, ld, lane);
             ld_advance();
         }
 
@@ -447,6 +473,31 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                         for (int x = 0; x < TileBuf<D, EB>::NW; ++x)
                             w[x] = (unsigned)__builtin_amdgcn_ds_bpermute(from, (int)buf[p].w[x]);
                         a[0] = fragment_of<EB>(w);
+                    } else if constexpr (LINEAR) {         // D > 32
+                        // piece q of the tile (row q / ROW_PIECES, position q % ROW_PIECES) is in register
+                        // group q / 64 of lane q % 64; lane (r, c) wants pieces c * NW/4 .. of row min(r, rows-1)
+                        constexpr int NX = TileBuf<D, EB>::NW / 4;
+                        uint4 *scr = s_tile + wave * 16 * (ROW_PIECES + 1);
+#pragma unroll
+                        for (int x = 0; x < NX; ++x) {
+                            const int q = 64 * x + lane;
+                            scr[(q / ROW_PIECES) * (ROW_PIECES + 1) + q % ROW_PIECES] =
+                                uint4{buf[p].w[4 * x], buf[p].w[4 * x + 1], buf[p].w[4 * x + 2], buf[p].w[4 * x + 3]};
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        const int rows = min(16, cs.t - cs.tile);
+                        const uint4 *mine = scr + min(r, rows - 1) * (ROW_PIECES + 1) + c * NX;
+                        unsigned w[TileBuf<D, EB>::NW];
+#pragma unroll
+                        for (int x = 0; x < NX; ++x) {
+                            const uint4 v = mine[x];
+                            w[4 * x] = v.x; w[4 * x + 1] = v.y; w[4 * x + 2] = v.z; w[4 * x + 3] = v.w;
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                        for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&w[2 * EB * s]);
                     } else {
 #pragma unroll
                         for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&buf[p].w[2 * EB * s]);
@@ -486,7 +537,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                     }
                     cs_advance();
                 }
-                issue_tile_load<D, EB>(buf[p], emb, ld, lane);
+                issue_tile_load<D, EB, LINEAR>(buf[p], emb, ld, lane);
                 ld_advance();
             }
         }

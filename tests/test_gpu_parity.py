@@ -115,6 +115,31 @@ def test_other_row_lengths_on_the_matrix_cores(d, Q):
     run_both(emb, off, q, cand, 10)
 
 
+@pytest.mark.parametrize("d,Q", [(64, 5), (64, 32), (64, 64), (96, 32), (96, 50), (128, 1), (128, 17), (128, 32),
+                                 (128, 33), (128, 64), (160, 32), (192, 7), (224, 32), (256, 32)])
+def test_few_pairs_against_a_large_table_take_the_lane_linear_loads(d, Q):
+    """With at most half as many (query, candidate) pairs as the table has documents, rows longer than 64 bytes
+    are fetched lane-linearly with non-temporal loads and put in order through LDS; with more pairs every lane
+    loads its own part of a row.  Same documents both ways: the scores have to be bit-identical, and right."""
+    lengths = np.array([0, 1, 2, 3, 4, 5, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 100, 127, 128, 129, 180, 7])
+    counts = np.tile(lengths, 40)                              # 960 documents
+    say("lane-linear loads d=%d Q=%d" % (d, Q))
+    emb, off, q, cand = random_problem(5 * d + Q, counts.size, d, 3, Q, 150, 0, 0, counts=counts)
+    assert 2 * cand.size <= counts.size
+    worst, (g_few, _, _), _ = run_both(emb, off, q, cand, 10)
+    # the same queries in a batch too large for that path (the extra queries are copies)
+    reps = 4
+    q_many, cand_many = np.tile(q, (reps, 1, 1)), np.tile(cand, (reps, 1))
+    assert 2 * cand_many.size > counts.size
+    table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
+    g_many = espn.espn_score(table, torch.from_numpy(q_many).to(DEV), torch.from_numpy(cand_many).to(DEV))
+    espn.espn_table_check(table)
+    g_many = g_many.cpu().numpy()
+    for rep in range(reps):
+        assert np.array_equal(g_many[rep * 3:(rep + 1) * 3].view(np.int32), np.asarray(g_few, dtype=np.float32).view(np.int32))
+    table.free()
+
+
 @pytest.mark.parametrize("d", [32, 128, 64])
 def test_empty_documents_score_minus_infinity_and_rank_last(d):
     say("empty docs d=%d" % d)
