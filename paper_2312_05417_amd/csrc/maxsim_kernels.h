@@ -197,20 +197,23 @@ constexpr int RANK_MAX = 256;        // candidates per query at most for ranking
 struct DocCursor {
     int64_t row0;       // first table row of the current document
     int t;              // its row count
-    int tile;           // first row of the current tile (multiple of 16)
+    int tile;           // first row of the current tile (a multiple of the rows per tile)
     int idx;            // index of the current document in the slice
     bool done;          // moved past the last tile (position stays on the last tile)
-    __device__ __forceinline__ bool last_tile() const { return tile + 16 >= t; }
+    __device__ __forceinline__ bool last_tile(int rows_per_tile) const { return tile + rows_per_tile >= t; }
 };
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 
-// Registers one lane holds of one 16-row tile: EB = bytes per component (2: binary16, 1: E4M3).
+// Registers one lane holds of one tile: EB = bytes per component (2: binary16, 1: E4M3).  A tile is 16
+// rows, one MFMA's worth; 32-byte rows (32 E4M3 codes) come 32 to a tile, so that a tile is a full KiB and
+// one 16-byte load per lane there too.
 template <int D, int EB>
 struct TileBuf {
-    static constexpr int NW = D / 32 * 2 * EB;     // dwords
+    static constexpr int ROWS = (D == 32 && EB == 1) ? 32 : 16;
+    static constexpr int NW = ROWS * D * EB / 256;  // dwords
     unsigned w[NW];
 };
 
@@ -231,21 +234,15 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
             buf.w[4 * x] = v.x; buf.w[4 * x + 1] = v.y; buf.w[4 * x + 2] = v.z; buf.w[4 * x + 3] = v.w;
         }
     } else if constexpr (D == 32) {
-        // lane-linear: piece `lane` of the 64 pieces of the 16-row tile (16 B each for binary16 rows,
-        // 8 B for E4M3 rows); past the document's end: the last valid piece
-        const int npiece = min(16, cur.t - cur.tile) * 4;
-        const uint8_t *p = emb + ((size_t)cur.row0 + cur.tile) * ROW;
-        const int piece = min(lane, npiece - 1);
-        // Every byte of the tile is asked for exactly once, by this one instruction: a non-temporal load
-        // (no claim on cache space the look-ups could use) is 1.5 % faster on a 32 us launch of binary16
-        // rows, and with 1024 queries per batch, a third of whose documents repeat, still 1.9 %.
-        if constexpr (EB == 2) {
-            const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p) + piece);
-            buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
-        } else {
-            const uint2v v = __builtin_nontemporal_load(reinterpret_cast<const uint2v *>(p) + piece);
-            buf.w[0] = v.x; buf.w[1] = v.y;
-        }
+        // lane-linear: the tile is 1 KiB (16 rows of 64 bytes, or 32 rows of 32 bytes), lane l loads its l-th
+        // 16 bytes; past the document's end: the last valid piece.  Every byte of the tile is asked for
+        // exactly once, by this one instruction: a non-temporal load (no claim on cache space the look-ups
+        // could use) is 1.5 % faster on a 32 us launch of binary16 rows, and with 1024 queries per batch, a
+        // third of whose documents repeat, still 1.9 %.
+        const int npiece = min(TileBuf<D, EB>::ROWS, cur.t - cur.tile) * (ROW / 16);
+        const uint4v *p = reinterpret_cast<const uint4v *>(emb + ((size_t)cur.row0 + cur.tile) * ROW);
+        const uint4v v = __builtin_nontemporal_load(p + min(lane, npiece - 1));
+        buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
     } else {
         // lane (r, c) loads the c-th quarter of tile row r: D/2 contiguous bytes (binary16) or D/4 (E4M3)
         const int r = lane & 15, c = lane >> 4;
@@ -312,12 +309,13 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     // rows are one piece apart from a multiple of the bank period, so that the 16 rows a read touches
     // fall on different banks
     constexpr int ROW_PIECES = D * EB / 16;
-    __shared__ uint4 s_tile[LINEAR && D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : 1];
+    __shared__ uint4 s_tile[LINEAR && D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : (D == 32 && EB == 1) ? WAVES * 64 : 1];
 
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const uint16_t *__restrict__ q = bt.q;
     const int Q = bt.Q, K = bt.K;
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
+    constexpr int TR = TileBuf<D, EB>::ROWS;   // rows per load tile
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
     const int xor16 = (lane ^ 16) * 4, xor32 = (lane ^ 32) * 4;     // ds_bpermute addresses
@@ -434,7 +432,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 
         auto ld_advance = [&]() {
             if (ld.done) return;
-            if (!ld.last_tile()) { ld.tile += 16; return; }
+            if (!ld.last_tile(TR)) { ld.tile += TR; return; }
             const int i = grab();
             if (i < 0) { ld.done = true; return; }
             enter(ld, i);
@@ -442,7 +440,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
             ++ld_seq;
         };
         auto cs_advance = [&]() {
-            if (!cs.last_tile()) { cs.tile += 16; return; }
+            if (!cs.last_tile(TR)) { cs.tile += TR; return; }
             // the load cursor has left this document already: no further one means the end
             if (cs_seq == ld_seq) { cs.done = true; return; }
             enter(cs, __builtin_amdgcn_readlane(ring, cs_seq & 63));
@@ -463,57 +461,84 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 if (!cs.done) {
+                    // 16 rows, as MFMA operand fragments, against the query: maxima into m
+                    auto contract = [&](const half8 (&a)[KS]) {
+                        floatx4 acc[QG];
+#pragma unroll
+                        for (int h = 0; h < QG; ++h) acc[h] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                            for (int h = 0; h < QG; ++h)
+                                acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[h][s], acc[h], 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int h = 0; h < QG; ++h) m[h] = max_into(m[h], acc[h]);
+                    };
                     half8 a[KS];
-                    if constexpr (D == 32) {
-                        // lane (r, c) takes piece c of tile row min(r, rows-1) from lane 4*row + c
-                        const int rows = min(16, cs.t - cs.tile);
-                        const int from = (4 * min(r, rows - 1) + c) * 4;
-                        unsigned w[TileBuf<D, EB>::NW];
-#pragma unroll
-                        for (int x = 0; x < TileBuf<D, EB>::NW; ++x)
-                            w[x] = (unsigned)__builtin_amdgcn_ds_bpermute(from, (int)buf[p].w[x]);
-                        a[0] = fragment_of<EB>(w);
-                    } else if constexpr (LINEAR) {         // D > 32
-                        // piece q of the tile (row q / ROW_PIECES, position q % ROW_PIECES) is in register
-                        // group q / 64 of lane q % 64; lane (r, c) wants pieces c * NW/4 .. of row min(r, rows-1)
-                        constexpr int NX = TileBuf<D, EB>::NW / 4;
-                        uint4 *scr = s_tile + wave * 16 * (ROW_PIECES + 1);
-#pragma unroll
-                        for (int x = 0; x < NX; ++x) {
-                            const int q = 64 * x + lane;
-                            scr[(q / ROW_PIECES) * (ROW_PIECES + 1) + q % ROW_PIECES] =
-                                uint4{buf[p].w[4 * x], buf[p].w[4 * x + 1], buf[p].w[4 * x + 2], buf[p].w[4 * x + 3]};
-                        }
+                    if constexpr (D == 32 && EB == 1) {
+                        // 32 rows of 32 bytes as loaded: lane l holds bytes [16 l, 16 l + 16) of the tile.  Through
+                        // the wave's own KiB of LDS, lane (r, c) takes bytes [8 c, 8 c + 8) of row min(r, rows-1)
+                        // of each half of the tile (the second half only if the document reaches into it)
+                        uint4 *scr = s_tile + wave * 64;
+                        scr[lane] = uint4{buf[p].w[0], buf[p].w[1], buf[p].w[2], buf[p].w[3]};
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                         __builtin_amdgcn_wave_barrier();
-                        const int rows = min(16, cs.t - cs.tile);
-                        const uint4 *mine = scr + min(r, rows - 1) * (ROW_PIECES + 1) + c * NX;
-                        unsigned w[TileBuf<D, EB>::NW];
-#pragma unroll
-                        for (int x = 0; x < NX; ++x) {
-                            const uint4 v = mine[x];
-                            w[4 * x] = v.x; w[4 * x + 1] = v.y; w[4 * x + 2] = v.z; w[4 * x + 3] = v.w;
-                        }
+                        const int rows = min(TR, cs.t - cs.tile);
+                        const uint2 *pieces = reinterpret_cast<const uint2 *>(scr);
+                        const uint2 lo = pieces[4 * min(r, rows - 1) + c];
+                        const uint2 hi = pieces[4 * min(16 + r, rows - 1) + c];
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                         __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                        for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&w[2 * EB * s]);
+                        const unsigned w_lo[2] = {lo.x, lo.y}, w_hi[2] = {hi.x, hi.y};
+                        a[0] = fragment_of<EB>(w_lo);
+                        contract(a);
+                        if (rows > 16) {                     // wave-uniform
+                            a[0] = fragment_of<EB>(w_hi);
+                            contract(a);
+                        }
                     } else {
+                        if constexpr (D == 32) {
+                            // lane (r, c) takes piece c of tile row min(r, rows-1) from lane 4*row + c
+                            const int rows = min(16, cs.t - cs.tile);
+                            const int from = (4 * min(r, rows - 1) + c) * 4;
+                            unsigned w[TileBuf<D, EB>::NW];
 #pragma unroll
-                        for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&buf[p].w[2 * EB * s]);
+                            for (int x = 0; x < TileBuf<D, EB>::NW; ++x)
+                                w[x] = (unsigned)__builtin_amdgcn_ds_bpermute(from, (int)buf[p].w[x]);
+                            a[0] = fragment_of<EB>(w);
+                        } else if constexpr (LINEAR) {         // D > 32
+                            // piece q of the tile (row q / ROW_PIECES, position q % ROW_PIECES) is in register
+                            // group q / 64 of lane q % 64; lane (r, c) wants pieces c * NW/4 .. of row min(r, rows-1)
+                            constexpr int NX = TileBuf<D, EB>::NW / 4;
+                            uint4 *scr = s_tile + wave * 16 * (ROW_PIECES + 1);
+#pragma unroll
+                            for (int x = 0; x < NX; ++x) {
+                                const int q = 64 * x + lane;
+                                scr[(q / ROW_PIECES) * (ROW_PIECES + 1) + q % ROW_PIECES] =
+                                    uint4{buf[p].w[4 * x], buf[p].w[4 * x + 1], buf[p].w[4 * x + 2], buf[p].w[4 * x + 3]};
+                            }
+                            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                            __builtin_amdgcn_wave_barrier();
+                            const int rows = min(16, cs.t - cs.tile);
+                            const uint4 *mine = scr + min(r, rows - 1) * (ROW_PIECES + 1) + c * NX;
+                            unsigned w[TileBuf<D, EB>::NW];
+#pragma unroll
+                            for (int x = 0; x < NX; ++x) {
+                                const uint4 v = mine[x];
+                                w[4 * x] = v.x; w[4 * x + 1] = v.y; w[4 * x + 2] = v.z; w[4 * x + 3] = v.w;
+                            }
+                            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                            for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&w[2 * EB * s]);
+                        } else {
+#pragma unroll
+                            for (int s = 0; s < KS; ++s) a[s] = fragment_of<EB>(&buf[p].w[2 * EB * s]);
+                        }
+                        contract(a);
                     }
-                    floatx4 acc[QG];
-#pragma unroll
-                    for (int h = 0; h < QG; ++h) acc[h] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-#pragma unroll
-                        for (int h = 0; h < QG; ++h)
-                            acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s], qf[h][s], acc[h], 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int h = 0; h < QG; ++h) m[h] = max_into(m[h], acc[h]);
-                    if (cs.last_tile()) {
+                    if (cs.last_tile(TR)) {
                         // max over the four row groups (lanes l, l^16, l^32, l^48 hold the same query row)
 #pragma unroll
                         for (int h = 0; h < QG; ++h) {
