@@ -307,6 +307,8 @@ def main():
     ap.add_argument("--slots", type=int, default=2,
                     help="c5 only: HBM staging slots (2 = double buffering; more slots also serve as a cache of "
                          "recently fetched documents)")
+    ap.add_argument("--fetch", default="auto", choices=["auto", "streaming", "cached"],
+                    help="how rows of 128 bytes and more are fetched (espn_table_set_fetch); auto = the library decides")
     ap.add_argument("--engine", default="gather", choices=["gather", "packed"],
                     help="c5 only: which prefetch engine fills the staging slots (espn_prefetch / espn_prefetch_packed)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
@@ -380,6 +382,8 @@ def main():
         table = espn.espn_table_load_e4m3(emb, doc_scale, off)
     else:
         table = espn.espn_table_load(emb, off)
+    espn.espn_table_set_fetch(table, {"auto": espn.ESPN_FETCH_AUTO, "streaming": espn.ESPN_FETCH_STREAMING,
+                                      "cached": espn.ESPN_FETCH_CACHED}[args.fetch])
     log("%s: table %d docs, %d rows x %d, %.2f GB in HBM (%.1f s)" % (
         w.name, w.n_docs, emb.shape[0], w.dim, emb.numel() * elem_bytes / 1e9, time.time() - t_setup))
     cands_np = [synth.candidates(w, seed, s) for s in range(n_sets)]
@@ -566,6 +570,7 @@ def main():
             "table_gb": emb.numel() * elem_bytes / 1e9, "codec": w.codec, "tokens_per_doc": "%s[%d,%d]" % (w.count_law, w.count_lo, w.count_hi),
             "batch_queries": w.B, "query_tokens": w.Q, "candidates_per_query": w.K, "scored_per_query": R,
             "top_k": w.k, "candidate_law": w.cand_law, "rotating_sets": n_sets, "accumulate": "f32", "seed": seed,
+            "fetch": args.fetch,
         },
         "queries_per_s": w.B * steps / wall,
         "wall_algorithmic_gbs": launch_bytes * steps / wall / 1e9,

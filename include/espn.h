@@ -100,6 +100,21 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
                     int32_t *residency, int32_t *device);
 
 /*
+ * How the rows of the table are fetched by the scoring kernels (rows of 128 bytes and more):
+ *   ESPN_FETCH_AUTO       decided per batch: streaming if the batch has at most half as many (query, candidate)
+ *                         pairs as the table has documents, cached otherwise.  The default.
+ *   ESPN_FETCH_STREAMING  non-temporal loads: fastest when the queries of a batch list different documents
+ *                         (uniformly drawn lists: 12 % faster than cached).
+ *   ESPN_FETCH_CACHED     ordinary loads that leave the rows in the caches: fastest when the lists overlap,
+ *                         whatever the batch size (lists drawn from a Zipf law: 10-14 % faster than streaming
+ *                         from 64 queries per batch on).  The library cannot see the law the lists follow;
+ *                         a caller that knows its lists share popular documents says so here.
+ * The scores do not depend on it.  Takes effect from the next call on.  Errors: ARG.
+ */
+enum { ESPN_FETCH_AUTO = 0, ESPN_FETCH_STREAMING = 1, ESPN_FETCH_CACHED = 2 };
+int espn_table_set_fetch(espn_table *table, int32_t mode);
+
+/*
  * MaxSim scores of every candidate (Eq. 1):
  *     scores[b,j] = sum over i < Q of  max over rows r of document cand[b,j] of  <q[b,i,:], emb[r,:]>
  * The candidate gather (offset lookup + streaming the document's rows) is fused into the

@@ -18,6 +18,7 @@ ESPN_OK = 0
 ESPN_ERR_ARG, ESPN_ERR_SHAPE, ESPN_ERR_OFFSETS, ESPN_ERR_ID_RANGE = 1, 2, 3, 4
 ESPN_ERR_NOMEM, ESPN_ERR_HIP, ESPN_ERR_UNSUPPORTED, ESPN_ERR_BUSY = 5, 6, 7, 8
 ESPN_RESIDENT_HBM, ESPN_RESIDENT_HOST_PINNED = 0, 1
+ESPN_FETCH_AUTO, ESPN_FETCH_STREAMING, ESPN_FETCH_CACHED = 0, 1, 2
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -28,6 +29,7 @@ SIGNATURES = {
     "espn_table_load": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
     "espn_table_load_e4m3": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
     "espn_table_free": (ctypes.c_int, [_c_p]),
+    "espn_table_set_fetch": (ctypes.c_int, [_c_p, _c_i32]),
     "espn_table_info": (ctypes.c_int, [_c_p, ctypes.POINTER(_c_i64), ctypes.POINTER(_c_i64),
                                        ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
     "espn_score": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p]),
@@ -180,6 +182,10 @@ def espn_table_load(emb: torch.Tensor, offsets, device: int | None = None) -> Ta
 
 def espn_table_load_e4m3(codes: torch.Tensor, doc_scale, offsets, device: int | None = None) -> Table:
     return Table(codes, offsets, device=device, doc_scale=doc_scale)
+
+
+def espn_table_set_fetch(table: Table, mode: int) -> None:
+    _check(lib().espn_table_set_fetch(table.handle, mode))
 
 
 def espn_table_free(table: Table) -> None:

@@ -105,6 +105,7 @@ struct espn_table {
     int32_t dim = 0;
     int32_t residency = 0;
     int32_t device = 0;
+    int32_t fetch = ESPN_FETCH_AUTO;   // how rows of 128 bytes and more are fetched
     StagingSlot slot[espn::MAX_SLOTS];
     int n_slots = 0;
     uint64_t prefetches = 0;         // prefetches enqueued so far
@@ -286,6 +287,15 @@ ESPN_API int espn_table_free(espn_table *table)
     return ESPN_OK;
 }
 
+ESPN_API int espn_table_set_fetch(espn_table *table, int32_t mode)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (mode != ESPN_FETCH_AUTO && mode != ESPN_FETCH_STREAMING && mode != ESPN_FETCH_CACHED)
+        return fail(ESPN_ERR_ARG, "fetch mode %d is not a known value", mode);
+    table->fetch = mode;
+    return ESPN_OK;
+}
+
 ESPN_API int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_rows, int32_t *dim,
                              int32_t *residency, int32_t *device)
 {
@@ -367,8 +377,11 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     // cached: ordinary loads.  Lane-linear loads take whole lines with one instruction each and can be
     // non-temporal, which this machine streams 13 % faster (c3 761 -> 673 us before the transpose is paid
     // for), but a document that several queries of the batch list is then fetched from memory every time.
-    // So: non-temporal when the batch cannot repeat documents much (pairs <= half the documents of the table).
-    p.linear = t->dim > 32 && 2 * (int64_t)B * K <= t->n_docs;
+    // So, unless the caller has said which it wants: non-temporal when the batch cannot repeat documents much
+    // (pairs <= half the documents of the table).  That is right for lists drawn uniformly and wrong for small
+    // batches of lists that share popular documents (Zipf: cached loads win from 64 queries on).
+    p.linear = t->dim > 32 && (t->fetch == ESPN_FETCH_STREAMING ||
+                               (t->fetch == ESPN_FETCH_AUTO && 2 * (int64_t)B * K <= t->n_docs));
     return p;
 }
 

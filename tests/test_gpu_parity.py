@@ -132,11 +132,19 @@ def test_few_pairs_against_a_large_table_take_the_lane_linear_loads(d, Q):
     q_many, cand_many = np.tile(q, (reps, 1, 1)), np.tile(cand, (reps, 1))
     assert 2 * cand_many.size > counts.size
     table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
-    g_many = espn.espn_score(table, torch.from_numpy(q_many).to(DEV), torch.from_numpy(cand_many).to(DEV))
-    espn.espn_table_check(table)
-    g_many = g_many.cpu().numpy()
-    for rep in range(reps):
-        assert np.array_equal(g_many[rep * 3:(rep + 1) * 3].view(np.int32), np.asarray(g_few, dtype=np.float32).view(np.int32))
+    q_d, cand_d = torch.from_numpy(q_many).to(DEV), torch.from_numpy(cand_many).to(DEV)
+    few = np.asarray(g_few, dtype=np.float32).view(np.int32)
+    # ... and both batches with the choice made by the caller instead of by the library
+    for mode in (espn.ESPN_FETCH_AUTO, espn.ESPN_FETCH_STREAMING, espn.ESPN_FETCH_CACHED):
+        espn.espn_table_set_fetch(table, mode)
+        g_many = espn.espn_score(table, q_d, cand_d).cpu().numpy()
+        g_again = espn.espn_score(table, q_d[:3].contiguous(), cand_d[:3].contiguous()).cpu().numpy()
+        espn.espn_table_check(table)
+        assert np.array_equal(g_again.view(np.int32), few), mode
+        for rep in range(reps):
+            assert np.array_equal(g_many[rep * 3:(rep + 1) * 3].view(np.int32), few), (mode, rep)
+    with pytest.raises(espn.EspnError):
+        espn.espn_table_set_fetch(table, 3)
     table.free()
 
 
