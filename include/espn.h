@@ -101,18 +101,27 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
 
 /*
  * How the rows of the table are fetched by the scoring kernels (rows of 128 bytes and more):
- *   ESPN_FETCH_AUTO       decided per batch: streaming if the batch has at most half as many (query, candidate)
- *                         pairs as the table has documents, cached otherwise.  The default.
+ *   ESPN_FETCH_AUTO       decided per batch.  Every 16th scoring call on the table also samples its candidate
+ *                         lists (one small kernel on the caller's stream, result left in pinned host memory);
+ *                         later calls take cached if more than 5 % of the sampled pairs repeated a document,
+ *                         streaming if not.  Before the first sample is in: streaming if the batch has at most
+ *                         half as many (query, candidate) pairs as the table has documents.  The default.
  *   ESPN_FETCH_STREAMING  non-temporal loads: fastest when the queries of a batch list different documents
  *                         (uniformly drawn lists: 12 % faster than cached).
  *   ESPN_FETCH_CACHED     ordinary loads that leave the rows in the caches: fastest when the lists overlap,
  *                         whatever the batch size (lists drawn from a Zipf law: 10-14 % faster than streaming
- *                         from 64 queries per batch on).  The library cannot see the law the lists follow;
- *                         a caller that knows its lists share popular documents says so here.
+ *                         from 64 queries per batch on).
  * The scores do not depend on it.  Takes effect from the next call on.  Errors: ARG.
  */
 enum { ESPN_FETCH_AUTO = 0, ESPN_FETCH_STREAMING = 1, ESPN_FETCH_CACHED = 2 };
 int espn_table_set_fetch(espn_table *table, int32_t mode);
+
+/*
+ * The last sample taken under ESPN_FETCH_AUTO: the fraction of up to 4096 sampled (query, candidate) pairs of a
+ * batch whose document another sampled pair had named already; -1 before the first sample has arrived.  Never
+ * waits (the value may be that of an earlier batch).  estimate: HOST pointer.  Errors: ARG.
+ */
+int espn_table_sharing_estimate(const espn_table *table, float *estimate);
 
 /*
  * MaxSim scores of every candidate (Eq. 1):

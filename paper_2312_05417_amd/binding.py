@@ -30,6 +30,7 @@ SIGNATURES = {
     "espn_table_load_e4m3": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
     "espn_table_free": (ctypes.c_int, [_c_p]),
     "espn_table_set_fetch": (ctypes.c_int, [_c_p, _c_i32]),
+    "espn_table_sharing_estimate": (ctypes.c_int, [_c_p, ctypes.POINTER(ctypes.c_float)]),
     "espn_table_info": (ctypes.c_int, [_c_p, ctypes.POINTER(_c_i64), ctypes.POINTER(_c_i64),
                                        ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
     "espn_score": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p]),
@@ -186,6 +187,12 @@ def espn_table_load_e4m3(codes: torch.Tensor, doc_scale, offsets, device: int | 
 
 def espn_table_set_fetch(table: Table, mode: int) -> None:
     _check(lib().espn_table_set_fetch(table.handle, mode))
+
+
+def espn_table_sharing_estimate(table: Table) -> float:
+    out = ctypes.c_float(0.0)
+    _check(lib().espn_table_sharing_estimate(table.handle, ctypes.byref(out)))
+    return float(out.value)
 
 
 def espn_table_free(table: Table) -> None:

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -106,6 +107,9 @@ struct espn_table {
     int32_t residency = 0;
     int32_t device = 0;
     int32_t fetch = ESPN_FETCH_AUTO;   // how rows of 128 bytes and more are fetched
+    float *share_host = nullptr;       // owned, pinned: the last estimate of how much a batch's lists overlap (-1: none yet)
+    float *share_dev = nullptr;        // the same word as the device sees it
+    mutable std::atomic<uint64_t> scored{0};   // scoring launches so far (the estimate is renewed every kShareEvery)
     StagingSlot slot[espn::MAX_SLOTS];
     int n_slots = 0;
     uint64_t prefetches = 0;         // prefetches enqueued so far
@@ -218,6 +222,11 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
         e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device);
         if (e == hipSuccess && n_cu > 0) t->n_cu = n_cu;
     }
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&t->share_host), kAlign, hipHostMallocDefault);
+    if (e == hipSuccess) {
+        *t->share_host = -1.f;
+        e = hipHostGetDevicePointer(reinterpret_cast<void **>(&t->share_dev), t->share_host, 0);
+    }
     if (e == hipSuccess && doc_scale_host) {
         e = hipMalloc(reinterpret_cast<void **>(&t->scale_dev), sizeof(float) * (size_t)(n_docs + 1));
         if (e == hipSuccess && n_docs > 0)
@@ -228,6 +237,7 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
         (void)hipFree(t->off_dev);
         (void)hipFree(t->err_dev);
         (void)hipFree(t->scale_dev);
+        if (t->share_host) (void)hipHostFree(t->share_host);
         delete[] t->off_host;
         delete t;
         return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "table set-up failed: %s",
@@ -282,6 +292,7 @@ ESPN_API int espn_table_free(espn_table *table)
     (void)hipFree(table->off_dev);
     (void)hipFree(table->err_dev);
     (void)hipFree(table->scale_dev);
+    if (table->share_host) (void)hipHostFree(table->share_host);
     delete[] table->off_host;
     delete table;
     return ESPN_OK;
@@ -293,6 +304,13 @@ ESPN_API int espn_table_set_fetch(espn_table *table, int32_t mode)
     if (mode != ESPN_FETCH_AUTO && mode != ESPN_FETCH_STREAMING && mode != ESPN_FETCH_CACHED)
         return fail(ESPN_ERR_ARG, "fetch mode %d is not a known value", mode);
     table->fetch = mode;
+    return ESPN_OK;
+}
+
+ESPN_API int espn_table_sharing_estimate(const espn_table *table, float *estimate)
+{
+    if (!table || !estimate) return fail(ESPN_ERR_ARG, "NULL pointer");
+    *estimate = table->share_host ? *static_cast<volatile const float *>(table->share_host) : -1.f;
     return ESPN_OK;
 }
 
@@ -335,6 +353,10 @@ constexpr int kNarrowWaves = 8;
 // compute unit instead of two of 8 (measured: c3 764 -> 760 us, c4 4.80 -> 4.68 ms; E4M3 rows of the
 // same length lose 4 % with it and keep 8 waves).
 constexpr int kNarrowWaves128 = 4;
+// Lists of a batch are taken to share documents if more than this fraction of a sample of 4096 pairs repeats a
+// document of the sample (uniform lists over 2 M documents: 0.002; Zipf(1.1) lists: above 0.5)
+constexpr float kShareThreshold = 0.05f;
+constexpr uint64_t kShareEvery = 16;
 
 // How a batch is cut into workgroup slices, and whether the scoring kernel ranks as well.
 struct SlicePlan {
@@ -380,8 +402,12 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     // So, unless the caller has said which it wants: non-temporal when the batch cannot repeat documents much
     // (pairs <= half the documents of the table).  That is right for lists drawn uniformly and wrong for small
     // batches of lists that share popular documents (Zipf: cached loads win from 64 queries on).
-    p.linear = t->dim > 32 && (t->fetch == ESPN_FETCH_STREAMING ||
-                               (t->fetch == ESPN_FETCH_AUTO && 2 * (int64_t)B * K <= t->n_docs));
+    // ... unless a sample of an earlier batch's lists has shown how much they overlap (sharing_probe_kernel,
+    // every kShareEvery-th scoring launch, written to pinned host memory and read here without waiting)
+    bool streaming = 2 * (int64_t)B * K <= t->n_docs;
+    const float overlap = t->share_host ? *static_cast<volatile const float *>(t->share_host) : -1.f;
+    if (overlap >= 0.f) streaming = overlap < kShareThreshold;
+    p.linear = t->dim > 32 && (t->fetch == ESPN_FETCH_STREAMING || (t->fetch == ESPN_FETCH_AUTO && streaming));
     return p;
 }
 
@@ -483,6 +509,11 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
         const dim3 grid((unsigned)((bt.K + 3) / 4) * B), block(256);
         hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim, bt, scores, t->err_dev);
     }
+    // every so often, look at how much this batch's lists overlap (for the choice of the next launches)
+    if (t->fetch == ESPN_FETCH_AUTO && t->dim > 32 && on_matrix_cores(t, bt.Q) && !src.row_map && t->share_dev &&
+        t->scored.fetch_add(1, std::memory_order_relaxed) % kShareEvery == 0)
+        hipLaunchKernelGGL(sharing_probe_kernel, dim3(1), dim3(1024), 0, st, bt.cand, (int64_t)B * bt.K, bt.K, bt.ldc,
+                           t->share_dev);
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }

@@ -176,6 +176,40 @@ __global__ __launch_bounds__(256) void staging_gather_kernel(
     }
 }
 
+// How much the candidate lists of a batch overlap, from a sample: up to 4096 of the batch's (query,
+// candidate) pairs, evenly spaced, go into a hash set in LDS (32-bit fingerprints of the ids, open
+// addressing, half full at most); the result is the fraction of them whose document was already there.
+// Uniformly drawn lists over a large table give about 0, lists that share popular documents far more.
+// One workgroup; `out` may be device-visible host memory.
+__global__ __launch_bounds__(1024) void sharing_probe_kernel(const int64_t *__restrict__ cand, int64_t n_pairs, int K,
+                                                             int ldc, float *__restrict__ out)
+{
+    constexpr unsigned SLOTS = 8192, SAMPLE = 4096, EMPTY = 0xffffffffu;
+    __shared__ unsigned s_set[SLOTS];
+    __shared__ unsigned s_repeats;
+    for (unsigned i = threadIdx.x; i < SLOTS; i += 1024) s_set[i] = EMPTY;
+    if (threadIdx.x == 0) s_repeats = 0u;
+    __syncthreads();
+    const unsigned n = (unsigned)(n_pairs < (int64_t)SAMPLE ? n_pairs : (int64_t)SAMPLE);
+    unsigned mine = 0;
+    for (unsigned i = threadIdx.x; i < n; i += 1024) {
+        const int64_t pair = (int64_t)i * n_pairs / n;
+        const uint64_t id = (uint64_t)cand[(pair / K) * ldc + pair % K];
+        unsigned key = (unsigned)id ^ ((unsigned)(id >> 32) * 0x85ebca6bu);
+        if (key == EMPTY) key = 0u;
+        unsigned slot = (key * 2654435761u) >> 19;                   // 13 bits
+        for (unsigned tries = 0; tries < SLOTS; ++tries) {             // the set is never more than half full
+            const unsigned seen = atomicCAS(&s_set[slot], EMPTY, key);
+            if (seen == EMPTY) break;
+            if (seen == key) { ++mine; break; }
+            slot = (slot + 1) & (SLOTS - 1);
+        }
+    }
+    if (mine) atomicAdd(&s_repeats, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) *out = n ? (float)s_repeats / (float)n : 0.f;
+}
+
 // Plain contiguous read of n 16-byte chunks: workgroup x walks chunks [x * per, (x + 1) * per), 8 loads
 // in flight per lane, non-temporal (measured against ordinary loads and against a grid-strided walk,
 // this is the fastest plain read on this machine: 6.3 TB/s on 165 MB windows, 6.5 TB/s on 4.5 GB; ordinary

@@ -148,6 +148,47 @@ def test_few_pairs_against_a_large_table_take_the_lane_linear_loads(d, Q):
     table.free()
 
 
+def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
+    """Under the default fetch mode every 16th scoring call samples the batch's candidate lists; the estimate (the
+    share of sampled pairs that repeat a document) separates uniformly drawn lists from lists that share popular
+    documents, and scores are the same whichever way the rows are then fetched."""
+    say("sharing estimate")
+    rng = np.random.default_rng(21)
+    N, d, B, K = 30_000, 128, 8, 200            # 1600 uniform pairs over 30 000 documents: about 2.7 % repeat
+    counts = rng.integers(1, 30, size=N)
+    emb, off, q, _ = random_problem(77, N, d, B, 32, K, 0, 0, counts=counts)
+    uniform = np.stack([rng.permutation(N)[:K] for _ in range(B)]).astype(np.int64)
+    popular = rng.permutation(N)[:260]
+    shared = np.stack([rng.permutation(popular)[:K] for _ in range(B)]).astype(np.int64)   # every list from 260 documents
+    table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
+    assert espn.espn_table_sharing_estimate(table) == -1.0
+    q_d = torch.from_numpy(q).to(DEV)
+    results = {}
+    for name, cand in (("uniform", uniform), ("shared", shared), ("uniform again", uniform)):
+        cand_d = torch.from_numpy(cand).to(DEV)
+        for call in range(16):                                  # the sample is taken on the first of every 16 calls
+            scores = espn.espn_score(table, q_d, cand_d)
+        torch.cuda.synchronize()
+        results[name] = (espn.espn_table_sharing_estimate(table), scores.cpu().numpy())
+    espn.espn_table_check(table)
+    assert 0.0 <= results["uniform"][0] < 0.05, results["uniform"][0]
+    assert results["shared"][0] > 0.5, results["shared"][0]
+    assert 0.0 <= results["uniform again"][0] < 0.05
+    # the first 16 calls on uniform lists were planned before any sample, the last 16 after the "shared" sample:
+    # whatever was chosen, the scores are the same bit for bit, and right
+    assert np.array_equal(results["uniform"][1].view(np.int32), results["uniform again"][1].view(np.int32))
+    assert_scores_close(results["shared"][1], oracle.scores(emb, off, q, shared), 32)
+    assert_scores_close(results["uniform"][1], oracle.scores(emb, off, q, uniform), 32)
+    # a caller's choice switches the sampling off
+    espn.espn_table_set_fetch(table, espn.ESPN_FETCH_CACHED)
+    before = espn.espn_table_sharing_estimate(table)
+    for call in range(20):
+        espn.espn_score(table, q_d, torch.from_numpy(shared).to(DEV))
+    torch.cuda.synchronize()
+    assert espn.espn_table_sharing_estimate(table) == before
+    table.free()
+
+
 @pytest.mark.parametrize("d", [32, 128, 64])
 def test_empty_documents_score_minus_infinity_and_rank_last(d):
     say("empty docs d=%d" % d)
