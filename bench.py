@@ -316,6 +316,8 @@ def main():
                     help="override the rows per query (up to 64 run on the matrix cores; more take the plain-ALU "
                          "kernel: a comparison point, not a workload of the paper)")
     ap.add_argument("--top-k", type=int, default=None, help="override the number of ranks returned per query")
+    ap.add_argument("--cand-law", default=None, choices=["uniform", "zipf"],
+                    help="override the law the candidate lists are drawn from")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--two-streams", nargs="?", type=int, const=2, default=0, metavar="N",
@@ -350,6 +352,8 @@ def main():
         w = synth.scaled(w, B=args.batch, name="%s-B%d" % (w.name, args.batch))
     if args.top_k is not None:
         w = synth.scaled(w, k=args.top_k, name="%s-k%d" % (w.name, args.top_k))
+    if args.cand_law is not None:
+        w = synth.scaled(w, cand_law=args.cand_law, name="%s-%s" % (w.name, args.cand_law))
     if args.query_tokens is not None:
         w = synth.scaled(w, Q=args.query_tokens, name="%s-Q%d" % (w.name, args.query_tokens))
     seed = synth.DEFAULT_SEED if args.seed is None else args.seed

@@ -100,16 +100,17 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
                     int32_t *residency, int32_t *device);
 
 /*
- * How the rows of the table are fetched by the scoring kernels (rows of 128 bytes and more):
- *   ESPN_FETCH_AUTO       decided per batch.  Every 16th scoring call on the table also samples its candidate
+ * How the rows of the table are fetched by the scoring kernels:
+ *   ESPN_FETCH_AUTO       decided per batch.  Every 64th scoring call on the table also samples its candidate
  *                         lists (one small kernel on the caller's stream, result left in pinned host memory);
  *                         later calls take cached if more than 5 % of the sampled pairs repeated a document,
- *                         streaming if not.  Before the first sample is in: streaming if the batch has at most
- *                         half as many (query, candidate) pairs as the table has documents.  The default.
+ *                         streaming if not.  Before the first sample is in: streaming for 64-byte rows, and for
+ *                         longer rows if the batch has at most half as many (query, candidate) pairs as the table
+ *                         has documents.  The default.
  *   ESPN_FETCH_STREAMING  non-temporal loads: fastest when the queries of a batch list different documents
- *                         (uniformly drawn lists: 12 % faster than cached).
+ *                         (uniformly drawn lists: 2 to 12 % faster than cached).
  *   ESPN_FETCH_CACHED     ordinary loads that leave the rows in the caches: fastest when the lists overlap,
- *                         whatever the batch size (lists drawn from a Zipf law: 10-14 % faster than streaming
+ *                         whatever the batch size (lists drawn from a Zipf law: 10 to 36 % faster than streaming
  *                         from 64 queries per batch on).
  * The scores do not depend on it.  Takes effect from the next call on.  Errors: ARG.
  */

@@ -356,7 +356,7 @@ constexpr int kNarrowWaves128 = 4;
 // Lists of a batch are taken to share documents if more than this fraction of a sample of 4096 pairs repeats a
 // document of the sample (uniform lists over 2 M documents: 0.002; Zipf(1.1) lists: above 0.5)
 constexpr float kShareThreshold = 0.05f;
-constexpr uint64_t kShareEvery = 16;
+constexpr uint64_t kShareEvery = 64;
 
 // How a batch is cut into workgroup slices, and whether the scoring kernel ranks as well.
 struct SlicePlan {
@@ -364,7 +364,7 @@ struct SlicePlan {
     int slices = 0;         // workgroups per query
     int waves = 0;          // waves per workgroup
     bool rank = false;      // the scoring kernel writes the top-k itself
-    bool linear = false;    // rows longer than 64 bytes: lane-linear non-temporal loads, tiles transposed through LDS
+    bool linear = false;    // non-temporal row loads (rows longer than 64 bytes: lane-linear, tiles transposed through LDS)
 };
 
 // Slices per query.  A launch small enough to be resident at once (two workgroups per compute unit)
@@ -407,7 +407,10 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     bool streaming = 2 * (int64_t)B * K <= t->n_docs;
     const float overlap = t->share_host ? *static_cast<volatile const float *>(t->share_host) : -1.f;
     if (overlap >= 0.f) streaming = overlap < kShareThreshold;
-    p.linear = t->dim > 32 && (t->fetch == ESPN_FETCH_STREAMING || (t->fetch == ESPN_FETCH_AUTO && streaming));
+    // 64-byte rows are fetched lane-linearly either way, so only the hint is at stake: non-temporal unless a
+    // sample has shown overlapping lists (uniform lists, 1024 queries: 1.9 % faster; Zipf lists: 27-36 % slower)
+    if (t->dim == 32) streaming = !(overlap >= kShareThreshold);
+    p.linear = t->fetch == ESPN_FETCH_STREAMING || (t->fetch == ESPN_FETCH_AUTO && streaming);
     return p;
 }
 
@@ -443,13 +446,8 @@ template <int D, int EB, bool RANK, int QG>
 void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
                    float *scores, const espn::RankOut &ro, hipStream_t st)
 {
-    if constexpr (D > 32) {
-        if (plan.linear) {
-            launch_slices<D, EB, RANK, QG, true>(src, bt, B, plan, err, scores, ro, st);
-            return;
-        }
-    }
-    launch_slices<D, EB, RANK, QG, false>(src, bt, B, plan, err, scores, ro, st);
+    if (plan.linear) launch_slices<D, EB, RANK, QG, true>(src, bt, B, plan, err, scores, ro, st);
+    else launch_slices<D, EB, RANK, QG, false>(src, bt, B, plan, err, scores, ro, st);
 }
 
 // rows longer than 256 bytes are held for 32 query rows only (their fragments would not fit the registers)
@@ -510,7 +508,7 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
         hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim, bt, scores, t->err_dev);
     }
     // every so often, look at how much this batch's lists overlap (for the choice of the next launches)
-    if (t->fetch == ESPN_FETCH_AUTO && t->dim > 32 && on_matrix_cores(t, bt.Q) && !src.row_map && t->share_dev &&
+    if (t->fetch == ESPN_FETCH_AUTO && on_matrix_cores(t, bt.Q) && !src.row_map && t->share_dev &&
         t->scored.fetch_add(1, std::memory_order_relaxed) % kShareEvery == 0)
         hipLaunchKernelGGL(sharing_probe_kernel, dim3(1), dim3(1024), 0, st, bt.cand, (int64_t)B * bt.K, bt.K, bt.ldc,
                            t->share_dev);

@@ -236,12 +236,15 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
     } else if constexpr (D == 32) {
         // lane-linear: the tile is 1 KiB (16 rows of 64 bytes, or 32 rows of 32 bytes), lane l loads its l-th
         // 16 bytes; past the document's end: the last valid piece.  Every byte of the tile is asked for
-        // exactly once, by this one instruction: a non-temporal load (no claim on cache space the look-ups
-        // could use) is 1.5 % faster on a 32 us launch of binary16 rows, and with 1024 queries per batch, a
-        // third of whose documents repeat, still 1.9 %.
+        // exactly once, by this one instruction.  LINEAR: a non-temporal load (no claim on cache space the
+        // look-ups could use: 1.5 % faster on a 32 us launch of binary16 rows, 1.9 % with 1024 queries a third
+        // of whose documents repeat); otherwise an ordinary load, which leaves the rows in the caches for the
+        // other queries of the batch that list the document (Zipf lists: 25 instead of 34 us).
         const int npiece = min(TileBuf<D, EB>::ROWS, cur.t - cur.tile) * (ROW / 16);
         const uint4v *p = reinterpret_cast<const uint4v *>(emb + ((size_t)cur.row0 + cur.tile) * ROW);
-        const uint4v v = __builtin_nontemporal_load(p + min(lane, npiece - 1));
+        uint4v v;
+        if constexpr (LINEAR) v = __builtin_nontemporal_load(p + min(lane, npiece - 1));
+        else v = p[min(lane, npiece - 1)];
         buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
     } else {
         // lane (r, c) loads the c-th quarter of tile row r: D/2 contiguous bytes (binary16) or D/4 (E4M3)
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const RankOut ro)
 {
     static_assert(D % 32 == 0 && D >= 32 && D <= 256 && (EB == 2 || D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 &&
-                      P >= 1 && (QG == 2 || (QG == 4 && D <= 128)) && (!LINEAR || D > 32), "unsupported shape");
+                      P >= 1 && (QG == 2 || (QG == 4 && D <= 128)), "unsupported shape");
     __shared__ int64_t s_row0[MAX_SLICE];
     __shared__ int s_ntok[MAX_SLICE];
     __shared__ float s_scale[EB == 1 ? MAX_SLICE : 1];

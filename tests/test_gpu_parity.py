@@ -115,8 +115,8 @@ def test_other_row_lengths_on_the_matrix_cores(d, Q):
     run_both(emb, off, q, cand, 10)
 
 
-@pytest.mark.parametrize("d,Q", [(64, 5), (64, 32), (64, 64), (96, 32), (96, 50), (128, 1), (128, 17), (128, 32),
-                                 (128, 33), (128, 64), (160, 32), (192, 7), (224, 32), (256, 32)])
+@pytest.mark.parametrize("d,Q", [(32, 32), (32, 64), (64, 5), (64, 32), (64, 64), (96, 32), (96, 50), (128, 1), (128, 17),
+                                 (128, 32), (128, 33), (128, 64), (160, 32), (192, 7), (224, 32), (256, 32)])
 def test_few_pairs_against_a_large_table_take_the_lane_linear_loads(d, Q):
     """With at most half as many (query, candidate) pairs as the table has documents, rows longer than 64 bytes
     are fetched lane-linearly with non-temporal loads and put in order through LDS; with more pairs every lane
@@ -149,7 +149,7 @@ def test_few_pairs_against_a_large_table_take_the_lane_linear_loads(d, Q):
 
 
 def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
-    """Under the default fetch mode every 16th scoring call samples the batch's candidate lists; the estimate (the
+    """Under the default fetch mode every 64th scoring call samples the batch's candidate lists; the estimate (the
     share of sampled pairs that repeat a document) separates uniformly drawn lists from lists that share popular
     documents, and scores are the same whichever way the rows are then fetched."""
     say("sharing estimate")
@@ -166,7 +166,7 @@ def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
     results = {}
     for name, cand in (("uniform", uniform), ("shared", shared), ("uniform again", uniform)):
         cand_d = torch.from_numpy(cand).to(DEV)
-        for call in range(16):                                  # the sample is taken on the first of every 16 calls
+        for call in range(64):                                  # the sample is taken on the first of every 64 calls
             scores = espn.espn_score(table, q_d, cand_d)
         torch.cuda.synchronize()
         results[name] = (espn.espn_table_sharing_estimate(table), scores.cpu().numpy())
@@ -174,7 +174,7 @@ def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
     assert 0.0 <= results["uniform"][0] < 0.05, results["uniform"][0]
     assert results["shared"][0] > 0.5, results["shared"][0]
     assert 0.0 <= results["uniform again"][0] < 0.05
-    # the first 16 calls on uniform lists were planned before any sample, the last 16 after the "shared" sample:
+    # the first 64 calls on uniform lists were planned before any sample, the last 64 after the "shared" sample:
     # whatever was chosen, the scores are the same bit for bit, and right
     assert np.array_equal(results["uniform"][1].view(np.int32), results["uniform again"][1].view(np.int32))
     assert_scores_close(results["shared"][1], oracle.scores(emb, off, q, shared), 32)
@@ -182,7 +182,7 @@ def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
     # a caller's choice switches the sampling off
     espn.espn_table_set_fetch(table, espn.ESPN_FETCH_CACHED)
     before = espn.espn_table_sharing_estimate(table)
-    for call in range(20):
+    for call in range(70):
         espn.espn_score(table, q_d, torch.from_numpy(shared).to(DEV))
     torch.cuda.synchronize()
     assert espn.espn_table_sharing_estimate(table) == before
