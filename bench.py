@@ -30,7 +30,7 @@ DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p
 # (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
 MEASURED_TRAFFIC_BYTES = {
     # (FETCH_SIZE KiB x 2.0 calibration + WRITE_SIZE KiB x 1.0) x 1024, MaxSim kernel, per launch
-    "c2": (88952.74 * 2.0 + 252.36) * 1024,          # profiles/maxsim_d32_c2_pmc.md
+    "c2": (88960.87 * 2.0 + 252.42) * 1024,          # profiles/maxsim_d32_c2_pmc.md
     "c3": (2262175.08 * 2.0 + 1173.36) * 1024,       # profiles/maxsim_d128_c3_pmc.md
     "c3e4m3": (1161113.45 * 2.0 + 1056.75) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
     "c4": (17564508.73 * 2.0 + 19738.29) * 1024,     # profiles/maxsim_d128_c4_pmc.md
