@@ -117,3 +117,53 @@ def test_random_shape_compressed(seed):
     magnitude = oracle.scores_e4m3(codes.numpy() & 0x7F, scale, off, np.abs(q), cand)     # sign bits cleared
     assert_scores_close(g_all.cpu().numpy(), o_all, Q, floor=cancellation_floor(magnitude, d, Q))
     table.free()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape_partial_and_with_a_prior(seed):
+    """The same shapes through partial re-ranking (Sec. 4.4; a random prefix length R) and through the
+    aggregated score (Sec. 3.1; a random prior and weight)."""
+    d, Q, B, K, k, N, emb, off, q, cand = draw_case(300 + seed)
+    if emb.shape[0] == 0:
+        pytest.skip("an empty table")
+    rng = np.random.default_rng(31000 + seed)
+    B = min(B, 50)
+    cand, q = np.ascontiguousarray(cand[:B]), np.ascontiguousarray(q[:B])
+    R = min(K, int(rng.choice([0, 1, 16, 64, 128, 256, 257, K // 2, K])))
+    alpha = float(rng.choice([0.0, 0.5, -2.0]))
+    say("partial / prior, seed %d: d=%d Q=%d B=%d K=%d k=%d R=%d alpha=%g N=%d" % (seed, d, Q, B, K, k, R, alpha, N))
+    table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
+    q_d, cand_d = torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
+
+    o_ids, o_sc = oracle.rerank_partial(emb, off, q, cand, R, k)
+    g_ids, g_sc = espn.espn_rerank_partial(table, q_d, cand_d, R, k)
+    espn.espn_table_check(table)
+    g_ids, g_sc = g_ids.cpu().numpy(), g_sc.cpu().numpy()
+    head = min(R, k)
+    # the appended tail is integer work: exact, and its scores are NaN on both sides
+    assert np.array_equal(g_ids[:, head:], o_ids[:, head:]) and np.array_equal(g_ids[:, head:], cand[:, head:k])
+    assert np.isnan(g_sc[:, head:]).all() and np.isnan(o_sc[:, head:]).all()
+    if head:
+        prefix = np.ascontiguousarray(cand[:, :R])
+        o_all = oracle.scores(emb, off, q, prefix)
+        floor = cancellation_floor(oracle.scores(np.abs(emb), off, np.abs(q), prefix), d, Q)
+        for b in sorted(set([0, B // 2, B - 1])):
+            assert_topk_matches(g_ids[b, :head], g_sc[b, :head], o_all[b], prefix[b], head, Q, floor=floor[b])
+
+    prior = (rng.normal(size=cand.shape) * 4).astype(np.float32)
+    o_tot = oracle.scores_prior(emb, off, q, cand, prior, alpha)
+    p_ids, p_top, ws = espn.espn_rerank_prior(table, q_d, cand_d, torch.from_numpy(prior).to(DEV), alpha, k)
+    espn.espn_table_check(table)
+    g_tot = ws[: 4 * B * K].view(torch.float32).view(B, K)
+    got = g_tot.cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isneginf(got), np.isneginf(o_tot))
+    # relative to the magnitudes that were added (the total itself may cancel to nearly nothing)
+    added = np.abs(oracle.scores(emb, off, q, cand)) + abs(alpha) * np.abs(prior)
+    tol = np.maximum(1e-3 * np.maximum(added, 1e-6 * Q),
+                     cancellation_floor(oracle.scores(np.abs(emb), off, np.abs(q), cand), d, Q))
+    fin = np.isfinite(o_tot)
+    assert np.all(np.abs(got[fin] - o_tot[fin]) <= tol[fin])
+    # the ranks of these totals: bit for bit those of the stand-alone ranking kernel on the same numbers
+    r_ids, r_top = espn.espn_topk(g_tot.contiguous(), cand_d, k)
+    assert torch.equal(p_ids, r_ids) and torch.equal(p_top.view(torch.int32), r_top.view(torch.int32))
+    table.free()
