@@ -373,13 +373,30 @@ struct SlicePlan {
 // slices of a fixed size that the dispatcher hands out as workgroups retire (measured on MI355X:
 // 125 candidates of 2.5 KB and 63 of 18 KB are the best sizes, +/- a factor 2 costs 1-2 %).
 // The kernel ranks as well when that leaves one slice of at most RANK_MAX candidates per query.
+//
+// Two refinements, both measured over batches of 1 to 768 queries with lists of 16 to 1000 candidates:
+// - the cut rounds down (floor(slots / B) slices, not ceil): a few workgroups more than the device holds
+//   run after the others, alone, and the launch takes as long as two rounds (136 queries of 256
+//   candidates, 64-byte rows: 25.8 us with 3 slices, 28.0 with 4; 192 queries: 2 slices beat 3 for every
+//   list length and both row lengths, by 2-8 %).  More than half the slots' worth of queries: 2 slices.
+// - a list short enough that 16 waves (8 for longer rows) finish it in a few documents each is not cut at
+//   all: the scoring kernel then ranks it, and the second launch, about 2.7 us, costs more than the
+//   documents a wave takes one after the other (64-byte rows, up to 4 documents per wave: 9.7 against
+//   12.3 us per batch of 1 to 64 queries with 64 candidates, 12.3 against 17.5 us at 192 queries; the
+//   crossover is at 6-7 documents per wave.  256-byte rows: up to 2 documents per wave, 10.7 against
+//   12.5 us for one query, 16.3 against 23.2 us for 192; at 4 per wave the cut list wins below 128 queries).
+constexpr int kUncutRounds32 = 4, kUncutRounds = 2;
 SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
 {
     const int waves = waves_per_workgroup(t->dim);
     const int slots = 2 * t->n_cu;
-    const int one_round = (slots + B - 1) / B;
+    int one_round = slots / std::max(B, 1);
+    if (one_round < 2) one_round = B < slots ? 2 : 1;
+    const bool uncut = k >= 1 && K <= espn::RANK_MAX &&
+                       (K + waves - 1) / waves <= (t->dim == 32 ? kUncutRounds32 : kUncutRounds);
     int slices;
-    if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, std::max(1, K / waves));
+    if (uncut) slices = 1;
+    else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, std::max(1, K / waves));
     else {
         // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
         const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);

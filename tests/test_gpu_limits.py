@@ -101,6 +101,17 @@ def test_plan_of_typical_shapes():
     # a batch that fits the device at once is cut to fill it once: 64 queries x 8 slices = 512 workgroups
     assert espn.espn_rerank_plan(t32, 64, 32, 1000, 10) == {"slices": 8, "slice": 125, "launches": 2}
     assert espn.espn_rerank_plan(t32, 1024, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
+    # the cut never makes more workgroups than the device holds at once: 192 queries x 2 slices, not x 3
+    assert espn.espn_rerank_plan(t32, 192, 32, 256, 10) == {"slices": 2, "slice": 128, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 136, 32, 400, 10) == {"slices": 3, "slice": 134, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 300, 32, 400, 10) == {"slices": 2, "slice": 200, "launches": 2}
+    # lists that the waves of one workgroup finish in a few documents each are not cut, whatever the batch:
+    # the scoring kernel ranks them (64-byte rows: 4 documents per wave of 16, longer rows: 2 per wave of 8)
+    assert espn.espn_rerank_plan(t32, 8, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
+    assert espn.espn_rerank_plan(t32, 8, 32, 65, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t128, 8, 32, 16, 10) == {"slices": 1, "slice": 16, "launches": 1}
+    assert espn.espn_rerank_plan(t128, 8, 32, 17, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t32, 8, 32, 64, 0)["slices"] > 1          # scoring alone is still spread out
     # shapes the matrix-core kernel does not take: one wave per candidate, a second launch ranks
     assert espn.espn_rerank_plan(t72, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
     assert espn.espn_rerank_plan(t32, 5, 65, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
