@@ -106,12 +106,23 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t128, 136, 32, 400, 10) == {"slices": 3, "slice": 134, "launches": 2}
     assert espn.espn_rerank_plan(t128, 300, 32, 400, 10) == {"slices": 2, "slice": 200, "launches": 2}
     # lists that the waves of one workgroup finish in a few documents each are not cut, whatever the batch:
-    # the scoring kernel ranks them (64-byte rows: 4 documents per wave of 16, longer rows: 2 per wave of 8)
+    # the scoring kernel ranks them (64-byte rows: 5 documents per wave of 16, longer rows: 2 per wave of 8)
     assert espn.espn_rerank_plan(t32, 8, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
-    assert espn.espn_rerank_plan(t32, 8, 32, 65, 10)["launches"] == 2
     assert espn.espn_rerank_plan(t128, 8, 32, 16, 10) == {"slices": 1, "slice": 16, "launches": 1}
     assert espn.espn_rerank_plan(t128, 8, 32, 17, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t32, 8, 32, 80, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t32, 8, 32, 81, 10)["launches"] == 2
     assert espn.espn_rerank_plan(t32, 8, 32, 64, 0)["slices"] > 1          # scoring alone is still spread out
+    # ... and longer lists stay whole from half a workgroup per compute unit on, where the cut has little left to
+    # spread the queries to (not where some compute units would get two workgroups and others one)
+    assert espn.espn_rerank_plan(t32, 192, 32, 112, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t32, 150, 32, 112, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t32, 300, 32, 112, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t32, 400, 32, 112, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t128, 100, 32, 32, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t128, 192, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
+    assert espn.espn_rerank_plan(t128, 300, 32, 64, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t128, 400, 32, 64, 10)["launches"] == 1
     # shapes the matrix-core kernel does not take: one wave per candidate, a second launch ranks
     assert espn.espn_rerank_plan(t72, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
     assert espn.espn_rerank_plan(t32, 5, 65, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}

@@ -80,13 +80,13 @@ def test_one_launch_path_at_eight_workgroups_per_compute_unit(K, k):
         assert_topk_matches(g_ids[b], g_sc[b], o_all[n], cand[b], k, 32)
 
 
-@pytest.mark.parametrize("d,B,K,k", [(32, 1, 64, 10), (32, 5, 49, 49), (32, 37, 64, 1), (32, 200, 33, 7),
-                                     (128, 1, 16, 10), (128, 9, 16, 16), (128, 130, 9, 3), (64, 6, 16, 5),
+@pytest.mark.parametrize("d,B,K,k", [(32, 1, 64, 10), (32, 5, 49, 49), (32, 37, 64, 1), (32, 200, 33, 7), (32, 3, 80, 10),
+                                     (32, 180, 112, 5), (32, 400, 100, 100), (128, 1, 16, 10), (128, 190, 64, 10), (128, 9, 16, 16), (128, 130, 9, 3), (64, 6, 16, 5),
                                      (192, 3, 8, 8)])
 def test_short_lists_of_small_batches_are_not_cut(d, B, K, k):
     """A list that the waves of one workgroup finish in a few documents each stays one slice however few the
     queries, so that the same launch ranks it (64-byte rows: up to 64 candidates; longer rows: 16, or 8 where
-    a workgroup has 4 waves)."""
+    a workgroup has 4 waves; more from half a workgroup per compute unit on)."""
     say("one launch, few queries: d=%d B=%d K=%d k=%d" % (d, B, K, k))
     emb, off, q, cand = random_problem(13 * K + d + B, 300, d, B, 32, K, 1, 40)
     if K > 2:
@@ -99,8 +99,8 @@ def test_short_lists_of_small_batches_are_not_cut(d, B, K, k):
 
 
 def test_lists_one_candidate_longer_are_cut_when_the_queries_are_few():
-    say("d=32 K=65 and d=128 K=17 with 8 queries: two launches")
-    emb, off, q, cand = random_problem(6, 300, 32, 8, 32, 65, 1, 20)
+    say("d=32 K=81 and d=128 K=17 with 8 queries: two launches")
+    emb, off, q, cand = random_problem(6, 300, 32, 8, 32, 81, 1, 20)
     both_paths(emb, off, q, cand, 10, expect_launches=2)
     emb, off, q, cand = random_problem(7, 300, 128, 8, 32, 17, 1, 20)
     both_paths(emb, off, q, cand, 10, expect_launches=2)
