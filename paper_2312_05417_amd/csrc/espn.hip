@@ -612,7 +612,10 @@ int enqueue_topk(const float *scores, const int64_t *cand, int ldc, int B, int K
     // falls back to k selection rounds once more than 64 entries survive its threshold).
     // More ranks: the whole list is sorted, at a cost independent of k (11 us for the same lists).
     // Lists beyond 4096 entries: k selection rounds over the list.
-    if (k <= 32 && K <= 64 * 16)
+    if (k <= 32 && K <= 64 * 4)
+        hipLaunchKernelGGL((topk_wave_kernel<4>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                           out_scores);
+    else if (k <= 32 && K <= 64 * 16)
         hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
                            out_scores);
     else if (k <= 32 && K <= 64 * 32)
