@@ -387,33 +387,35 @@ struct SlicePlan {
 //   9.7 against 12.3 us per batch of 1 to 64 queries, 12.3 against 15.8 at 192 queries.
 // Documents per wave up to which a rankable list stays uncut, by queries per compute unit (n_cu = 256 here;
 // whole path, us per batch, uncut against cut the way plan_slices cuts; "narrow" = 64-byte rows in workgroups of
-// 16 waves, "wide" = longer rows in workgroups of 8):
+// 16 waves, "wide" = longer rows in workgroups of 8, "codes" = 32-byte rows of E4M3 codes in workgroups of 16, for
+// which the cut list is cheaper than for binary16 rows: 80 candidates at 100 queries 13.5 uncut against 12.0 cut,
+// 96 candidates at 192 queries 16.4 against 15.2, but 64 candidates 9.2-12.4 against 11.7-13.7 at 16 to 256 queries):
 struct UncutBand {
     int num, den;           // the band ends at B = num / den * n_cu
-    int narrow, wide;
+    int narrow, wide, codes;
 };
 constexpr UncutBand kUncutBands[] = {
     // few queries: narrow, 80 candidates (5 per wave) 11.4 against 11.8 at 16 queries, 12.4 against 12.9 at 64;
     // 100 candidates 14.4 against 12.4 at 64.  Wide, 16 candidates (2 per wave) 12.4 against 12.8 at 16 queries;
     // 24 candidates 15.5 against 13.4
-    {3, 8, 5, 2},
+    {3, 8, 5, 2, 4},
     // 100-128 queries: wide, 32 candidates (4 per wave) 20.6 against 23.4; 64 candidates 33.5 against 29.6
-    {1, 2, 5, 4},
+    {1, 2, 5, 4, 4},
     // 129-170: narrow, 80 candidates 13.7 against 15.5, 112 candidates (7 per wave) 18.4 against 17.5;
     // wide, 64 candidates (8 per wave) 36.9 against 39.9
-    {2, 3, 6, 8},
+    {2, 3, 6, 8, 5},
     // up to one workgroup per compute unit: narrow, 192 queries, 64 candidates 12.3 against 15.8, 100 candidates
     // 17.8 against 19.4, 128 a tie; wide, 32 candidates 24.8 against 31.7, 64 candidates 41.6 against 49.0
-    {1, 1, 7, 8},
+    {1, 1, 7, 8, 5},
     // some compute units get two workgroups and others one: narrow, 320 queries, 80 candidates 21.4 against 23.0
     // but 112 candidates 28.0 against 27.1; wide, 32 candidates 42.9 against 44.3 but 64 candidates 75.6 against 72.1
-    {11, 8, 5, 4},
+    {11, 8, 5, 4, 5},
 };
 // ... and beyond (up to two per compute unit; from there on nothing is cut anyway): narrow, 400 queries, 112
 // candidates 30.3 against 32.5, 100 candidates 26.8 against 30.5; wide, 64 candidates 80.5 against 90.0
-constexpr UncutBand kUncutBeyond = {0, 1, 7, 8};
+constexpr UncutBand kUncutBeyond = {0, 1, 7, 8, 6};
 
-int uncut_rounds(int dim, int B, int n_cu)
+int uncut_rounds(int dim, int elem_bytes, int B, int n_cu)
 {
     const UncutBand *band = &kUncutBeyond;
     for (const UncutBand &b : kUncutBands)
@@ -421,7 +423,7 @@ int uncut_rounds(int dim, int B, int n_cu)
             band = &b;
             break;
         }
-    return dim == 32 ? band->narrow : band->wide;
+    return dim != 32 ? band->wide : elem_bytes == 1 ? band->codes : band->narrow;
 }
 
 SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
@@ -430,7 +432,7 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     const int slots = 2 * t->n_cu;
     int one_round = slots / std::max(B, 1);
     if (one_round < 2) one_round = B < slots ? 2 : 1;
-    const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, B, t->n_cu);
+    const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, B, t->n_cu);
     int slices;
     if (uncut) slices = 1;
     else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, std::max(1, K / waves));

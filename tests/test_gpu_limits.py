@@ -123,6 +123,14 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t128, 192, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
     assert espn.espn_rerank_plan(t128, 300, 32, 64, 10)["launches"] == 2
     assert espn.espn_rerank_plan(t128, 400, 32, 64, 10)["launches"] == 1
+    # rows of 32 E4M3 codes: the cut list is cheaper there, so the limits are lower
+    codes = torch.zeros((64, 32), dtype=torch.uint8, device=DEV)
+    t32c = espn.espn_table_load_e4m3(codes, np.ones(1, dtype=np.float32), np.array([0, 64], dtype=np.int64))
+    assert espn.espn_rerank_plan(t32c, 8, 32, 64, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t32c, 8, 32, 80, 10)["launches"] == 2
+    assert espn.espn_rerank_plan(t32c, 192, 32, 80, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t32c, 192, 32, 96, 10)["launches"] == 2
+    t32c.free()
     # shapes the matrix-core kernel does not take: one wave per candidate, a second launch ranks
     assert espn.espn_rerank_plan(t72, 5, 32, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
     assert espn.espn_rerank_plan(t32, 5, 65, 40, 3) == {"slices": 40, "slice": 1, "launches": 2}
