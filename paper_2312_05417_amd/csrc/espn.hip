@@ -405,8 +405,9 @@ constexpr UncutBand kUncutBands[] = {
     // wide, 64 candidates (8 per wave) 36.9 against 39.9
     {2, 3, 6, 8, 5},
     // up to one workgroup per compute unit: narrow, 192 queries, 64 candidates 12.3 against 15.8, 100 candidates
-    // 17.8 against 19.4, 128 a tie; wide, 32 candidates 24.8 against 31.7, 64 candidates 41.6 against 49.0
-    {1, 1, 7, 8, 5},
+    // 17.8 against 19.4, 128 a tie; wide, 32 candidates 24.8 against 31.7, 64 candidates 41.6 against 49.0, 128
+    // candidates (16 per wave) 77.7 against 83.2 (at 256 queries: 98.6 against 99.5)
+    {1, 1, 7, 16, 5},
     // some compute units get two workgroups and others one: narrow, 320 queries, 80 candidates 21.4 against 23.0
     // but 112 candidates 28.0 against 27.1; wide, 32 candidates 42.9 against 44.3 but 64 candidates 75.6 against 72.1
     {11, 8, 5, 4, 5},
@@ -430,12 +431,23 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
 {
     const int waves = waves_per_workgroup(t->dim);
     const int slots = 2 * t->n_cu;
-    int one_round = slots / std::max(B, 1);
+    // Rows longer than 64 bytes: the cut aims at ONE workgroup per compute unit, and it may leave half the waves of
+    // a workgroup without a document.  Every slice count timed for batches of 8 to 256 queries, 256-byte rows: the
+    // best is floor(n_cu / B) throughout, with a cliff right behind it (20 queries of 128 candidates: 17.9 us with
+    // 12 slices = 240 workgroups, 21.8 with 13 = 260; 64 queries: 32.9 us with 4 slices, 34.7 with 8; 100
+    // queries: 45.8 with 2, 47.5 with 5; 8 queries: 13.0 with 32 slices of 4, 14.1 with 16 of 8).  More than half
+    // a compute unit's worth of queries cannot have that and fill the two slots per compute unit instead (136-170
+    // queries: 3 slices beat 1, 2 and 4 by 2-25 %).  64-byte rows gain 1-8 % from the same rule at 20 to 48
+    // queries and nothing elsewhere, and keep two workgroups per compute unit.
+    const bool wide = t->dim != 32;
+    int one_round = (wide ? t->n_cu : slots) / std::max(B, 1);
+    if (one_round < 2) one_round = slots / std::max(B, 1);
     if (one_round < 2) one_round = B < slots ? 2 : 1;
+    const int most_slices = std::max(1, wide ? 2 * K / waves : K / waves);     // slices a list can usefully have
     const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, B, t->n_cu);
     int slices;
     if (uncut) slices = 1;
-    else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, std::max(1, K / waves));
+    else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
     else {
         // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
         const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);

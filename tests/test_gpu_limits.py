@@ -121,7 +121,16 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t32, 400, 32, 112, 10)["launches"] == 1
     assert espn.espn_rerank_plan(t128, 100, 32, 32, 10)["launches"] == 1
     assert espn.espn_rerank_plan(t128, 192, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
+    assert espn.espn_rerank_plan(t128, 192, 32, 128, 10)["launches"] == 1
+    assert espn.espn_rerank_plan(t128, 170, 32, 128, 10)["launches"] == 2
     assert espn.espn_rerank_plan(t128, 300, 32, 64, 10)["launches"] == 2
+    # rows longer than 64 bytes are cut for ONE workgroup per compute unit (64-byte rows: two), and may leave
+    # half the waves of a workgroup without a document
+    assert espn.espn_rerank_plan(t128, 64, 32, 300, 10) == {"slices": 4, "slice": 75, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 64, 32, 300, 10) == {"slices": 8, "slice": 38, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 20, 32, 128, 10) == {"slices": 12, "slice": 11, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 8, 32, 128, 10) == {"slices": 32, "slice": 4, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 150, 32, 300, 10) == {"slices": 3, "slice": 100, "launches": 2}
     assert espn.espn_rerank_plan(t128, 400, 32, 64, 10)["launches"] == 1
     # rows of 32 E4M3 codes: the cut list is cheaper there, so the limits are lower
     codes = torch.zeros((64, 32), dtype=torch.uint8, device=DEV)
