@@ -447,6 +447,12 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, B, t->n_cu);
     int slices;
     if (uncut) slices = 1;
+    // 64-byte rows, more than two thirds of a workgroup per compute unit and at most one: a list too long to be
+    // ranked by the scoring kernel also stays whole, one workgroup of 16 waves per compute unit (uncut against the
+    // cut it replaces, alternating in one run: 192 queries, 34.6 against 37.3 us at 300 candidates, 58.6 against
+    // 59.0 at 600, 90.2 against 91.2 at 1000; 224 queries, 65.2 against 71.8 at 600, 101.3 against 104.2 at 1000;
+    // 256 queries, 73.8 against 76.0 at 600, 114.7 against 117.3 at 1000)
+    else if (!wide && K > espn::RANK_MAX && K <= espn::MAX_SLICE && 3 * B > 2 * t->n_cu && B <= t->n_cu) slices = 1;
     else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
     else {
         // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes

@@ -131,6 +131,11 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t128, 20, 32, 128, 10) == {"slices": 12, "slice": 11, "launches": 2}
     assert espn.espn_rerank_plan(t128, 8, 32, 128, 10) == {"slices": 32, "slice": 4, "launches": 2}
     assert espn.espn_rerank_plan(t128, 150, 32, 300, 10) == {"slices": 3, "slice": 100, "launches": 2}
+    # 64-byte rows, 171 to 256 queries: longer lists stay whole too (one workgroup of 16 waves per compute unit)
+    assert espn.espn_rerank_plan(t32, 192, 32, 600, 10) == {"slices": 1, "slice": 600, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 170, 32, 600, 10)["slices"] > 1
+    assert espn.espn_rerank_plan(t32, 257, 32, 600, 10)["slices"] > 1
+    assert espn.espn_rerank_plan(t32, 192, 32, 1025, 10)["slices"] > 1
     assert espn.espn_rerank_plan(t128, 400, 32, 64, 10)["launches"] == 1
     # rows of 32 E4M3 codes: the cut list is cheaper there, so the limits are lower
     codes = torch.zeros((64, 32), dtype=torch.uint8, device=DEV)
