@@ -374,7 +374,8 @@ struct SlicePlan {
 // 125 candidates of 2.5 KB and 63 of 18 KB are the best sizes, +/- a factor 2 costs 1-2 %).
 // The kernel ranks as well when that leaves one slice of at most RANK_MAX candidates per query.
 //
-// Two refinements, both measured over batches of 1 to 768 queries with lists of 16 to 1000 candidates:
+// Refinements, all measured over batches of 1 to 768 queries with lists of 16 to 1000 candidates (two here, two
+// more where plan_slices applies them):
 // - the cut rounds down (floor(slots / B) slices, not ceil): a few workgroups more than the device holds
 //   run after the others, alone, and the launch takes as long as two rounds (136 queries of 256
 //   candidates, 64-byte rows: 25.8 us with 3 slices, 28.0 with 4; 192 queries: 2 slices beat 3 for every
