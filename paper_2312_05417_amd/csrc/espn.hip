@@ -391,33 +391,39 @@ struct SlicePlan {
 // 16 waves, "wide" = longer rows in workgroups of 8, "codes" = 32-byte rows of E4M3 codes in workgroups of 16, for
 // which the cut list is cheaper than for binary16 rows: 80 candidates at 100 queries 13.5 uncut against 12.0 cut,
 // 96 candidates at 192 queries 16.4 against 15.2, but 64 candidates 9.2-12.4 against 11.7-13.7 at 16 to 256 queries):
+// "wide, cached" = the longer rows when the lists of a batch share documents and the rows are fetched with ordinary
+// loads (each lane its own part of a row): a document costs more there while the launch is short, so lists of few
+// queries are cut sooner (Zipf lists, 16 queries of 16 candidates: 16.6 uncut against 12.5 cut, 100 queries of 32:
+// 26.2 against 21.7, 150 queries of 64: 43.6 against 41.0; from 171 queries on uncut wins as before, 192 queries of
+// 128 candidates: 76.9 against 84.3).  64-byte rows keep their limits under such lists (64 candidates: 9.6-14.5
+// against 12.0-17.0 at 16 to 400 queries; 112 candidates at 256 queries: 18.2 against 17.0).
 struct UncutBand {
     int num, den;           // the band ends at B = num / den * n_cu
-    int narrow, wide, codes;
+    int narrow, wide, codes, wide_cached;
 };
 constexpr UncutBand kUncutBands[] = {
     // few queries: narrow, 80 candidates (5 per wave) 11.4 against 11.8 at 16 queries, 12.4 against 12.9 at 64;
     // 100 candidates 14.4 against 12.4 at 64.  Wide, 16 candidates (2 per wave) 12.4 against 12.8 at 16 queries;
     // 24 candidates 15.5 against 13.4
-    {3, 8, 5, 2, 4},
+    {3, 8, 5, 2, 4, 1},
     // 100-128 queries: wide, 32 candidates (4 per wave) 20.6 against 23.4; 64 candidates 33.5 against 29.6
-    {1, 2, 5, 4, 4},
+    {1, 2, 5, 4, 4, 2},
     // 129-170: narrow, 80 candidates 13.7 against 15.5, 112 candidates (7 per wave) 18.4 against 17.5;
     // wide, 64 candidates (8 per wave) 36.9 against 39.9
-    {2, 3, 6, 8, 5},
+    {2, 3, 6, 8, 5, 4},
     // up to one workgroup per compute unit: narrow, 192 queries, 64 candidates 12.3 against 15.8, 100 candidates
     // 17.8 against 19.4, 128 a tie; wide, 32 candidates 24.8 against 31.7, 64 candidates 41.6 against 49.0, 128
     // candidates (16 per wave) 77.7 against 83.2 (at 256 queries: 98.6 against 99.5)
-    {1, 1, 7, 16, 5},
+    {1, 1, 7, 16, 5, 16},
     // some compute units get two workgroups and others one: narrow, 320 queries, 80 candidates 21.4 against 23.0
     // but 112 candidates 28.0 against 27.1; wide, 32 candidates 42.9 against 44.3 but 64 candidates 75.6 against 72.1
-    {11, 8, 5, 4, 5},
+    {11, 8, 5, 4, 5, 4},
 };
 // ... and beyond (up to two per compute unit; from there on nothing is cut anyway): narrow, 400 queries, 112
 // candidates 30.3 against 32.5, 100 candidates 26.8 against 30.5; wide, 64 candidates 80.5 against 90.0
-constexpr UncutBand kUncutBeyond = {0, 1, 7, 8, 6};
+constexpr UncutBand kUncutBeyond = {0, 1, 7, 8, 6, 8};
 
-int uncut_rounds(int dim, int elem_bytes, int B, int n_cu)
+int uncut_rounds(int dim, int elem_bytes, bool streaming, int B, int n_cu)
 {
     const UncutBand *band = &kUncutBeyond;
     for (const UncutBand &b : kUncutBands)
@@ -425,50 +431,12 @@ int uncut_rounds(int dim, int elem_bytes, int B, int n_cu)
             band = &b;
             break;
         }
-    return dim != 32 ? band->wide : elem_bytes == 1 ? band->codes : band->narrow;
+    if (dim != 32) return streaming ? band->wide : band->wide_cached;
+    return elem_bytes == 1 ? band->codes : band->narrow;
 }
 
 SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
 {
-    const int waves = waves_per_workgroup(t->dim);
-    const int slots = 2 * t->n_cu;
-    // Rows longer than 64 bytes: the cut aims at ONE workgroup per compute unit, and it may leave half the waves of
-    // a workgroup without a document.  Every slice count timed for batches of 8 to 256 queries, 256-byte rows: the
-    // best is floor(n_cu / B) throughout, with a cliff right behind it (20 queries of 128 candidates: 17.9 us with
-    // 12 slices = 240 workgroups, 21.8 with 13 = 260; 64 queries: 32.9 us with 4 slices, 34.7 with 8; 100
-    // queries: 45.8 with 2, 47.5 with 5; 8 queries: 13.0 with 32 slices of 4, 14.1 with 16 of 8).  More than half
-    // a compute unit's worth of queries cannot have that and fill the two slots per compute unit instead (136-170
-    // queries: 3 slices beat 1, 2 and 4 by 2-25 %).  64-byte rows gain 1-8 % from the same rule at 20 to 48
-    // queries and nothing elsewhere, and keep two workgroups per compute unit.
-    const bool wide = t->dim != 32;
-    int one_round = (wide ? t->n_cu : slots) / std::max(B, 1);
-    if (one_round < 2) one_round = slots / std::max(B, 1);
-    if (one_round < 2) one_round = B < slots ? 2 : 1;
-    const int most_slices = std::max(1, wide ? 2 * K / waves : K / waves);     // slices a list can usefully have
-    const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, B, t->n_cu);
-    int slices;
-    if (uncut) slices = 1;
-    // 64-byte rows, more than two thirds of a workgroup per compute unit and at most one: a list too long to be
-    // ranked by the scoring kernel also stays whole, one workgroup of 16 waves per compute unit (uncut against the
-    // cut it replaces, alternating in one run: 192 queries, 34.6 against 37.3 us at 300 candidates, 58.6 against
-    // 59.0 at 600, 90.2 against 91.2 at 1000; 224 queries, 65.2 against 71.8 at 600, 101.3 against 104.2 at 1000;
-    // 256 queries, 73.8 against 76.0 at 600, 114.7 against 117.3 at 1000)
-    else if (!wide && K > espn::RANK_MAX && K <= espn::MAX_SLICE && 3 * B > 2 * t->n_cu && B <= t->n_cu) slices = 1;
-    else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
-    else {
-        // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
-        const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);
-        slices = (K + per_slice - 1) / per_slice;
-    }
-    slices = std::max(slices, (K + espn::MAX_SLICE - 1) / espn::MAX_SLICE);
-    SlicePlan p;
-    p.slice = (K + slices - 1) / slices;
-    p.slices = (K + p.slice - 1) / p.slice;
-    p.rank = p.slices == 1 && K <= espn::RANK_MAX && k >= 1;
-    const int64_t workgroups = (int64_t)B * p.slices;
-    p.waves = waves;
-    if (t->dim == 32 && workgroups >= 4 * (int64_t)t->n_cu) p.waves = kNarrowWaves;
-    if (t->dim == 128 && t->elem_bytes == 2 && workgroups >= 8 * (int64_t)t->n_cu) p.waves = kNarrowWaves128;     // Q <= 32 only
     // Rows of 128 bytes and more can be fetched in two ways.  Each lane loading its own D/2 contiguous bytes
     // needs no transpose, but its four instructions come back to every cache line, so the lines have to stay
     // cached: ordinary loads.  Lane-linear loads take whole lines with one instruction each and can be
@@ -485,7 +453,45 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     // 64-byte rows are fetched lane-linearly either way, so only the hint is at stake: non-temporal unless a
     // sample has shown overlapping lists (uniform lists, 1024 queries: 1.9 % faster; Zipf lists: 27-36 % slower)
     if (t->dim == 32) streaming = !(overlap >= kShareThreshold);
-    p.linear = t->fetch == ESPN_FETCH_STREAMING || (t->fetch == ESPN_FETCH_AUTO && streaming);
+    // (a host-resident table is scored from a staging slot, which holds each document once for all the queries that
+    // list it: ordinary loads)
+    const bool linear = t->residency == ESPN_RESIDENT_HBM &&
+                        (t->fetch == ESPN_FETCH_STREAMING || (t->fetch == ESPN_FETCH_AUTO && streaming));
+
+    const int waves = waves_per_workgroup(t->dim);
+    const int slots = 2 * t->n_cu;
+    // Rows longer than 64 bytes: the cut aims at ONE workgroup per compute unit, and it may leave half the waves of
+    // a workgroup without a document.  Every slice count timed for batches of 8 to 256 queries, 256-byte rows: the
+    // best is floor(n_cu / B) throughout, with a cliff right behind it (20 queries of 128 candidates: 17.9 us with
+    // 12 slices = 240 workgroups, 21.8 with 13 = 260; 64 queries: 32.9 us with 4 slices, 34.7 with 8; 100
+    // queries: 45.8 with 2, 47.5 with 5; 8 queries: 13.0 with 32 slices of 4, 14.1 with 16 of 8).  More than half
+    // a compute unit's worth of queries cannot have that and fill the two slots per compute unit instead (136-170
+    // queries: 3 slices beat 1, 2 and 4 by 2-25 %).  64-byte rows gain 1-8 % from the same rule at 20 to 48
+    // queries and nothing elsewhere, and keep two workgroups per compute unit.
+    const bool wide = t->dim != 32;
+    int one_round = (wide ? t->n_cu : slots) / std::max(B, 1);
+    if (one_round < 2) one_round = slots / std::max(B, 1);
+    if (one_round < 2) one_round = B < slots ? 2 : 1;
+    const int most_slices = std::max(1, wide ? 2 * K / waves : K / waves);     // slices a list can usefully have
+    const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, linear, B, t->n_cu);
+    int slices;
+    if (uncut) slices = 1;
+    else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
+    else {
+        // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
+        const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);
+        slices = (K + per_slice - 1) / per_slice;
+    }
+    slices = std::max(slices, (K + espn::MAX_SLICE - 1) / espn::MAX_SLICE);
+    SlicePlan p;
+    p.slice = (K + slices - 1) / slices;
+    p.slices = (K + p.slice - 1) / p.slice;
+    p.rank = p.slices == 1 && K <= espn::RANK_MAX && k >= 1;
+    const int64_t workgroups = (int64_t)B * p.slices;
+    p.waves = waves;
+    if (t->dim == 32 && workgroups >= 4 * (int64_t)t->n_cu) p.waves = kNarrowWaves;
+    if (t->dim == 128 && t->elem_bytes == 2 && workgroups >= 8 * (int64_t)t->n_cu) p.waves = kNarrowWaves128;     // Q <= 32 only
+    p.linear = linear;
     return p;
 }
 
