@@ -466,17 +466,40 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     // 12 slices = 240 workgroups, 21.8 with 13 = 260; 64 queries: 32.9 us with 4 slices, 34.7 with 8; 100
     // queries: 45.8 with 2, 47.5 with 5; 8 queries: 13.0 with 32 slices of 4, 14.1 with 16 of 8).  More than half
     // a compute unit's worth of queries cannot have that and fill the two slots per compute unit instead (136-170
-    // queries: 3 slices beat 1, 2 and 4 by 2-25 %).  64-byte rows gain 1-8 % from the same rule at 20 to 48
-    // queries and nothing elsewhere, and keep two workgroups per compute unit.
+    // queries: 3 slices beat 1, 2 and 4 by 2-25 %).  171 to 192 queries, for which that would be 2 slices, take 4,
+    // three workgroups per compute unit (192 queries of 300 candidates: 165.7 us against 175.7; under Zipf lists 144.4
+    // against 174.0; as E4M3 codes 93.0 against 98.2), and 193 to 256 queries no longer fit a whole number of
+    // workgroups per compute unit with so few slices (200 queries of 500 candidates: 296 us with 3 slices, 276 with
+    // 5; Zipf lists 284 against 244; E4M3 165 against 151; from 224 queries on all counts are within a few per cent).  64-byte rows gain 1-8 % from the
+    // one-per-compute-unit rule at 20 to 48 queries and nothing elsewhere, and keep two workgroups per compute unit.
     const bool wide = t->dim != 32;
     int one_round = (wide ? t->n_cu : slots) / std::max(B, 1);
     if (one_round < 2) one_round = slots / std::max(B, 1);
+    bool fixed = false;
+    if (wide && one_round == 2 && B <= t->n_cu) {
+        one_round = 3 * t->n_cu / B;
+        if (one_round < 4) {
+            // the count of 4 to 12 slices whose workgroups come closest, from below, to a whole number per compute
+            // unit, fewer slices preferred (196-200 queries: 5, 980-1000 workgroups; 210: 6; 240: 4); a full device's
+            // worth of queries keeps the fixed slices
+            fixed = B == t->n_cu;
+            double best = -1.;
+            for (int s = 4; s <= 12 && !fixed; ++s) {
+                const int64_t groups = (int64_t)B * s, rounds = (groups + t->n_cu - 1) / t->n_cu;
+                const double score = (double)groups / (double)(rounds * t->n_cu) - 0.02 * s;
+                if (score > best) {
+                    best = score;
+                    one_round = s;
+                }
+            }
+        }
+    }
     if (one_round < 2) one_round = B < slots ? 2 : 1;
     const int most_slices = std::max(1, wide ? 2 * K / waves : K / waves);     // slices a list can usefully have
     const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, linear, B, t->n_cu);
     int slices;
     if (uncut) slices = 1;
-    else if ((K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
+    else if (!fixed && (K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
     else {
         // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
         const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);

@@ -134,6 +134,13 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t128, 20, 32, 128, 10) == {"slices": 12, "slice": 11, "launches": 2}
     assert espn.espn_rerank_plan(t128, 8, 32, 128, 10) == {"slices": 32, "slice": 4, "launches": 2}
     assert espn.espn_rerank_plan(t128, 150, 32, 300, 10) == {"slices": 3, "slice": 100, "launches": 2}
+    # 171 to 255 queries: the slice count whose workgroups come closest, from below, to a whole number per compute
+    # unit; a full device's worth of queries keeps the fixed slices (the c3 shape)
+    assert espn.espn_rerank_plan(t128, 192, 32, 600, 10) == {"slices": 4, "slice": 150, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 200, 32, 600, 10) == {"slices": 5, "slice": 120, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 210, 32, 600, 10) == {"slices": 6, "slice": 100, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 240, 32, 600, 10) == {"slices": 4, "slice": 150, "launches": 2}
+    assert espn.espn_rerank_plan(t128, 256, 32, 1000, 10) == {"slices": 16, "slice": 63, "launches": 2}
     # rows fetched with ordinary loads (lists that share documents): a document costs more while the launch is
     # short, so the lists of few queries are cut sooner; from 171 queries on the limits are the same
     espn.espn_table_set_fetch(t128, espn.ESPN_FETCH_CACHED)
