@@ -476,7 +476,11 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     int one_round = (wide ? t->n_cu : slots) / std::max(B, 1);
     if (one_round < 2) one_round = slots / std::max(B, 1);
     bool fixed = false;
-    if (wide && one_round == 2 && B <= t->n_cu) {
+    if (one_round == 2 && B <= t->n_cu && (wide || 3 * t->n_cu / B >= 4)) {
+        // (171 to 192 queries: 4 slices for 64-byte rows too: 1000 candidates 83.7-90.1 us against 86.6-91.2 with
+        // the fixed slices, 300 candidates 33.3-35.4 against 36.5-37.3 with 2; under Zipf lists 67.5-69.0 against
+        // 72.4-72.5 and 27.0-27.5 against 29.4-30.0; as E4M3 codes 58.5-61.7 against 59.2-60.8 and 26.3-26.9
+        // against 27.3-27.5.  From 193 queries on no count is better for them in all three settings.)
         one_round = 3 * t->n_cu / B;
         if (one_round < 4) {
             // the count of 4 to 12 slices whose workgroups come closest, from below, to a whole number per compute

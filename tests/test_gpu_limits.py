@@ -102,7 +102,9 @@ def test_plan_of_typical_shapes():
     assert espn.espn_rerank_plan(t32, 64, 32, 1000, 10) == {"slices": 8, "slice": 125, "launches": 2}
     assert espn.espn_rerank_plan(t32, 1024, 32, 64, 10) == {"slices": 1, "slice": 64, "launches": 1}
     # the cut never makes more workgroups than the device holds at once: 192 queries x 2 slices, not x 3
-    assert espn.espn_rerank_plan(t32, 192, 32, 256, 10) == {"slices": 2, "slice": 128, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 200, 32, 256, 10) == {"slices": 2, "slice": 128, "launches": 2}
+    assert espn.espn_rerank_plan(t32, 192, 32, 256, 10) == {"slices": 4, "slice": 64, "launches": 2}      # 3 per compute unit
+    assert espn.espn_rerank_plan(t32, 192, 32, 1000, 10) == {"slices": 4, "slice": 250, "launches": 2}
     assert espn.espn_rerank_plan(t128, 136, 32, 400, 10) == {"slices": 3, "slice": 134, "launches": 2}
     assert espn.espn_rerank_plan(t128, 300, 32, 400, 10) == {"slices": 2, "slice": 200, "launches": 2}
     # (the limits for rows longer than 64 bytes depend on how the rows are fetched: say which, this table of one
