@@ -174,6 +174,25 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * espn_rerank for callers that cannot allocate device memory and have no workspace to hand in: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  The B*K scores that espn_rerank keeps
+ * in the caller's workspace go to a fixed array inside the library's code object instead (one copy per device,
+ * sizeof(float) * ESPN_NOALLOC_MAX_PAIRS bytes, held until the process ends); its address on the table's device
+ * was looked up when the table was loaded.  The call allocates and frees nothing, on the host or on the device.
+ *
+ *   Arguments and results as espn_rerank (same kernels, same bits); B * K <= ESPN_NOALLOC_MAX_PAIRS,
+ *   ESPN_ERR_SHAPE beyond.
+ * All calls on one device share the array, whatever table or stream they name: two calls whose kernels may
+ * overlap in time (different streams, or different host threads) race on it and must be ordered by the caller;
+ * calls on one stream are ordered already.  Afterwards the array holds the scores of the last call.
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP.
+ */
+#define ESPN_NOALLOC_MAX_PAIRS (4 * 1024 * 1024)
+int espn_rerank_noalloc(espn_table *table, const void *q, const int64_t *cand,
+                        int32_t B, int32_t Q, int32_t K, int32_t k,
+                        int64_t *out_ids, float *out_scores, void *stream);
+
+/*
  * How espn_rerank (and its variants) would run a batch of this shape on this table: the candidate list
  * of a query is cut into `slices` runs of `slice` candidates, one workgroup each; `launches` is 1 if the
  * scoring kernel also ranks (one slice of at most 256 candidates per query), 2 if the stand-alone ranking kernel

@@ -39,6 +39,7 @@ SIGNATURES = {
     "espn_rerank_plan": (ctypes.c_int, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_i32),
                                         ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
     "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "espn_rerank_noalloc": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
     "espn_rerank_partial": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
                                            _c_p, _c_sz, _c_p]),
     "espn_rerank_prior": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_p, ctypes.c_float, _c_i32, _c_i32, _c_i32, _c_i32,
@@ -261,6 +262,22 @@ def espn_rerank(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_i
     _check(lib().espn_rerank(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"), B, Q, K, k,
                              _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_scores
+
+
+ESPN_NOALLOC_MAX_PAIRS = 4 * 1024 * 1024
+
+
+def espn_rerank_noalloc(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_ids: torch.Tensor,
+                        out_scores: torch.Tensor, stream=None):
+    """espn_rerank without a workspace: the library's static scratch holds the scores.  The outputs are the
+    caller's (this wrapper allocates nothing either)."""
+    B, Q, K = _batch_shape(q, cand)
+    if q.shape[2] != table.dim:
+        raise ValueError("q has dim %d, table has %d" % (q.shape[2], table.dim))
+    _check(lib().espn_rerank_noalloc(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"),
+                                     B, Q, K, k, _dev(out_ids, torch.int64, "out_ids"),
+                                     _dev(out_scores, torch.float32, "out_scores"), _stream_ptr(stream)))
     return out_ids, out_scores
 
 

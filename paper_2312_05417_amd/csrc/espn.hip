@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -57,6 +58,8 @@ struct DeviceScope {
 };
 
 constexpr size_t kAlign = 256;
+// Most devices a process is expected to see (the per-device address of the static scratch is kept in a table).
+constexpr int kMaxDevices = 64;
 // Workgroups of the host-to-HBM copy kernel: 32 x 4 waves x 8 KiB = 1 MiB of reads in flight.  PCIe needs
 // about 64 GB/s x 5 us = 0.3 MiB to stay busy (measured: 8 workgroups reach 45 GB/s, 16 and more 56-57 GB/s),
 // and every host read that waits in the memory system's queues delays the HBM reads of the scoring kernel
@@ -64,6 +67,32 @@ constexpr size_t kAlign = 256;
 constexpr unsigned kGatherBlocks = 32;
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+}  // namespace
+
+// Scratch of espn_rerank_noalloc: the scores of one batch, up to ESPN_NOALLOC_MAX_PAIRS of them, in an array
+// that is part of the code object, so that the call has nothing to allocate.  Every device the library runs on
+// holds a copy of its own at an address of its own; in host code the name below is only a handle for
+// hipGetSymbolAddress, never an address to pass to a kernel.
+static __device__ __align__(256) unsigned char scratch[sizeof(float) * (size_t)ESPN_NOALLOC_MAX_PAIRS];
+
+namespace {
+std::mutex g_scratch_mutex;
+void *g_scratch_of_device[kMaxDevices] = {};
+
+// Address of `scratch` on `device`, which must be the current device; asked for once per device.
+int scratch_address(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(ESPN_ERR_UNSUPPORTED, "device %d is beyond the %d this build tracks", device, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_of_device[device]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ESPN_ERR_HIP, "hipGetSymbolAddress gave no address for the static scratch on device %d", device);
+        g_scratch_of_device[device] = p;
+    }
+    *out = g_scratch_of_device[device];
+    return ESPN_OK;
+}
 }  // namespace
 
 // One HBM staging slot of a host-resident table (all device memory, owned by the table).
@@ -100,6 +129,7 @@ struct espn_table {
     int32_t elem_bytes = 2;          // 2: binary16 rows, 1: E4M3 codes
     int64_t *off_dev = nullptr;      // owned, [n_docs + 1]
     unsigned *err_dev = nullptr;     // owned, one flag word
+    void *static_scratch = nullptr;  // this device's copy of the file-scope scratch array (espn_rerank_noalloc)
     int n_cu = 256;                  // compute units of the device
     int64_t n_docs = 0;
     int64_t total_rows = 0;
@@ -233,13 +263,16 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
             e = hipMemcpy(t->scale_dev, doc_scale_host, sizeof(float) * (size_t)n_docs, hipMemcpyHostToDevice);
     }
     if (e == hipSuccess) e = hipDeviceSynchronize();
-    if (e != hipSuccess) {
+    int scratch_rc = ESPN_OK;
+    if (e == hipSuccess) scratch_rc = scratch_address(device, &t->static_scratch);      // `device` is current here
+    if (e != hipSuccess || scratch_rc != ESPN_OK) {
         (void)hipFree(t->off_dev);
         (void)hipFree(t->err_dev);
         (void)hipFree(t->scale_dev);
         if (t->share_host) (void)hipHostFree(t->share_host);
         delete[] t->off_host;
         delete t;
+        if (e == hipSuccess) return scratch_rc;           // the message is already set
         return fail(e == hipErrorOutOfMemory ? ESPN_ERR_NOMEM : ESPN_ERR_HIP, "table set-up failed: %s",
                     hipGetErrorString(e));
     }
@@ -790,6 +823,24 @@ ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace,
                           st);
+}
+
+ESPN_API int espn_rerank_noalloc(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q,
+                                 int32_t K, int32_t k, int64_t *out_ids, float *out_scores, void *stream)
+{
+    if (int rc = check_batch(table, q, cand, B, Q, K)) return rc;
+    if ((int64_t)B * K > (int64_t)ESPN_NOALLOC_MAX_PAIRS)
+        return fail(ESPN_ERR_SHAPE, "B * K = %lld pairs exceed the %lld the static scratch holds", (long long)B * K,
+                    (long long)ESPN_NOALLOC_MAX_PAIRS);
+    void *ws = table->static_scratch;
+    if (int rc = check_rerank_outputs(B, K, k, out_ids, out_scores, ws, sizeof(float) * (size_t)ESPN_NOALLOC_MAX_PAIRS))
+        return rc;
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    if (table->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
+    return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, ws,
+                          static_cast<hipStream_t>(stream));
 }
 
 ESPN_API int espn_rerank_partial(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q,
