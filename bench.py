@@ -1,17 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the re-ranking hot path (candidate gather + MaxSim + ranked top-k) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c1|c2|c3|c4|c5|c5pinned|...]
 
-One step = one pass of the whole path (espn_rerank) over one batch of synthetic input that is
-already resident in HBM.  Successive steps use different pre-drawn candidate sets and queries, so
-that a batch is not simply served from the last-level cache.  Prints ONE JSON line.
+One step = one pass of the whole path over one batch of synthetic input that is already resident in HBM
+(host-resident workloads: one prefetch + one staged re-rank).  Successive steps use different pre-drawn
+candidate sets and queries, so that a batch is not simply served from the last-level cache.
+
+The default (`--workload all`) measures every configuration in one process and prints ONE JSON line: the
+headline fields are those of c4, the largest configuration a single GPU holds in HBM, and `configs` carries
+c3, c2 and the two host-resident runs (c5 at its stated size from ordinary host memory, and the largest
+table the machine lets a process pin) with their own ms_per_step, roofline, cpu_baseline and parity.
+The timed regions of the HBM-resident configurations run back to back (inputs of all of them are set up
+first), each exactly W warm-up and K timed steps; the per-kernel legs and the CPU oracle come afterwards.
 """
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,58 +30,434 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, raw
-DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 12, "c2p64": 400, "c3p64": 100,
+DEFAULT_STEPS = {"c1": 200, "c2": 400, "c3": 100, "c4": 12, "c5": 12, "c5pinned": 12, "c2p64": 400, "c3p64": 100,
                  "c2e4m3": 400, "c3e4m3": 100, "c5e4m3": 12}
-DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c2p64": 16, "c3p64": 4, "c2e4m3": 32, "c3e4m3": 8,
-                "c5e4m3": 3}
-
-# HBM bytes per score-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/*.md give the commands and the copy-kernel calibration); None until measured.
-MEASURED_TRAFFIC_BYTES = {
-    # (FETCH_SIZE KiB x 2.0 calibration + WRITE_SIZE KiB x 1.0) x 1024, MaxSim kernel, per launch
-    "c2": (88960.87 * 2.0 + 252.42) * 1024,          # profiles/maxsim_d32_c2_pmc.md
-    "c3": (2262175.08 * 2.0 + 1173.36) * 1024,       # profiles/maxsim_d128_c3_pmc.md
-    "c3e4m3": (1161113.45 * 2.0 + 1056.75) * 1024,   # profiles/maxsim_d128_c3e4m3_pmc.md
-    "c4": (17564508.73 * 2.0 + 19738.29) * 1024,     # profiles/maxsim_d128_c4_pmc.md
-}
+DEFAULT_SETS = {"c1": 16, "c2": 32, "c3": 8, "c4": 2, "c5": 3, "c5pinned": 3, "c2p64": 16, "c3p64": 4, "c2e4m3": 32,
+                "c3e4m3": 8, "c5e4m3": 3}
+HOST_WORKLOADS = ("c5", "c5pinned", "c5e4m3")
+ALL = ("c4", "c3", "c2", "c5", "c5pinned")        # the default run: headline first
+SHORT_STEPS = ("c1", "c2", "c2p64", "c2e4m3")     # steps of tens of microseconds
 
 
 def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def run_host_resident(args, w, seed, steps, warmup, n_sets):
-    """Table in pinned host memory; batch n+1 is prefetched over PCIe on a side stream into one HBM
-    staging slot while batch n is scored from the other."""
+_ORACLE_THREADS = None
+
+
+def oracle_threads() -> int:
+    """Threads the oracle runs on when it is given all of them: asked once, before any one-thread leg (a thread
+    count handed to the oracle stays in force for its later calls)."""
+    global _ORACLE_THREADS
+    if _ORACLE_THREADS is None:
+        import oracle
+        _ORACLE_THREADS = oracle.max_threads()
+    return _ORACLE_THREADS
+
+
+# ------------------------------------------------------------------------------------------------------
+# Hardware byte counters.  They are collected by separate rocprofv3 --pmc runs (one counter per run) whose
+# summaries are tracked under profiles/*_pmc.md; each summary carries one machine-readable line
+#     <!-- bench-traffic {json} -->
+# naming the workload, the kernel instantiation, the batch shape and the slice plan it was taken at.  A run
+# reports `traffic` only if all of that equals what it launches itself; otherwise null.
+# ------------------------------------------------------------------------------------------------------
+def measured_traffic(signature: dict):
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_pmc.md"))):
+        for m in re.finditer(r"<!-- bench-traffic (\{.*?\}) -->", open(path).read()):
+            try:
+                rec = json.loads(m.group(1))
+            except ValueError:
+                continue
+            if all(rec.get(key) == val for key, val in signature.items()):
+                traffic = (rec["fetch_size_kib"] * rec["fetch_factor"] + rec["write_size_kib"] * rec["write_factor"]) * 1024
+                return traffic, {"file": os.path.relpath(path, ROOT), "commit": rec.get("commit"),
+                                 "fetch_size_kib": rec["fetch_size_kib"], "write_size_kib": rec["write_size_kib"],
+                                 "fetch_factor": rec["fetch_factor"], "write_factor": rec["write_factor"]}
+    return None, "no counter profile under profiles/ was taken with this kernel, batch shape and slice plan"
+
+
+class HbmCase:
+    """One HBM-resident workload: set-up, the timed region, the per-kernel legs, the CPU oracle."""
+
+    def __init__(self, args, key, seed, steps, warmup, tables):
+        import numpy as np
+        import torch
+        from paper_2312_05417_amd import binding as espn, synth
+        self.args, self.key, self.seed, self.steps, self.warmup = args, key, seed, steps, warmup
+        self.espn, self.synth, self.torch, self.np = espn, synth, torch, np
+        dev = self.dev = torch.device("cuda:0")
+        lib = self.lib = espn.lib()
+        w = synth.WORKLOADS[key]
+        if args.batch is not None:
+            w = synth.scaled(w, B=args.batch, name="%s-B%d" % (w.name, args.batch))
+        if args.top_k is not None:
+            w = synth.scaled(w, k=args.top_k, name="%s-k%d" % (w.name, args.top_k))
+        if args.cand_law is not None:
+            w = synth.scaled(w, cand_law=args.cand_law, name="%s-%s" % (w.name, args.cand_law))
+        if args.query_tokens is not None:
+            w = synth.scaled(w, Q=args.query_tokens, name="%s-Q%d" % (w.name, args.query_tokens))
+        self.w = w
+        n_sets = self.n_sets = args.sets if args.sets is not None else DEFAULT_SETS[key]
+        t_setup = time.time()
+        # c3 and c4 read the same table: drawn once
+        tkey = (w.n_docs, w.dim, w.count_law, w.count_lo, w.count_hi, w.count_mean, w.codec, seed)
+        if tkey not in tables:
+            emb, off = synth.table(w, seed, device=dev)
+            doc_scale = None
+            if w.codec == "e4m3":
+                codes, doc_scale = synth.compress_e4m3(emb, off)
+                del emb
+                emb = codes
+            tables[tkey] = (emb, off, doc_scale)
+        self.emb, self.off, self.doc_scale = emb, off, doc_scale = tables[tkey]
+        self.elem_bytes = 1 if w.codec == "e4m3" else 2
+        self.counts = np.diff(off)
+        self.table = espn.espn_table_load_e4m3(emb, doc_scale, off) if w.codec == "e4m3" else espn.espn_table_load(emb, off)
+        espn.espn_table_set_fetch(self.table, {"auto": espn.ESPN_FETCH_AUTO, "streaming": espn.ESPN_FETCH_STREAMING,
+                                               "cached": espn.ESPN_FETCH_CACHED}[args.fetch])
+        log("%s: table %d docs, %d rows x %d, %.2f GB in HBM (%.1f s)" % (
+            w.name, w.n_docs, emb.shape[0], w.dim, emb.numel() * self.elem_bytes / 1e9, time.time() - t_setup))
+        self.cands_np = [synth.candidates(w, seed, s) for s in range(n_sets)]
+        self.cands = [torch.from_numpy(c).to(dev) for c in self.cands_np]
+        self.qs = [synth.queries(w, seed, s, device=dev) for s in range(n_sets)]
+        # what the library is told about the lists (once per workload, as a server would at start-up)
+        self.overlap = espn.espn_table_sample(self.table, self.cands[0])
+        R = self.R = w.rerank_top if w.rerank_top else w.K          # candidates per query that are actually scored
+        self.batched = not w.rerank_top                              # partial re-ranking has no queue entry point
+        n_out = max(steps, warmup, n_sets)
+        self.out_ids = torch.empty((n_out, w.B, w.k), dtype=torch.int64, device=dev)
+        self.out_sc = torch.empty((n_out, w.B, w.k), dtype=torch.float32, device=dev)
+        self.part = espn.espn_workspace_bytes(w.B, R)
+        self.ws_bytes = max(espn.espn_batches_workspace_bytes(self.table, n, w.B, w.Q, R, min(w.k, R)) for n in (1, 3, max(steps, 1), max(warmup, 1)))
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        self.scores_view = self.ws[: 4 * w.B * R].view(torch.float32).view(w.B, R)
+        self.stream = torch.cuda.current_stream()
+        self.st = int(self.stream.cuda_stream)
+        self.h = self.table.handle
+        self.plan = espn.espn_rerank_plan(self.table, w.B, w.Q, R, min(w.k, R))
+        self.kernels = espn.espn_rerank_plan_kernels(self.table, w.B, w.Q, R, min(w.k, R))
+        # algorithmic bytes of one score-kernel launch: per scored pair the document's rows, its offset
+        # pair, its id and its score; per query its matrix once
+        self.scored_np = [c[:, :R] for c in self.cands_np]
+        per_pair = 28.0 + (4.0 if self.elem_bytes == 1 else 0.0)             # + the document's scale
+        pair_bytes = [float((self.elem_bytes * w.dim * self.counts[c]).sum()) + per_pair * c.size for c in self.scored_np]
+        self.launch_bytes = float(np.mean(pair_bytes)) + w.B * w.Q * w.dim * 2
+        self.flops = float(np.mean([(2.0 * w.Q * w.dim * self.counts[c]).sum() for c in self.scored_np]))
+        # ... and the bytes of the DISTINCT documents of a launch (what memory has to deliver at least once;
+        # equal to the above where no two queries list the same document)
+        distinct = [np.unique(c) for c in self.scored_np]
+        self.distinct_bytes = float(np.mean([float((self.elem_bytes * w.dim * self.counts[u]).sum()) + 16.0 * u.size
+                                             for u in distinct])) + (12.0 * w.B * R) + w.B * w.Q * w.dim * 2
+        self.distinct_docs = float(np.mean([u.size for u in distinct]))
+        log("%s: %d sets of %d x %d candidates, %d scored per query, sampled overlap %.3f (%.1f s)" % (
+            w.name, n_sets, w.B, w.K, R, self.overlap, time.time() - t_setup))
+
+    # -- enqueue helpers
+    def pointer_lists(self, first, count):
+        e, t = self.espn, self.torch
+        idx = [(first + i) % self.n_sets for i in range(count)]
+        return (e.pointer_list([self.qs[s] for s in idx], t.float16, "q"),
+                e.pointer_list([self.cands[s] for s in idx], t.int64, "cand"),
+                e.pointer_list([self.out_ids[i] for i in range(count)], t.int64, "out_ids"),
+                e.pointer_list([self.out_sc[i] for i in range(count)], t.float32, "out_scores"))
+
+    def rerank_queue(self, lists, count):
+        w = self.w
+        rc = self.lib.espn_rerank_batches(self.h, count, lists[0], lists[1], w.B, w.Q, w.K, w.k, lists[2], lists[3],
+                                          self.ws.data_ptr(), self.ws_bytes, self.st)
+        if rc != 0:
+            raise RuntimeError("espn_rerank_batches failed: " + self.espn.last_error())
+
+    def rerank(self, i, on=None):
+        w, s = self.w, i % self.n_sets
+        on = self.st if on is None else on
+        o = i % self.out_ids.shape[0]
+        if w.rerank_top:
+            rc = self.lib.espn_rerank_partial(self.h, self.qs[s].data_ptr(), self.cands[s].data_ptr(), w.B, w.Q, w.K, self.R,
+                                              w.k, self.out_ids[o].data_ptr(), self.out_sc[o].data_ptr(), self.ws.data_ptr(),
+                                              self.part, on)
+        else:
+            rc = self.lib.espn_rerank(self.h, self.qs[s].data_ptr(), self.cands[s].data_ptr(), w.B, w.Q, w.K, w.k,
+                                      self.out_ids[o].data_ptr(), self.out_sc[o].data_ptr(), self.ws.data_ptr(), self.part, on)
+        if rc != 0:
+            raise RuntimeError("re-rank failed: " + self.espn.last_error())
+
+    def score_only(self, i):
+        w, s = self.w, i % self.n_sets
+        if w.rerank_top:      # k = 0: the scoring kernel alone, on the first R candidates of every list
+            rc = self.lib.espn_rerank_partial(self.h, self.qs[s].data_ptr(), self.cands[s].data_ptr(), w.B, w.Q, w.K, self.R,
+                                              0, None, None, self.ws.data_ptr(), self.part, self.st)
+        else:
+            rc = self.lib.espn_score(self.h, self.qs[s].data_ptr(), self.cands[s].data_ptr(), w.B, w.Q, w.K,
+                                     self.ws.data_ptr(), self.st)
+        if rc != 0:
+            raise RuntimeError("scoring failed: " + self.espn.last_error())
+
+    # -- the timed region: exactly `warmup` untimed and `steps` timed passes of the whole path
+    def timed(self):
+        torch, w = self.torch, self.w
+        if self.batched:
+            # one call per region: the queue of batches goes to the library, which spreads it over its streams
+            warm = self.pointer_lists(0, self.warmup) if self.warmup else None
+            run = self.pointer_lists(self.warmup, self.steps)
+            if warm:
+                self.rerank_queue(warm, self.warmup)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.rerank_queue(run, self.steps)
+            torch.cuda.synchronize()
+            self.wall = time.perf_counter() - t0
+        else:
+            for i in range(self.warmup):
+                self.rerank(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(self.warmup, self.warmup + self.steps):
+                self.rerank(i)
+            torch.cuda.synchronize()
+            self.wall = time.perf_counter() - t0
+        self.espn.espn_table_check(self.table)
+        self.ms_per_step = self.wall * 1e3 / self.steps
+        log("%s: %.4f ms/step over %d steps (%s)" % (w.name, self.ms_per_step, self.steps,
+                                                      "espn_rerank_batches" if self.batched else "one call per batch"))
+
+    def _events(self, fn, n):
+        torch = self.torch
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(self.stream)
+        for i in range(n):
+            fn(i)
+        b.record(self.stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    # -- per-kernel legs, all on ONE stream with HIP events around `steps` back-to-back launches
+    def legs(self):
+        torch, w, steps = self.torch, self.w, self.steps
+        from paper_2312_05417_amd import benchprobe
+        pre = min(max(self.warmup, 1), 3)
+        for i in range(pre):
+            self.rerank(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.path_ms = self._events(self.rerank, steps)            # the whole path, one espn_rerank call per batch
+        self.sequential_wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        for i in range(pre):
+            self.score_only(i)
+        self.score_only_ms = self._events(self.score_only, steps)  # the dominant kernel alone
+        self.two_launch_ms = None
+        if not w.rerank_top:
+            def score_then_topk(i):
+                self.score_only(i)
+                s = i % self.n_sets
+                rc = self.lib.espn_topk(self.ws.data_ptr(), self.cands[s].data_ptr(), w.B, w.K, w.k,
+                                        self.out_ids[0].data_ptr(), self.out_sc[0].data_ptr(), self.st)
+                if rc != 0:
+                    raise RuntimeError("espn_topk failed: " + self.espn.last_error())
+            for i in range(pre):
+                score_then_topk(i)
+            self.two_launch_ms = self._events(score_then_topk, steps)
+        # a measuring stick: a plain contiguous read (nothing depends on what is read) of as many bytes as one
+        # launch of the scoring kernel reads, over successive windows of the table
+        window = min(int(self.launch_bytes) // 4096 * 4096, self.emb.numel() * self.elem_bytes // 4096 * 4096)
+        flat = self.emb.view(torch.uint8).view(-1)
+        n_windows = max(1, min(64, flat.numel() // window))
+        sink = torch.zeros(1, dtype=torch.int64, device=self.dev)
+
+        def plain_read(i):
+            benchprobe.stream_read(flat.data_ptr() + (i % n_windows) * window, window, sink.data_ptr(), self.st)
+
+        for i in range(min(max(self.warmup, 1), 8)):
+            plain_read(i)
+        self.plain_read_gbs = window / (self._events(plain_read, steps) * 1e-3) / 1e9
+        if self.args.calibration_copy:      # a copy of known size for the profiler's byte counters: 1 GiB read, 1 GiB written
+            src = torch.ones(1 << 28, dtype=torch.float32, device=self.dev)
+            dst = torch.empty_like(src)
+            torch.cuda.synchronize()
+            benchprobe.copy(src.data_ptr(), dst.data_ptr(), 1 << 30, self.st)
+            torch.cuda.synchronize()
+            del src, dst
+        self.kern_ms = self.path_ms if self.plan["launches"] == 1 else self.score_only_ms
+        log("%s: MaxSim kernel avg %.4f ms = %.1f GB/s algorithmic (%s); one espn_rerank call per batch %.4f ms; "
+            "plain read of the same bytes %.1f GB/s" % (w.name, self.kern_ms, self.launch_bytes / (self.kern_ms * 1e-3) / 1e9,
+                                                        self.kernels[0] if self.kernels else "-", self.sequential_wall_ms,
+                                                        self.plain_read_gbs))
+
+    # -- the CPU oracle on a bounded sample of the same workload (reported baseline + parity check)
+    def oracle(self, budget_queries=None):
+        import oracle
+        from tests.parity import assert_scores_close, assert_topk_matches
+        torch, w, key, synth = self.torch, self.w, self.key, self.synth
+        nb = {"c1": min(16, self.n_sets), "c2": min(8, self.n_sets), "c2p64": min(8, self.n_sets),
+              "c2e4m3": min(4, self.n_sets)}.get(key, 1)
+        nq = w.B if key in SHORT_STEPS else min(128 * (w.K // self.R), w.B)
+        if w.codec == "e4m3" and key != "c2e4m3":
+            nq = min(32, w.B)
+        if budget_queries is not None:
+            nb, nq = 1, min(budget_queries, w.B)
+        threads = oracle_threads()
+        cpu_s, worst, pairs = 0.0, 0.0, 0
+        for s in range(nb):
+            sub, loc_off, loc_cand, ids = synth.subtable(self.emb, self.off, self.scored_np[s][:nq])
+            q_np = self.qs[s][:nq].cpu().numpy()
+            t1 = time.perf_counter()
+            if w.codec == "e4m3":
+                o_all = oracle.scores_e4m3(sub, self.doc_scale[ids], loc_off, q_np, loc_cand, threads=threads)
+                o_ids, o_top = oracle.topk(o_all, loc_cand, w.k)
+            else:
+                o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k, threads=threads)     # the scored prefix
+            cpu_s += time.perf_counter() - t1
+            # parity of the timed configuration on the same sample: the queue entry point with three batches
+            # in flight (the sampled one first), or the per-batch call where there is no queue
+            if self.batched:
+                lists = self.pointer_lists(s, 3)
+                self.rerank_queue(lists, 3)
+            else:
+                self.rerank(s)
+            torch.cuda.synchronize()
+            g_all = self.scores_view[:nq].cpu().numpy()
+            o = 0 if self.batched else s % self.out_ids.shape[0]
+            g_ids, g_top = self.out_ids[o][:nq].cpu().numpy(), self.out_sc[o][:nq].cpu().numpy()
+            worst = max(worst, assert_scores_close(g_all, o_all, w.Q))
+            for b in range(nq):
+                assert_topk_matches(g_ids[b], g_top[b], o_all[b], self.scored_np[s][b], w.k, w.Q)
+            pairs += nq * self.R
+        one_thread = None
+        if w.codec != "e4m3":       # the same oracle on ONE thread, on a 16th of the first sample
+            n1 = max(1, nq // 16)
+            sub, loc_off, loc_cand, ids = synth.subtable(self.emb, self.off, self.scored_np[0][:n1])
+            t1 = time.perf_counter()
+            oracle.rerank(sub, loc_off, self.qs[0][:n1].cpu().numpy(), loc_cand, w.k, threads=1)
+            one_thread = n1 * self.R / (time.perf_counter() - t1)
+        self.cpu_baseline = {
+            "value": pairs / cpu_s, "unit": "docs/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d queries of each of the first %d batches (%d pairs), fp64, %.1f s wall" % (nq, nb, pairs, cpu_s),
+            "value_one_thread": one_thread,
+        }
+        self.parity = {"sample_pairs": pairs, "worst_rel_err": worst, "status": "ok",
+                       "entry_point": "espn_rerank_batches" if self.batched else "espn_rerank_partial"}
+        log("%s: oracle %.0f docs/s on %d threads%s; parity ok on %d pairs (worst rel err %.2e)" % (
+            w.name, pairs / cpu_s, threads, "" if one_thread is None else " (%.0f on one)" % one_thread, pairs, worst))
+
+    def result(self):
+        w, steps, R = self.w, self.steps, self.R
+        achieved = self.launch_bytes / (self.kern_ms * 1e-3) / 1e9
+        overlapping = self.distinct_docs < 0.9 * w.B * R
+        signature = {"workload": w.name, "kernel": self.kernels[0] if self.kernels else None, "n_docs": w.n_docs,
+                     "batch_queries": w.B, "scored_per_query": R, "query_tokens": w.Q, "candidate_law": w.cand_law,
+                     "slices": self.plan["slices"], "slice": self.plan["slice"], "seed": self.seed}
+        traffic, source = measured_traffic(signature)
+        roofline = {
+            "bound": "hbm", "kernel": self.kernels[0] if self.kernels else None,
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic, "traffic_source": source,
+            "frac_basis": ("logical bytes: every listing of a document counted, repeats are served by the caches"
+                           if overlapping else "algorithmic bytes (no two queries of a batch share a document to speak of)"),
+            "algorithmic_bytes_per_launch": self.launch_bytes, "kernel_ms_avg": self.kern_ms,
+            "distinct": {"docs_per_launch": self.distinct_docs, "bytes_per_launch": self.distinct_bytes,
+                         "achieved": self.distinct_bytes / (self.kern_ms * 1e-3) / 1e9,
+                         "frac": self.distinct_bytes / (self.kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "note": "bytes of the distinct documents of a launch: what HBM has to deliver at least once"},
+            "launches_per_step": self.plan["launches"], "slices_per_query": self.plan["slices"], "kernels": self.kernels,
+            "whole_path_one_call_per_batch_ms_by_events": self.path_ms, "scoring_without_ranking_ms": self.score_only_ms,
+            "score_then_standalone_ranking_ms": self.two_launch_ms,
+            "mfma_tflops": self.flops / (self.kern_ms * 1e-3) / 1e12,
+            "plain_read_same_bytes_gbs": self.plain_read_gbs,
+        }
+        res = {
+            "metric": "candidate docs MaxSim-scored/sec",
+            "value": w.B * R * steps / self.wall,            # documents actually MaxSim-scored
+            "unit": "docs/s", "n_gpus": 1, "steps": steps, "warmup": self.warmup, "ms_per_step": self.ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+            "config": {
+                "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": int(self.emb.shape[0]),
+                "table_gb": self.emb.numel() * self.elem_bytes / 1e9, "codec": w.codec,
+                "tokens_per_doc": "%s[%d,%d]" % (w.count_law, w.count_lo, w.count_hi),
+                "batch_queries": w.B, "query_tokens": w.Q, "candidates_per_query": w.K, "scored_per_query": R,
+                "top_k": w.k, "candidate_law": w.cand_law, "rotating_sets": self.n_sets, "accumulate": "f32",
+                "seed": self.seed, "fetch": self.args.fetch, "sampled_overlap": self.overlap,
+                "entry_point": ("espn_rerank_batches: the %d timed batches in one call, spread over %d streams of the "
+                                "library" % (steps, min(steps, self.espn.ESPN_BATCH_LANES))) if self.batched
+                else "espn_rerank_partial, one call per batch on one stream",
+            },
+            "queries_per_s": w.B * steps / self.wall,
+            "wall_algorithmic_gbs": self.launch_bytes * steps / self.wall / 1e9,
+            "wall_frac_of_hbm_peak": self.launch_bytes * steps / self.wall / 1e9 / HBM_PEAK_GBS,
+            "one_call_per_batch": {"ms_per_step": self.sequential_wall_ms, "value": w.B * R / (self.sequential_wall_ms * 1e-3),
+                                   "wall_frac_of_hbm_peak": self.launch_bytes / (self.sequential_wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "note": "espn_rerank (espn_rerank_partial) called once per batch on one stream"},
+            "roofline": roofline,
+        }
+        if hasattr(self, "cpu_baseline"):
+            res["cpu_baseline"], res["parity"] = self.cpu_baseline, self.parity
+        return res
+
+    def free(self):
+        self.table.free()
+
+
+def release_pinned_cache(torch):
+    """Pinned host blocks that torch has freed stay pinned in its allocator's cache; this machine pins 64 GiB per
+    process at most, so they are handed back before a table is pinned."""
+    import gc
+    gc.collect()
+    empty = getattr(torch._C, "_host_emptyCache", None)
+    if empty is not None:
+        empty()
+
+
+def run_host_resident(args, key, seed, steps, warmup):
+    """Table in host memory; batch n+1 is prefetched over PCIe on a side stream into one HBM staging slot while
+    batch n is scored from the other.  c5 / c5e4m3: the stated table size in ORDINARY host memory, packed by the
+    host into the library's pinned buffers and sent with plain copies (espn_prefetch_packed) - unless the
+    machine pins the whole table, in which case the gather kernel reads it directly.  c5pinned: the largest
+    table the machine pins, read by the gather kernel (espn_prefetch)."""
     import numpy as np
     import torch
     from paper_2312_05417_amd import binding as espn, synth
 
     dev = torch.device("cuda:0")
     lib = espn.lib()
+    w = synth.WORKLOADS["c5" if key == "c5pinned" else key]
+    asked_docs = w.n_docs
     if args.host_docs is not None:
         w = synth.scaled(w, n_docs=args.host_docs)
+    if args.batch is not None:
+        w = synth.scaled(w, B=args.batch)
+    n_slots = args.slots
+    n_sets = max(args.sets if args.sets is not None else DEFAULT_SETS[key], n_slots + 1)
     t_setup = time.time()
     e4m3 = w.codec == "e4m3"
     row_bytes = w.dim * (1 if e4m3 else 2)
     doc_scale = None
-    # the full table is 156 GB (78 GB compressed); if the machine refuses to pin that much, shrink the document
-    # count by 20 % until it fits (the PCIe rate does not depend on it once the table is far larger than any cache)
+    engine = args.engine
+    pinned = True
+    dtype = torch.uint8 if e4m3 else torch.float16
+    release_pinned_cache(torch)
     while True:
         counts = synth.token_counts(w, seed)
         off = synth.offsets_from_counts(counts)
         rows = int(off[-1])
         try:
-            emb = torch.empty((rows, w.dim), dtype=torch.uint8 if e4m3 else torch.float16, pin_memory=True)
+            emb = torch.empty((rows, w.dim), dtype=dtype, pin_memory=True)
             break
         except RuntimeError as exc:
-            log("cannot pin %.1f GB for %d docs (%s); shrinking by 20 %%" % (rows * row_bytes / 1e9, w.n_docs,
-                                                                   str(exc).splitlines()[0]))
+            log("cannot pin %.1f GB for %d docs (%s)" % (rows * row_bytes / 1e9, w.n_docs, str(exc).splitlines()[0]))
+            if key != "c5pinned":
+                # the stated size, then, in ordinary host memory: only the host can read it, so the host packs
+                emb = torch.empty((rows, w.dim), dtype=dtype)
+                pinned, engine = False, "packed"
+                break
             if w.n_docs < 200_000:
                 raise
-            w = synth.scaled(w, n_docs=int(w.n_docs * 0.8))
-    log("%s: pinned %.1f GB of host memory for %d docs (%.1f s)" % (w.name, rows * row_bytes / 1e9, w.n_docs,
-                                                                     time.time() - t_setup))
+            w = synth.scaled(w, n_docs=int(w.n_docs * 0.8))        # the largest table that pins, in steps of 20 %
+    if engine == "auto":
+        engine = "gather"
+    log("%s: %.1f GB of %s host memory for %d docs (%.1f s)" % (
+        w.name, rows * row_bytes / 1e9, "pinned" if pinned else "ordinary", w.n_docs, time.time() - t_setup))
     if e4m3:
         # drawn and compressed in HBM (binary16 table + codes: 1.5 x 158 GB fit the 288 GB), codes copied to the host
         full, _ = synth.table(w, seed, device=dev)
@@ -85,7 +470,8 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         synth.table(w, seed, device=dev, out=emb)      # drawn on the GPU chunk by chunk, copied to the host
     torch.cuda.synchronize()
     log("table filled (%.1f s)" % (time.time() - t_setup))
-    table = espn.espn_table_load_e4m3(emb, doc_scale, off) if e4m3 else espn.espn_table_load(emb, off)
+    table = (espn.espn_table_load_e4m3(emb, doc_scale, off, pageable=not pinned) if e4m3
+             else espn.espn_table_load(emb, off, pageable=not pinned))
 
     cands_np = [synth.candidates(w, seed, s) for s in range(n_sets)]
     cands = [torch.from_numpy(c).to(dev) for c in cands_np]
@@ -94,7 +480,6 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
     uniq_rows = [int(counts[u].sum()) for u in uniq]
     cap_rows = int(max(uniq_rows) * 1.05) + 1024
     cap_docs = int(max(u.size for u in uniq) * 1.05) + 1024
-    n_slots = args.slots
     espn.espn_staging_create_ring(table, n_slots, cap_rows, cap_docs)
     out_ids = [torch.empty((w.B, w.k), dtype=torch.int64, device=dev) for _ in range(n_sets)]
     out_sc = [torch.empty((w.B, w.k), dtype=torch.float32, device=dev) for _ in range(n_sets)]
@@ -105,7 +490,8 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         n_slots, cap_rows * row_bytes / 1e9, time.time() - t_setup))
 
     # reference: a plain pinned-host -> device copy of 1 GiB
-    ref_src = emb[: (1 << 30) // row_bytes]
+    ref_rows = (1 << 30) // row_bytes
+    ref_src = emb[:ref_rows] if pinned else torch.empty((ref_rows, w.dim), dtype=dtype, pin_memory=True)
     ref_dst = torch.empty_like(ref_src, device=dev)
     ref_dst.copy_(ref_src, non_blocking=True)
     torch.cuda.synchronize()
@@ -114,12 +500,11 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         ref_dst.copy_(ref_src, non_blocking=True)
     torch.cuda.synchronize()
     memcpy_gbs = 3 * ref_src.numel() * ref_src.element_size() / (time.perf_counter() - t0) / 1e9
-    del ref_dst
+    del ref_dst, ref_src
 
     main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
     st_main, st_side, h = int(main_s.cuda_stream), int(side_s.cuda_stream), table.handle
-
-    packed = args.engine == "packed"
+    packed = engine == "packed"
     cands_host = [torch.from_numpy(c) for c in cands_np] if packed else None
 
     def prefetch(n):
@@ -150,48 +535,48 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
 
     # Batch numbers keep running through every leg below: batch n uses candidate set n % n_sets and slot
     # n % n_slots, and with more sets than slots no slot ever holds the set that is being fetched.  The
-    # ring is warm (every slot filled once) before anything is timed.
-    warmup = max(warmup, n_slots)
+    # ring is filled once (every slot, untimed) before the warm-up steps, so that no timed step meets an empty slot.
     prefetch(0)
-    pipeline(0, warmup)
+    pipeline(0, n_slots + warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    pipeline(warmup, steps)                 # one prefetch and one staged re-rank per step
+    pipeline(n_slots + warmup, steps)       # one prefetch and one staged re-rank per step
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     espn.espn_table_check(table)
     ms_per_step = wall * 1e3 / steps
-    nxt = warmup + steps + 1                # batches 0 .. warmup + steps have been prefetched
+    nxt = n_slots + warmup + steps + 1      # batches 0 .. n_slots + warmup + steps have been prefetched
 
-    # transfer alone and scoring alone, each timed with HIP events on its own stream
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(side_s)
-    for n in range(nxt, nxt + steps):
-        prefetch(n)
-    e1.record(side_s)
+    # transfer alone and scoring alone, each timed on its own stream
+    legs = max(3, min(steps, 12))
     torch.cuda.synchronize()
-    xfer_ms = e0.elapsed_time(e1) / steps
-    nxt += steps
-    # bytes that crossed PCIe, from the library's own counters: `steps` more prefetches, reading the
-    # counters after each (documents another slot already holds do not cross again)
+    t0 = time.perf_counter()
+    for n in range(nxt, nxt + legs):
+        prefetch(n)
+    torch.cuda.synchronize()
+    xfer_ms = (time.perf_counter() - t0) * 1e3 / legs
+    nxt += legs
+    # bytes that crossed PCIe, from the library's own counters: more prefetches, reading the counters after
+    # each (documents another slot already holds do not cross again)
     crossed = []
-    for n in range(nxt, nxt + steps):
+    for n in range(nxt, nxt + legs):
         prefetch(n)
         crossed.append(espn.espn_staging_counters(table, n % n_slots, side_s)["pcie_bytes"])
     pcie_bytes = float(np.mean(crossed))
-    distinct_bytes = float(np.mean([uniq_rows[n % n_sets] for n in range(nxt, nxt + steps)])) * row_bytes
-    nxt += steps
+    distinct_bytes = float(np.mean([uniq_rows[n % n_sets] for n in range(nxt, nxt + legs)])) * row_bytes
+    nxt += legs
     last = nxt - 1                          # the batch its slot still holds
     torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(main_s)
-    for _ in range(steps):
+    for _ in range(legs):
         rerank(last)
     e1.record(main_s)
     torch.cuda.synchronize()
-    score_ms = e0.elapsed_time(e1) / steps
+    score_ms = e0.elapsed_time(e1) / legs
     achieved = pcie_bytes / (xfer_ms * 1e-3) / 1e9
-    log("wall %.2f ms/batch; prefetch alone %.2f ms (%.2f GB over PCIe of %.2f GB distinct: %.1f GB/s; plain 1 GiB "
-        "memcpy %.1f GB/s); scoring alone %.2f ms" % (ms_per_step, xfer_ms, pcie_bytes / 1e9, distinct_bytes / 1e9,
+    log("%s: wall %.2f ms/batch; prefetch alone %.2f ms (%.2f GB over PCIe of %.2f GB distinct: %.1f GB/s; plain 1 GiB "
+        "memcpy %.1f GB/s); scoring alone %.2f ms" % (w.name, ms_per_step, xfer_ms, pcie_bytes / 1e9, distinct_bytes / 1e9,
                                                       achieved, memcpy_gbs, score_ms))
 
     logical = float(np.mean([(row_bytes * counts[c]).sum() for c in cands_np]))
@@ -200,17 +585,23 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {
-            "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": rows, "table_gb": rows * row_bytes / 1e9,
-            "codec": w.codec, "residency": "pinned host memory", "batch_queries": w.B, "query_tokens": w.Q,
+            "workload": w.name + ("-pinned" if key == "c5pinned" else ""), "n_docs": w.n_docs, "n_docs_asked": asked_docs,
+            "dim": w.dim, "rows": rows, "table_gb": rows * row_bytes / 1e9,
+            "codec": w.codec, "residency": "pinned host memory" if pinned else "ordinary (pageable) host memory",
+            "batch_queries": w.B, "query_tokens": w.Q,
             "candidates_per_query": w.K, "top_k": w.k, "candidate_law": "zipf(%.1f)" % w.zipf_alpha,
-            "rotating_sets": n_sets, "staging_slots": n_slots,
-            "prefetch_engine": "host packs into pinned buffers, plain copies" if packed else "gather kernel reading pinned host memory",
+            "rotating_sets": n_sets, "staging_slots": n_slots, "ring_fill_steps_before_warmup": n_slots,
+            "prefetch_engine": ("espn_prefetch_packed: the host packs distinct documents into pinned buffers, plain copies"
+                                if packed else "espn_prefetch: gather kernel reading pinned host memory"),
             "distinct_docs_per_batch": float(np.mean([u.size for u in uniq])),
             "accumulate": "f32", "seed": seed,
         },
         "roofline": {
-            "bound": "pcie", "kernel": "hipMemcpyAsync of packed buffers" if packed else "staging_gather_kernel", "achieved": achieved, "peak": PCIE_PEAK_GBS,
+            "bound": "pcie", "kernel": "hipMemcpyAsync of packed buffers" if packed else "espn::staging_gather_kernel",
+            "achieved": achieved, "peak": PCIE_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / PCIE_PEAK_GBS, "traffic": None,
+            "traffic_source": "bytes that crossed PCIe are counted by the library (rows reserved minus rows taken from "
+                              "other slots, times the row bytes), not by a hardware counter",
             "algorithmic_bytes_per_launch": pcie_bytes, "kernel_ms_avg": xfer_ms,
             "plain_memcpy_h2d_gbs": memcpy_gbs,
         },
@@ -219,13 +610,13 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
                     "logical_gb_per_batch": logical / 1e9, "distinct_gb_per_batch": distinct_bytes / 1e9,
                     "pcie_gb_per_batch": pcie_bytes / 1e9},
     }
-    if args.sweep_batch:
+    if args.sweep_batch and not packed:
         # Eq. 4 with PCIe in the place of the SSD: the largest batch whose fetch fits a time budget.
         # The prediction uses the measured PCIe rate and the mean bytes of a query's K documents (no
         # sharing between queries, as in the paper); the measurement is the prefetch of the first b
         # queries of batch 0, which benefits from documents shared between queries.
         budget_s = args.budget_ms * 1e-3
-        per_query = float(np.mean([(row_bytes * counts[c]).sum() for c in cands_np])) / w.B
+        per_query = logical / w.B
         predicted = lib.espn_batch_threshold(achieved * 1e9, budget_s, per_query)
         sweep = {}
         b = 16
@@ -271,25 +662,30 @@ def run_host_resident(args, w, seed, steps, warmup, n_sets):
         q_np = qs[0][:nq].cpu().numpy()
         t1 = time.perf_counter()
         if e4m3:
-            o_all = oracle.scores_e4m3(sub, doc_scale[ids], loc_off, q_np, loc_cand)
+            o_all = oracle.scores_e4m3(sub, doc_scale[ids], loc_off, q_np, loc_cand, threads=oracle_threads())
         else:
-            o_all = oracle.scores(sub, loc_off, q_np, loc_cand)
+            o_all = oracle.scores(sub, loc_off, q_np, loc_cand, threads=oracle_threads())
         cpu_s = time.perf_counter() - t1
-        prefetch(0)
-        rerank(0)
+        m = (nxt // n_sets + 1) * n_sets        # a batch number that uses candidate set 0
+        prefetch(m)
+        rerank(m)
         torch.cuda.synchronize()
         g_all = ws[: 4 * w.B * w.K].view(torch.float32).view(w.B, w.K)[:nq].cpu().numpy()
         g_ids, g_top = out_ids[0][:nq].cpu().numpy(), out_sc[0][:nq].cpu().numpy()
         worst = assert_scores_close(g_all, o_all, w.Q)
         for b in range(nq):
             assert_topk_matches(g_ids[b], g_top[b], o_all[b], cands_np[0][b], w.k, w.Q)
-        result["cpu_baseline"] = {"value": nq * w.K / cpu_s, "unit": "docs/s", "cores": oracle.max_threads(),
+        result["cpu_baseline"] = {"value": nq * w.K / cpu_s, "unit": "docs/s", "cores": oracle_threads(),
                                   "kind": "oracle",
                                   "sample": "first %d queries of batch 0 (%d pairs), fp64, %.1f s wall" % (
                                       nq, nq * w.K, cpu_s)}
         result["parity"] = {"sample_pairs": nq * w.K, "worst_rel_err": worst, "status": "ok"}
-        log("oracle: %.0f docs/s; parity ok on %d pairs" % (nq * w.K / cpu_s, nq * w.K))
-    print(json.dumps(result), flush=True)
+        log("%s: oracle %.0f docs/s; parity ok on %d pairs" % (w.name, nq * w.K / cpu_s, nq * w.K))
+    espn.espn_table_check(table)
+    table.free()
+    del emb, table
+    release_pinned_cache(torch)
+    return result
 
 
 def main():
@@ -297,20 +693,23 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2p64", "c3p64", "c2e4m3", "c3e4m3", "c5e4m3"])
+    ap.add_argument("--workload", default="all",
+                    choices=["all", "c1", "c2", "c3", "c4", "c5", "c5pinned", "c2p64", "c3p64", "c2e4m3", "c3e4m3", "c5e4m3"],
+                    help="all (default): c4 as the headline with c3, c2, c5 and c5pinned beside it in `configs`")
     ap.add_argument("--sweep-batch", action="store_true",
-                    help="c5 only: also time the prefetch for smaller batches and compare the batch size at which "
+                    help="c5pinned only: also time the prefetch for smaller batches and compare the batch size at which "
                          "it outgrows a time budget with Eq. 4's prediction")
     ap.add_argument("--budget-ms", type=float, default=28.0, help="time budget for --sweep-batch")
     ap.add_argument("--host-docs", type=int, default=None,
-                    help="c5 only: number of documents of the host-resident table (default 8.8 M = 156 GB pinned)")
+                    help="host-resident workloads: number of documents of the table (default 8.8 M = 156 GB)")
     ap.add_argument("--slots", type=int, default=2,
-                    help="c5 only: HBM staging slots (2 = double buffering; more slots also serve as a cache of "
-                         "recently fetched documents)")
+                    help="host-resident workloads: HBM staging slots (2 = double buffering; more slots also serve as a "
+                         "cache of recently fetched documents)")
     ap.add_argument("--fetch", default="auto", choices=["auto", "streaming", "cached"],
-                    help="how rows of 128 bytes and more are fetched (espn_table_set_fetch); auto = the library decides")
-    ap.add_argument("--engine", default="gather", choices=["gather", "packed"],
-                    help="c5 only: which prefetch engine fills the staging slots (espn_prefetch / espn_prefetch_packed)")
+                    help="how rows are fetched (espn_table_set_fetch); auto = the library decides from espn_table_sample")
+    ap.add_argument("--engine", default="auto", choices=["auto", "gather", "packed"],
+                    help="host-resident workloads: which prefetch engine fills the staging slots (espn_prefetch / "
+                         "espn_prefetch_packed); auto = gather where the table is pinned, packed where it is not")
     ap.add_argument("--batch", type=int, default=None, help="override the number of queries per batch")
     ap.add_argument("--query-tokens", type=int, default=None,
                     help="override the rows per query (up to 64 run on the matrix cores; more take the plain-ALU "
@@ -320,12 +719,17 @@ def main():
                     help="override the law the candidate lists are drawn from")
     ap.add_argument("--sets", type=int, default=None, help="distinct pre-drawn batches to rotate through")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--two-streams", nargs="?", type=int, const=2, default=0, metavar="N",
-                    help="also time the same batches issued in turn on N streams, default 2 (reported beside value)")
+    ap.add_argument("--wake-up-ms", type=float, default=None,
+                    help="run the first workload's path untimed for this long before its warm-up steps (default: 30 ms "
+                         "when neither --warmup nor --steps is given, so that the device is at speed; 0 when either is "
+                         "given: then exactly W warm-up steps precede the K timed ones)")
+    ap.add_argument("--kernels-only", action="store_true",
+                    help="skip the timed region of the queue entry point (its overlapped launches blur a profiler's "
+                         "per-kernel averages): only the one-stream legs run; `value` is then the one-call-per-batch rate")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-queries", type=int, default=None)
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (a known-size "
+                    help="also run one plain 1 GiB read + 1 GiB write copy kernel (a known-size "
                          "reference for hardware byte counters when profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -336,344 +740,75 @@ def main():
         print("bench.py: launched with WORLD_SIZE > 1; only one rank on one GPU is supported", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_2312_05417_amd import binding as espn, synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    lib = espn.lib()                       # fails loudly if the HIP library is not built
-
-    w = synth.WORKLOADS[args.workload]
-    if args.batch is not None:
-        w = synth.scaled(w, B=args.batch, name="%s-B%d" % (w.name, args.batch))
-    if args.top_k is not None:
-        w = synth.scaled(w, k=args.top_k, name="%s-k%d" % (w.name, args.top_k))
-    if args.cand_law is not None:
-        w = synth.scaled(w, cand_law=args.cand_law, name="%s-%s" % (w.name, args.cand_law))
-    if args.query_tokens is not None:
-        w = synth.scaled(w, Q=args.query_tokens, name="%s-Q%d" % (w.name, args.query_tokens))
+    torch.cuda.set_device(torch.device("cuda:0"))
+    espn.lib()                              # fails loudly if the HIP library is not built
     seed = synth.DEFAULT_SEED if args.seed is None else args.seed
-    steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload]
-    # steps of tens of microseconds: a warm-up as long as the timed region (about 15 ms), or the first timed
-    # steps still run at the clocks of an idle device (measured on c2: 38.3 us per step after 40 warm-up steps,
-    # 37.4 us after 400 or 2000)
-    short_steps = args.workload in ("c1", "c2", "c2p64", "c2e4m3")
-    if args.warmup is not None:
-        warmup = args.warmup
-    elif short_steps:
-        warmup = steps
-    else:       # about 20-30 ms of warm-up for the steps of 0.4-5 ms as well (c3 after 10 steps: 0.70 ms per launch
-        warmup = max(4, (steps * 2) // 5)       # in the first timed loop, 0.68 ms in the later ones)
-    n_sets = args.sets if args.sets is not None else DEFAULT_SETS[args.workload]
-    if w.host_resident:
-        if n_sets <= args.slots:
-            n_sets = args.slots + 1        # a prefetch takes over what other slots hold: never the same batch again
-        run_host_resident(args, w, seed, steps, args.warmup if args.warmup is not None else 1, n_sets)
-        return
+    keys = list(ALL) if args.workload == "all" else [args.workload]
 
-    t_setup = time.time()
-    emb, off = synth.table(w, seed, device=dev)
-    counts = np.diff(off)
-    elem_bytes, doc_scale = 2, None
-    if w.codec == "e4m3":
-        codes, doc_scale = synth.compress_e4m3(emb, off)
-        del emb
-        emb, elem_bytes = codes, 1
-        table = espn.espn_table_load_e4m3(emb, doc_scale, off)
-    else:
-        table = espn.espn_table_load(emb, off)
-    espn.espn_table_set_fetch(table, {"auto": espn.ESPN_FETCH_AUTO, "streaming": espn.ESPN_FETCH_STREAMING,
-                                      "cached": espn.ESPN_FETCH_CACHED}[args.fetch])
-    log("%s: table %d docs, %d rows x %d, %.2f GB in HBM (%.1f s)" % (
-        w.name, w.n_docs, emb.shape[0], w.dim, emb.numel() * elem_bytes / 1e9, time.time() - t_setup))
-    cands_np = [synth.candidates(w, seed, s) for s in range(n_sets)]
-    cands = [torch.from_numpy(c).to(dev) for c in cands_np]
-    qs = [synth.queries(w, seed, s, device=dev) for s in range(n_sets)]
-    out_ids = [torch.empty((w.B, w.k), dtype=torch.int64, device=dev) for _ in range(n_sets)]
-    out_sc = [torch.empty((w.B, w.k), dtype=torch.float32, device=dev) for _ in range(n_sets)]
-    R = w.rerank_top if w.rerank_top else w.K          # candidates per query that are actually scored
-    ws_bytes = espn.espn_workspace_bytes(w.B, R)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    scores_view = ws[: 4 * w.B * R].view(torch.float32).view(w.B, R)
-    log("inputs ready: %d sets of %d x %d candidates, %d scored per query (%.1f s)" % (
-        n_sets, w.B, w.K, R, time.time() - t_setup))
+    def steps_of(key):
+        return args.steps if args.steps is not None else DEFAULT_STEPS[key]
 
-    # algorithmic bytes of one score-kernel launch: per scored pair the document's rows, its offset
-    # pair, its id and its score; per query its matrix once
-    scored_np = [c[:, :R] for c in cands_np]
-    per_pair = 28.0 + (4.0 if elem_bytes == 1 else 0.0)             # + the document's scale
-    pair_bytes = [float((elem_bytes * w.dim * counts[c]).sum()) + per_pair * c.size for c in scored_np]
-    launch_bytes = float(np.mean(pair_bytes)) + w.B * w.Q * w.dim * 2
-    flops = float(np.mean([(2.0 * w.Q * w.dim * counts[c]).sum() for c in scored_np]))
+    def warmup_of(key):
+        if args.warmup is not None:
+            return args.warmup
+        steps = steps_of(key)       # short steps: as many as are timed; long ones: two fifths of them
+        return steps if key in SHORT_STEPS else max(4, (steps * 2) // 5)
 
-    stream = torch.cuda.current_stream()
-    st = int(stream.cuda_stream)
-    h = table.handle
+    wake_ms = args.wake_up_ms
+    if wake_ms is None:
+        wake_ms = 30.0 if (args.warmup is None and args.steps is None) else 0.0
 
-    def rerank(i, on=None, scratch=None):
-        s = i % n_sets
-        on = st if on is None else on
-        scratch = ws if scratch is None else scratch
-        if w.rerank_top:
-            rc = lib.espn_rerank_partial(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, R, w.k,
-                                         out_ids[s].data_ptr(), out_sc[s].data_ptr(), scratch.data_ptr(), ws_bytes, on)
-        else:
-            rc = lib.espn_rerank(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, w.k,
-                                 out_ids[s].data_ptr(), out_sc[s].data_ptr(), scratch.data_ptr(), ws_bytes, on)
-        if rc != 0:
-            raise RuntimeError("re-rank failed: " + espn.last_error())
-
-    def score_only(i):
-        s = i % n_sets
-        if w.rerank_top:      # k = 0: the scoring kernel alone, on the first R candidates of every list
-            rc = lib.espn_rerank_partial(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, R, 0,
-                                         None, None, ws.data_ptr(), ws_bytes, st)
-        else:
-            rc = lib.espn_score(h, qs[s].data_ptr(), cands[s].data_ptr(), w.B, w.Q, w.K, ws.data_ptr(), st)
-        if rc != 0:
-            raise RuntimeError("scoring failed: " + espn.last_error())
-
-    def score_then_topk(i):
-        score_only(i)
-        if not w.rerank_top:
-            s = i % n_sets
-            rc = lib.espn_topk(ws.data_ptr(), cands[s].data_ptr(), w.B, w.K, w.k,
-                               out_ids[s].data_ptr(), out_sc[s].data_ptr(), st)
-            if rc != 0:
-                raise RuntimeError("espn_topk failed: " + espn.last_error())
-
-    if args.calibration_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.add(src, 1.0, out=dst)            # reads 2^30 bytes, writes 2^30 bytes
-        torch.cuda.synchronize()
-        del src, dst
-
-    # ---- timed region: exactly `steps` passes of the whole path
-    plan = espn.espn_rerank_plan(table, w.B, w.Q, R, min(w.k, R))
-    wake_up = 0
-    if args.warmup is not None:
-        # an explicit --warmup is run as asked; before it, the same call is repeated for about 30 ms so that the
-        # device is at speed whatever W is (reported as wake_up_steps, not part of warmup or steps)
-        t_wake = time.perf_counter()
-        while time.perf_counter() - t_wake < 0.03 and wake_up < 5000:
-            for i in range(8):
-                rerank(wake_up + i)
-            torch.cuda.synchronize()
-            wake_up += 8
-    t_warm = time.perf_counter()
-    for i in range(warmup):
-        rerank(i)
-    torch.cuda.synchronize()
-    if args.warmup is None:
-        # the default warm-up counts assume the workload's own batch size; with a smaller batch they may end
-        # before the device is at speed (512 Zipf lists at d=128: 1.32 ms per step in a timed region that follows
-        # 5 ms of warm-up, 1.20 ms after 30 ms), so go on to about 30 ms
-        spent = time.perf_counter() - t_warm
-        if spent < 0.03 and warmup > 0:
-            more = min(5000, int((0.03 - spent) / (spent / warmup)) + 1)
-            for i in range(warmup, warmup + more):
-                rerank(i)
-            warmup += more
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for i in range(warmup, warmup + steps):
-        rerank(i)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    espn.espn_table_check(table)
-    ms_per_step = wall * 1e3 / steps
-    path_ms = e0.elapsed_time(e1) / steps
-    docs_per_s = w.B * R * steps / wall            # documents actually MaxSim-scored
-
-    # ---- the dominant (MaxSim) kernel: average duration of a launch, dispatch gap included, from one
-    # pair of HIP events on the launch stream around `steps` back-to-back launches.  Where one pass is
-    # one launch (the scoring kernel ranks as well) that is the timed region itself; where a second
-    # launch ranks, the scoring kernel is launched `steps` times on its own.
-    for i in range(min(warmup, 3)):
-        score_only(i)
-    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    s0.record(stream)
-    for i in range(steps):
-        score_only(i)
-    s1.record(stream)
-    torch.cuda.synchronize()
-    score_only_ms = s0.elapsed_time(s1) / steps
-
-    # ---- ... and the path as two launches (scores, then the stand-alone ranking kernel)
-    two_launch_ms = None
-    if not w.rerank_top:
-        for i in range(min(warmup, 3)):
-            score_then_topk(i)
-        u0, u1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        u0.record(stream)
-        for i in range(steps):
-            score_then_topk(i)
-        u1.record(stream)
-        torch.cuda.synchronize()
-        two_launch_ms = u0.elapsed_time(u1) / steps
-    # ---- the same `steps` batches issued alternately on two streams (each with its own workspace): a
-    # server with independent batches in flight hides one batch's launch gaps, look-up latency and
-    # ranking behind the other batch's streaming.  Reported beside `value`, never as `value`.
-    # Only with --two-streams: overlapped launches would blur the per-kernel averages of a profiler run.
-    two_stream_wall = None
-    if args.two_streams:
-        ns = args.two_streams
-        side = [torch.cuda.Stream() for _ in range(ns)]
-        side_ws = [ws] + [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(ns - 1)]
-        side_st = [int(x.cuda_stream) for x in side]
-        for i in range(max(min(warmup, 8), ns)):
-            rerank(i, side_st[i % ns], side_ws[i % ns])
-        torch.cuda.synchronize()
+    # ---- HBM-resident workloads: set all of them up, then their timed regions back to back
+    tables, cases, results = {}, [], {}
+    for key in keys:
+        if key not in HOST_WORKLOADS:
+            cases.append(HbmCase(args, key, seed, steps_of(key), warmup_of(key), tables))
+    woken = 0
+    if cases and wake_ms > 0:
+        c = cases[0]
         t0 = time.perf_counter()
-        for i in range(steps):
-            rerank(i, side_st[i % ns], side_ws[i % ns])
-        torch.cuda.synchronize()
-        two_stream_wall = time.perf_counter() - t0
-        espn.espn_table_check(table)
-
-    # ---- a measuring stick: a plain contiguous read (nothing depends on what is read) of as many bytes as one
-    # launch of the scoring kernel reads, over successive windows of the table (the last-level cache never holds
-    # the window that comes next), `steps` launches back to back, timed like the scoring kernel
-    window = min(int(launch_bytes) // 4096 * 4096, emb.numel() * elem_bytes // 4096 * 4096)
-    flat = emb.view(torch.uint8).view(-1)
-    n_windows = max(1, min(64, flat.numel() // window))
-    sink = torch.zeros(1, dtype=torch.int64, device=dev)
-
-    def plain_read(i):
-        o = (i % n_windows) * window
-        rc = lib.espn_stream_read_probe(flat.data_ptr() + o, window, sink.data_ptr(), st)
-        if rc != 0:
-            raise RuntimeError("read probe failed: " + espn.last_error())
-
-    for i in range(min(warmup, 8)):
-        plain_read(i)
-    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    p0.record(stream)
-    for i in range(steps):
-        plain_read(i)
-    p1.record(stream)
-    torch.cuda.synchronize()
-    plain_read_gbs = window / (p0.elapsed_time(p1) / steps * 1e-3) / 1e9
-
-    kern_avg_ms = path_ms if plan["launches"] == 1 else score_only_ms
-    achieved = launch_bytes / (kern_avg_ms * 1e-3) / 1e9
-    log("plain read of %.1f MB windows: %.1f GB/s (%d windows)" % (window / 1e6, plain_read_gbs, n_windows))
-    log("wall %.4f ms/step (%d launch(es), %d slice(s) of %d per query); MaxSim kernel avg %.4f ms = %.1f GB/s "
-        "algorithmic; scoring without ranking %.4f ms; score + stand-alone ranking %s ms" % (
-            ms_per_step, plan["launches"], plan["slices"], plan["slice"], kern_avg_ms, achieved, score_only_ms,
-            "n/a" if two_launch_ms is None else "%.4f" % two_launch_ms))
-    if two_stream_wall is not None:
-        log("on %d streams: %.4f ms/step = %.1f GB/s algorithmic" % (
-            args.two_streams, two_stream_wall * 1e3 / steps, launch_bytes * steps / two_stream_wall / 1e9))
-
-    result = {
-        "metric": "candidate docs MaxSim-scored/sec",
-        "value": docs_per_s,
-        "unit": "docs/s",
-        "n_gpus": 1,
-        "steps": steps,
-        "warmup": warmup,
-        "wake_up_steps": wake_up,
-        "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f16",
-        "data": "synthetic",
-        "config": {
-            "workload": w.name, "n_docs": w.n_docs, "dim": w.dim, "rows": int(emb.shape[0]),
-            "table_gb": emb.numel() * elem_bytes / 1e9, "codec": w.codec, "tokens_per_doc": "%s[%d,%d]" % (w.count_law, w.count_lo, w.count_hi),
-            "batch_queries": w.B, "query_tokens": w.Q, "candidates_per_query": w.K, "scored_per_query": R,
-            "top_k": w.k, "candidate_law": w.cand_law, "rotating_sets": n_sets, "accumulate": "f32", "seed": seed,
-            "fetch": args.fetch,
-        },
-        "queries_per_s": w.B * steps / wall,
-        "wall_algorithmic_gbs": launch_bytes * steps / wall / 1e9,
-        "wall_frac_of_hbm_peak": launch_bytes * steps / wall / 1e9 / HBM_PEAK_GBS,
-        "two_streams": None if two_stream_wall is None else {
-            "value": w.B * R * steps / two_stream_wall, "unit": "docs/s", "ms_per_step": two_stream_wall * 1e3 / steps,
-            "algorithmic_gbs": launch_bytes * steps / two_stream_wall / 1e9,
-            "streams": args.two_streams, "note": "the same batches issued in turn on several streams"},
-        "roofline": {
-            "bound": "hbm",
-            "kernel": ("maxsim_slice_kernel<%d>%s" % (w.dim, " (ranks as well)" if plan["launches"] == 1 else "")
-                       if w.dim in (32, 128) and w.Q <= 64 else "maxsim_generic_kernel (plain ALU)"),
-            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-            "algorithmic_bytes_per_launch": launch_bytes, "kernel_ms_avg": kern_avg_ms,
-            "launches_per_step": plan["launches"], "slices_per_query": plan["slices"],
-            "whole_path_ms_by_events": path_ms, "scoring_without_ranking_ms": score_only_ms,
-            "score_then_standalone_ranking_ms": two_launch_ms,
-            "mfma_tflops": flops / (kern_avg_ms * 1e-3) / 1e12,
-            "plain_read_same_bytes_gbs": plain_read_gbs, "achieved_over_plain_read": achieved / plain_read_gbs,
-        },
-    }
-
-    # ---- the CPU oracle on a bounded sample of the same workload (reported baseline + parity check)
-    if not args.no_cpu_baseline:
-        import oracle
-        from tests.parity import assert_scores_close, assert_topk_matches
-        # sample: whole batches 0..nb-1 (c1, c2) or the first nq queries of batch 0 (c3, c4), sized for
-        # roughly 10-30 core-seconds of oracle work
-        nb = {"c1": min(16, n_sets), "c2": min(8, n_sets), "c2p64": min(8, n_sets),
-              "c2e4m3": min(4, n_sets)}.get(args.workload, 1)
-        nq = w.B if args.workload in ("c1", "c2", "c2p64", "c2e4m3") else min(128 * (w.K // R), w.B)
-        if w.codec == "e4m3" and args.workload != "c2e4m3":
-            nq = min(32, w.B)
-        if args.cpu_sample_queries is not None:
-            nb, nq = 1, min(args.cpu_sample_queries, w.B)
-        threads = oracle.max_threads()
-        cpu_s, worst, pairs = 0.0, 0.0, 0
-        for s in range(nb):
-            sub, loc_off, loc_cand, ids = synth.subtable(emb, off, scored_np[s][:nq])
-            q_np = qs[s][:nq].cpu().numpy()
-            t1 = time.perf_counter()
-            if w.codec == "e4m3":
-                o_all = oracle.scores_e4m3(sub, doc_scale[ids], loc_off, q_np, loc_cand)
-                o_ids, o_top = oracle.topk(o_all, loc_cand, w.k)
-            else:
-                o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q_np, loc_cand, w.k)     # the scored prefix
-            cpu_s += time.perf_counter() - t1
-            # parity of the timed configuration on the same sample
-            rerank(s)
+        while time.perf_counter() - t0 < wake_ms * 1e-3 and woken < 20000:
+            for i in range(4):
+                c.rerank(woken + i)
             torch.cuda.synchronize()
-            g_all = scores_view[:nq].cpu().numpy()
-            g_ids, g_top = out_ids[s][:nq].cpu().numpy(), out_sc[s][:nq].cpu().numpy()
-            worst = max(worst, assert_scores_close(g_all, o_all, w.Q))
-            for b in range(nq):
-                assert_topk_matches(g_ids[b], g_top[b], o_all[b], scored_np[s][b], w.k, w.Q)
-            pairs += nq * R
-        # the same oracle on ONE thread, on a 16th of the first sample (last: the thread count it sets stays)
-        one_thread = None
-        if w.codec != "e4m3":
-            n1 = max(1, nq // 16)
-            sub, loc_off, loc_cand, ids = synth.subtable(emb, off, scored_np[0][:n1])
-            t1 = time.perf_counter()
-            oracle.rerank(sub, loc_off, qs[0][:n1].cpu().numpy(), loc_cand, w.k, threads=1)
-            one_thread = n1 * R / (time.perf_counter() - t1)
-        result["cpu_baseline"] = {
-            "value": pairs / cpu_s, "unit": "docs/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d queries of each of the first %d batches (%d pairs), fp64, %.1f s wall" % (
-                nq, nb, pairs, cpu_s),
-            "value_one_thread": one_thread,
-        }
-        result["parity"] = {"sample_pairs": pairs, "worst_rel_err": worst, "status": "ok"}
-        log("oracle: %.0f docs/s on %d threads%s; parity ok on %d pairs (worst rel err %.2e)" % (
-            pairs / cpu_s, threads, "" if one_thread is None else " (%.0f on one)" % one_thread, pairs, worst))
+            woken += 4
+    for c in cases:
+        if args.kernels_only:
+            c.batched = False
+            c.legs()
+            c.wall, c.ms_per_step = c.sequential_wall_ms * 1e-3 * c.steps, c.sequential_wall_ms
+        else:
+            c.timed()
+    for c in cases:
+        if not args.kernels_only:
+            c.legs()
+        if not args.no_cpu_baseline:
+            c.oracle(args.cpu_sample_queries)
+        results[c.key] = c.result()
+        results[c.key]["wake_up_steps"] = woken if c is cases[0] else 0
+        if args.kernels_only:
+            results[c.key]["config"]["entry_point"] = "espn_rerank, one call per batch on one stream (--kernels-only)"
+        c.free()
+    del cases
+    tables.clear()
+    torch.cuda.empty_cache()
 
-    print(json.dumps(result), flush=True)
+    # ---- host-resident workloads, one after the other (each holds up to 156 GB of host memory)
+    for key in keys:
+        if key in HOST_WORKLOADS:
+            results[key] = run_host_resident(args, key, seed, steps_of(key), args.warmup if args.warmup is not None else 1)
+            torch.cuda.empty_cache()
+
+    head = results[keys[0]]
+    if len(keys) > 1:
+        head["configs"] = [results[key] for key in keys[1:]]
+    print(json.dumps(head), flush=True)
 
 
 if __name__ == "__main__":

@@ -38,14 +38,15 @@ typedef enum espn_status {
     ESPN_ERR_ID_RANGE = 4,     /* a candidate id outside [0, n_docs) was met by a kernel */
     ESPN_ERR_NOMEM = 5,        /* host or device allocation failed */
     ESPN_ERR_HIP = 6,          /* a HIP runtime call failed; see espn_last_error() */
-    ESPN_ERR_UNSUPPORTED = 7,  /* a shape this build has no kernel for */
-    ESPN_ERR_BUSY = 8          /* a staging slot is still in use */
+    ESPN_ERR_UNSUPPORTED = 7   /* a shape this build has no kernel for */
 } espn_status;
 
 typedef struct espn_table espn_table;   /* opaque; owned by the library */
 
-/* Where the packed embedding rows live. */
-enum { ESPN_RESIDENT_HBM = 0, ESPN_RESIDENT_HOST_PINNED = 1 };
+/* Where the packed embedding rows live: in device memory; in pinned host memory, which the device can read
+ * (either prefetch engine works); or in ordinary host memory, which only the host reads (espn_prefetch_packed
+ * only: what a machine that refuses to pin a table of the paper's size still can do). */
+enum { ESPN_RESIDENT_HBM = 0, ESPN_RESIDENT_HOST_PINNED = 1, ESPN_RESIDENT_HOST = 2 };
 
 /* Static string for a status code. */
 const char *espn_status_string(int status);
@@ -59,7 +60,7 @@ const char *espn_last_error(void);
  *   emb          [total_rows, dim] binary16, row-major, packed: document i owns rows
  *                offsets[i] .. offsets[i+1]-1.  DEVICE pointer if residency is
  *                ESPN_RESIDENT_HBM; pinned HOST pointer (hipHostMalloc) if
- *                ESPN_RESIDENT_HOST_PINNED.  BORROWED: never copied, never freed; the caller
+ *                ESPN_RESIDENT_HOST_PINNED; any HOST pointer if ESPN_RESIDENT_HOST.  BORROWED: never copied, never freed; the caller
  *                keeps it alive and unchanged until espn_table_free.  Must be 16-byte aligned.
  *   offsets_host [n_docs + 1] int64 HOST pointer, in rows; offsets[0] = 0, non-decreasing
  *                (a document may be empty).  COPIED (to the device); may be freed after the call.
@@ -101,27 +102,34 @@ int espn_table_info(const espn_table *table, int64_t *n_docs, int64_t *total_row
 
 /*
  * How the rows of the table are fetched by the scoring kernels:
- *   ESPN_FETCH_AUTO       decided per batch.  Every 64th scoring call on the table also samples its candidate
- *                         lists (one small kernel on the caller's stream, result left in pinned host memory);
- *                         later calls take cached if more than 5 % of the sampled pairs repeated a document,
- *                         streaming if not.  Before the first sample is in: streaming for 64-byte rows, and for
- *                         longer rows if the batch has at most half as many (query, candidate) pairs as the table
- *                         has documents.  The default.
+ *   ESPN_FETCH_AUTO       decided per batch from what the library knows, nothing else: if espn_table_sample has
+ *                         been called, cached if more than 5 % of the sampled pairs repeated a document, streaming
+ *                         if not; before that, streaming for 64-byte rows, and for longer rows if the batch has at
+ *                         most half as many (query, candidate) pairs as the table has documents.  The default.
  *   ESPN_FETCH_STREAMING  non-temporal loads: fastest when the queries of a batch list different documents
  *                         (uniformly drawn lists: 2 to 12 % faster than cached).
  *   ESPN_FETCH_CACHED     ordinary loads that leave the rows in the caches: fastest when the lists overlap,
  *                         whatever the batch size (lists drawn from a Zipf law: 10 to 36 % faster than streaming
  *                         from 64 queries per batch on).
- * The scores do not depend on it.  Takes effect from the next call on.  Errors: ARG.
+ * The scores do not depend on it.  Takes effect from the next call on.  The same calls in the same order always
+ * run the same kernels (no call looks at the clock, at a call count or at unfinished work).  Errors: ARG.
  */
 enum { ESPN_FETCH_AUTO = 0, ESPN_FETCH_STREAMING = 1, ESPN_FETCH_CACHED = 2 };
 int espn_table_set_fetch(espn_table *table, int32_t mode);
 
 /*
- * The last sample taken under ESPN_FETCH_AUTO: the fraction of up to 4096 sampled (query, candidate) pairs of a
- * batch whose document another sampled pair had named already; -1 before the first sample has arrived.  Never
- * waits (the value may be that of an earlier batch).  estimate: HOST pointer.  Errors: ARG.
+ * Tell the library what this caller's candidate lists look like (Sec. 4.4: about a thousand candidates per query
+ * from the first stage; popular documents recur): up to 4096 evenly spaced (query, candidate) pairs of the batch
+ * are put into a hash set by one small kernel on `stream`, and the fraction whose document another sampled pair
+ * had named already is kept with the table for ESPN_FETCH_AUTO (and espn_table_sharing_estimate).  Uniform lists
+ * over 2 M documents give 0.002, Zipf(1.1) lists more than 0.5.
+ *   cand  [B, K] int64, DEVICE.
+ * SYNCHRONOUS: waits for `stream` (call it once when a workload starts, not per batch).  Errors: ARG, HIP.
  */
+int espn_table_sample(espn_table *table, const int64_t *cand, int32_t B, int32_t K, void *stream);
+
+/* The result of the last espn_table_sample on this table, -1 if there was none.  estimate: HOST pointer.
+ * Errors: ARG. */
 int espn_table_sharing_estimate(const espn_table *table, float *estimate);
 
 /*
@@ -174,6 +182,35 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The whole hot path for a QUEUE of batches of one shape (Sec. 5.4, 5.5: throughput under batched queries): the
+ * same results as n_batches calls of espn_rerank, bit for bit, at the cost of a long launch instead of many short
+ * ones.  Small batches (64 queries x 1000 candidates at dim 32: a 31 us scoring launch, of which the launch gap and
+ * the two dependent look-ups at its start are a sixth, plus a ranking launch) are scored up to 16 at a time by ONE
+ * launch that streams like one large batch, and ranked by one more; these chunks - or, for batches that fill the
+ * device many times over by themselves, the batches - are dealt in turn to ESPN_BATCH_LANES streams of the library's
+ * own (created with the table, default priority), so that the ranking of one chunk and the start of the next
+ * overlap with the streaming of the one before.  The library's streams wait for everything enqueued on `stream`
+ * before the call (nothing, if it is idle), and `stream` waits for all of the call's batches: to the caller it is
+ * one asynchronous operation on `stream`, results valid when it is through.
+ *
+ *   q, cand, out_ids, out_scores  HOST arrays of n_batches DEVICE pointers, each as in espn_rerank; the arrays
+ *                                 themselves are read before the call returns.
+ *   workspace                     DEVICE, 256-byte aligned, espn_batches_workspace_bytes(table, n_batches, B, Q, K, k)
+ *                                 bytes (up to 3 x 16 x espn_workspace_bytes(B, K)); contents undefined afterwards,
+ *                                 except that a call with n_batches <= ESPN_BATCH_LANES leaves the B*K scores of
+ *                                 batch 0 at its start.
+ * A queue that makes one launch runs on `stream` itself.  Not to be called for one table from several host
+ * threads at once.
+ * Errors: ARG, SHAPE, UNSUPPORTED, HIP (all argument checks are done before anything is enqueued).
+ */
+#define ESPN_BATCH_LANES 3
+size_t espn_batches_workspace_bytes(const espn_table *table, int32_t n_batches, int32_t B, int32_t Q, int32_t K, int32_t k);
+int espn_rerank_batches(espn_table *table, int32_t n_batches, const void *const *q, const int64_t *const *cand,
+                        int32_t B, int32_t Q, int32_t K, int32_t k,
+                        int64_t *const *out_ids, float *const *out_scores,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * espn_rerank for callers that cannot allocate device memory and have no workspace to hand in: code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation.  The B*K scores that espn_rerank keeps
  * in the caller's workspace go to a fixed array inside the library's code object instead (one copy per device,
@@ -201,6 +238,16 @@ int espn_rerank_noalloc(espn_table *table, const void *q, const int64_t *cand,
  */
 int espn_rerank_plan(const espn_table *table, int32_t B, int32_t Q, int32_t K, int32_t k,
                      int32_t *slices, int32_t *slice, int32_t *launches);
+
+/*
+ * The kernels espn_rerank would launch for a batch of this shape, by the names a profiler prints for them (template
+ * arguments included), separated by ';': the scoring kernel, then the ranking kernel if a second launch ranks.
+ * Lets a benchmark tie a counter profile to the kernels that actually run.  Empty for an empty batch.
+ *   buf  HOST, buf_len bytes (256 always suffice); receives a NUL-terminated string.
+ * Host arithmetic only.  Errors: ARG, SHAPE (k > K, or buf too small).
+ */
+int espn_rerank_plan_kernels(const espn_table *table, int32_t B, int32_t Q, int32_t K, int32_t k,
+                             char *buf, size_t buf_len);
 
 /*
  * Partial re-ranking (Sec. 4.4): the candidate list of a query arrives best-first from the first
@@ -257,18 +304,6 @@ int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_t ka,
 double espn_batch_threshold(double bandwidth_bytes_per_s, double budget_s, double bytes_per_query);
 
 /*
- * A measuring stick, not a step of the method: read `bytes` bytes starting at `src` once, contiguously,
- * with nothing that depends on what is read (16 bytes per lane, non-temporal loads, every workgroup
- * walks its own contiguous part: the fastest plain read found on this machine).  bench.py times it over windows of the table as large as one batch's reads, as the
- * rate a dependency-free kernel reaches on the same machine next to the gather + MaxSim kernel (whose
- * reads hang on two dependent look-ups per document, Sec. 4).
- *   src    DEVICE (or device-visible pinned HOST) memory, 16-byte aligned; bytes a multiple of 16.
- *   sink   DEVICE, 8 bytes, written only if the xor of everything read is all ones (keeps the loads alive).
- * Errors: ARG, HIP.
- */
-int espn_stream_read_probe(const void *src, size_t bytes, uint64_t *sink, void *stream);
-
-/*
  * Wait for `stream` and report errors kernels recorded for this table since the last check:
  * returns ESPN_ERR_ID_RANGE if any candidate id was out of range, else ESPN_OK; clears the flag.
  */
@@ -314,7 +349,8 @@ int espn_staging_create_ring(espn_table *table, int32_t n_slots, int64_t capacit
  * distinct ids, reserve rows, copy rows).  The call waits (on the device) for the last prefetch into
  * every other slot, whatever stream that ran on.
  *   cand  [B, K] int64, DEVICE; must stay unchanged until the prefetch has run.
- * Errors: ARG, HIP.  Ids out of range are flagged as in espn_score.
+ * Errors: ARG, HIP, UNSUPPORTED (a table in ordinary host memory, which the device cannot read).  Ids out of
+ * range are flagged as in espn_score.
  */
 int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, int32_t K, int32_t slot, void *side_stream);
 
@@ -326,8 +362,11 @@ int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, int32_t K, 
  * taken from other slots.  The slot ends up in the same state as after espn_prefetch (espn_rerank_staged,
  * espn_staging_counters and later espn_prefetch calls into other slots work on it unchanged).
  *   cand_host  [B, K] int64, HOST; read before the call returns.
+ * The table may be in pinned or in ordinary host memory (ESPN_RESIDENT_HOST_PINNED, ESPN_RESIDENT_HOST).
  * Unlike espn_prefetch this call BLOCKS the host until all but the last two buffers have been sent, and
- * its first call on a table allocates the pinned buffers (freed with the staging slots).  Its errors
+ * its first call on a table allocates the pinned buffers and starts the packing threads (released with the
+ * staging slots).  The slot's document map is written after the last row copy: if a copy cannot be enqueued
+ * the call returns the error and the slot holds no document.  Its errors
  * are found on the host before anything is enqueued: ID_RANGE (an id outside the table), NOMEM (the
  * batch does not fit the slot, or no pinned memory), UNSUPPORTED (the table is HBM-resident, or a
  * document is larger than a buffer), ARG, HIP.

@@ -16,8 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libespn.so")
 
 ESPN_OK = 0
 ESPN_ERR_ARG, ESPN_ERR_SHAPE, ESPN_ERR_OFFSETS, ESPN_ERR_ID_RANGE = 1, 2, 3, 4
-ESPN_ERR_NOMEM, ESPN_ERR_HIP, ESPN_ERR_UNSUPPORTED, ESPN_ERR_BUSY = 5, 6, 7, 8
-ESPN_RESIDENT_HBM, ESPN_RESIDENT_HOST_PINNED = 0, 1
+ESPN_ERR_NOMEM, ESPN_ERR_HIP, ESPN_ERR_UNSUPPORTED = 5, 6, 7
+ESPN_RESIDENT_HBM, ESPN_RESIDENT_HOST_PINNED, ESPN_RESIDENT_HOST = 0, 1, 2
+ESPN_BATCH_LANES = 3
 ESPN_FETCH_AUTO, ESPN_FETCH_STREAMING, ESPN_FETCH_CACHED = 0, 1, 2
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
@@ -30,6 +31,7 @@ SIGNATURES = {
     "espn_table_load_e4m3": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i64, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_p)]),
     "espn_table_free": (ctypes.c_int, [_c_p]),
     "espn_table_set_fetch": (ctypes.c_int, [_c_p, _c_i32]),
+    "espn_table_sample": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_i32, _c_p]),
     "espn_table_sharing_estimate": (ctypes.c_int, [_c_p, ctypes.POINTER(ctypes.c_float)]),
     "espn_table_info": (ctypes.c_int, [_c_p, ctypes.POINTER(_c_i64), ctypes.POINTER(_c_i64),
                                        ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
@@ -38,7 +40,11 @@ SIGNATURES = {
     "espn_workspace_bytes": (_c_sz, [_c_i32, _c_i32]),
     "espn_rerank_plan": (ctypes.c_int, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_i32),
                                         ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32)]),
+    "espn_rerank_plan_kernels": (ctypes.c_int, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, ctypes.c_char_p, _c_sz]),
     "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "espn_batches_workspace_bytes": (_c_sz, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32]),
+    "espn_rerank_batches": (ctypes.c_int, [_c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p,
+                                           _c_sz, _c_p]),
     "espn_rerank_noalloc": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
     "espn_rerank_partial": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p,
                                            _c_p, _c_sz, _c_p]),
@@ -46,7 +52,6 @@ SIGNATURES = {
                                          _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "espn_merge_topk": (ctypes.c_int, [_c_p, _c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
     "espn_batch_threshold": (ctypes.c_double, [ctypes.c_double, ctypes.c_double, ctypes.c_double]),
-    "espn_stream_read_probe": (ctypes.c_int, [_c_p, _c_sz, _c_p, _c_p]),
     "espn_table_check": (ctypes.c_int, [_c_p, _c_p]),
     "espn_staging_create": (ctypes.c_int, [_c_p, _c_i64, _c_i64]),
     "espn_staging_create_ring": (ctypes.c_int, [_c_p, _c_i32, _c_i64, _c_i64]),
@@ -124,7 +129,7 @@ class Table:
     """Handle of a loaded table (espn_table_load / espn_table_free).  Keeps `emb` alive."""
 
     def __init__(self, emb: torch.Tensor, offsets, dim: int | None = None, device: int | None = None,
-                 doc_scale=None):
+                 doc_scale=None, pageable: bool = False):
         import numpy as np
         want = torch.float16 if doc_scale is None else torch.uint8
         if emb.dtype != want or emb.dim() != 2 or not emb.is_contiguous():
@@ -138,8 +143,11 @@ class Table:
             residency, dev = ESPN_RESIDENT_HBM, emb.device.index
         elif emb.is_pinned():
             residency, dev = ESPN_RESIDENT_HOST_PINNED, (torch.cuda.current_device() if device is None else device)
+        elif pageable:
+            residency, dev = ESPN_RESIDENT_HOST, (torch.cuda.current_device() if device is None else device)
         else:
-            raise TypeError("emb must live in device memory or in pinned host memory")
+            raise TypeError("emb must live in device memory or in pinned host memory (ordinary host memory: "
+                            "pass pageable=True; only espn_prefetch_packed can then fill staging slots)")
         self.emb, self.n_docs, self.dim = emb, off.shape[0] - 1, emb.shape[1] if dim is None else dim
         self.device = dev
         self._h = _c_p()
@@ -178,16 +186,26 @@ class Table:
                 "device": dev.value}
 
 
-def espn_table_load(emb: torch.Tensor, offsets, device: int | None = None) -> Table:
-    return Table(emb, offsets, device=device)
+def espn_table_load(emb: torch.Tensor, offsets, device: int | None = None, pageable: bool = False) -> Table:
+    return Table(emb, offsets, device=device, pageable=pageable)
 
 
-def espn_table_load_e4m3(codes: torch.Tensor, doc_scale, offsets, device: int | None = None) -> Table:
-    return Table(codes, offsets, device=device, doc_scale=doc_scale)
+def espn_table_load_e4m3(codes: torch.Tensor, doc_scale, offsets, device: int | None = None,
+                         pageable: bool = False) -> Table:
+    return Table(codes, offsets, device=device, doc_scale=doc_scale, pageable=pageable)
 
 
 def espn_table_set_fetch(table: Table, mode: int) -> None:
     _check(lib().espn_table_set_fetch(table.handle, mode))
+
+
+def espn_table_sample(table: Table, cand: torch.Tensor, stream=None) -> float:
+    """Samples the batch's candidate lists (synchronous); returns the estimate the table now holds."""
+    if cand.dim() != 2:
+        raise ValueError("cand must be [B,K]")
+    _check(lib().espn_table_sample(table.handle, _dev(cand, torch.int64, "cand"), cand.shape[0], cand.shape[1],
+                                   _stream_ptr(stream)))
+    return espn_table_sharing_estimate(table)
 
 
 def espn_table_sharing_estimate(table: Table) -> float:
@@ -210,6 +228,14 @@ def espn_rerank_plan(table: Table, B: int, Q: int, K: int, k: int) -> dict:
     _check(lib().espn_rerank_plan(table.handle, B, Q, K, k, ctypes.byref(slices), ctypes.byref(slice_),
                                   ctypes.byref(launches)))
     return {"slices": slices.value, "slice": slice_.value, "launches": launches.value}
+
+
+def espn_rerank_plan_kernels(table: Table, B: int, Q: int, K: int, k: int) -> list:
+    """Profiler names of the kernels espn_rerank launches for this shape (scoring, then ranking if separate)."""
+    buf = ctypes.create_string_buffer(256)
+    _check(lib().espn_rerank_plan_kernels(table.handle, B, Q, K, k, buf, 256))
+    text = buf.value.decode()
+    return text.split(";") if text else []
 
 
 def _batch_shape(q: torch.Tensor, cand: torch.Tensor):
@@ -262,6 +288,50 @@ def espn_rerank(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_i
     _check(lib().espn_rerank(table.handle, _dev(q, torch.float16, "q"), _dev(cand, torch.int64, "cand"), B, Q, K, k,
                              _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_scores
+
+
+def espn_batches_workspace_bytes(table: Table, n_batches: int, B: int, Q: int, K: int, k: int) -> int:
+    return int(lib().espn_batches_workspace_bytes(table.handle, n_batches, B, Q, K, k))
+
+
+def pointer_list(tensors, dtype, name: str):
+    """A host array of device pointers (what espn_rerank_batches takes for q, cand, out_ids, out_scores)."""
+    return (_c_p * len(tensors))(*[_dev(t, dtype, "%s[%d]" % (name, i)) for i, t in enumerate(tensors)])
+
+
+def espn_rerank_batches(table: Table, qs, cands, k: int, out_ids=None, out_scores=None,
+                        workspace: torch.Tensor | None = None, stream=None):
+    """A queue of batches of one shape in one call.  qs, cands: lists of [B,Q,dim] / [B,K] tensors.
+    Returns (list of out_ids, list of out_scores)."""
+    n = len(qs)
+    if n != len(cands):
+        raise ValueError("as many query tensors as candidate tensors are needed")
+    if n == 0:
+        return [], []
+    B, Q, K = _batch_shape(qs[0], cands[0])
+    for q, c in zip(qs, cands):
+        if _batch_shape(q, c) != (B, Q, K) or q.shape[2] != table.dim:
+            raise ValueError("all batches of a call must have one shape, with the table's dim")
+    dev = qs[0].device
+    if out_ids is None:
+        out_ids = [torch.empty((B, max(k, 0)), dtype=torch.int64, device=dev) for _ in range(n)]
+    if out_scores is None:
+        out_scores = [torch.empty((B, max(k, 0)), dtype=torch.float32, device=dev) for _ in range(n)]
+    if workspace is None:
+        nbytes = espn_batches_workspace_bytes(table, n, B, Q, K, k)
+        if isinstance(stream, torch.cuda.Stream):
+            with torch.cuda.stream(stream):
+                workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        elif stream is None:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        else:
+            raise ValueError("pass a workspace along with a raw stream handle: torch cannot allocate in its order")
+    _check(lib().espn_rerank_batches(table.handle, n, pointer_list(qs, torch.float16, "q"),
+                                     pointer_list(cands, torch.int64, "cand"), B, Q, K, k,
+                                     pointer_list(out_ids, torch.int64, "out_ids"),
+                                     pointer_list(out_scores, torch.float32, "out_scores"),
+                                     _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream_ptr(stream)))
     return out_ids, out_scores
 
 
@@ -393,14 +463,6 @@ def espn_merge_topk(ids_a: torch.Tensor, scores_a: torch.Tensor, ids_b: torch.Te
                                  _dev(out_ids, torch.int64, "out_ids"), _dev(out_scores, torch.float32, "out_scores"),
                                  _stream_ptr(stream)))
     return out_ids, out_scores
-
-
-def espn_stream_read_probe(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
-    """Enqueue one plain read of all of `src` (a contiguous tensor); sink: an int64 device tensor of one element."""
-    if not src.is_contiguous():
-        raise ValueError("src must be contiguous")
-    _check(lib().espn_stream_read_probe(src.data_ptr(), src.numel() * src.element_size(), _dev(sink, torch.int64, "sink"),
-                                        _stream_ptr(stream)))
 
 
 def espn_batch_threshold(bandwidth_bytes_per_s: float, budget_s: float, bytes_per_query: float) -> float:

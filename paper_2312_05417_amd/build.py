@@ -9,6 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libespn.so")
 SOURCES = [os.path.join(CSRC, "espn.hip")]
+# the benchmark's measuring sticks (a plain read, a plain copy): a library of their own, not part of the product ABI
+PROBE_LIB = os.path.join(HERE, "libespn_benchprobe.so")
+PROBE_SOURCES = [os.path.join(CSRC, "bench_probe.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
@@ -28,14 +31,19 @@ def hipcc() -> str:
     return cand if os.path.exists(cand) else "hipcc"
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *SOURCES]
+def _compile(lib, sources, verbose, extra_flags) -> str:
+    tmp = lib + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *sources]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
+
+
+def build_library(verbose: bool = True, extra_flags=()) -> str:
+    _compile(PROBE_LIB, PROBE_SOURCES, verbose, extra_flags)
+    return _compile(LIB, SOURCES, verbose, extra_flags)
 
 
 if __name__ == "__main__":

@@ -4,10 +4,10 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <condition_variable>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -108,6 +108,73 @@ struct StagingSlot {
     hipEvent_t consumed = nullptr;         // recorded when a re-rank reading the slot has been enqueued
 };
 
+// Worker threads of the packing prefetch engine: run(n, f) calls f(0) .. f(n-1), f(0) on the calling thread.
+class PackPool {
+public:
+    ~PackPool()
+    {
+        {
+            std::lock_guard<std::mutex> lock(m_);
+            stop_ = true;
+        }
+        go_.notify_all();
+        for (std::thread &t : workers_) t.join();
+    }
+    // may throw (std::system_error, std::bad_alloc): call it inside a try block
+    void start(int n_workers)
+    {
+        for (int x = 0; x < n_workers; ++x) workers_.emplace_back([this, x] { loop(x + 1); });
+    }
+    int parts() const { return (int)workers_.size() + 1; }
+    template <typename F>
+    void run(int n, const F &f)
+    {
+        struct Call { static void thunk(const void *ctx, int x) { (*static_cast<const F *>(ctx))(x); } };
+        {
+            std::lock_guard<std::mutex> lock(m_);
+            job_ = &Call::thunk;
+            ctx_ = &f;
+            n_ = n;
+            pending_ = std::min(n, parts()) - 1;
+            ++generation_;
+        }
+        go_.notify_all();
+        f(0);
+        std::unique_lock<std::mutex> lock(m_);
+        done_.wait(lock, [this] { return pending_ == 0; });
+    }
+
+private:
+    void loop(int x)
+    {
+        uint64_t seen = 0;
+        while (true) {
+            void (*job)(const void *, int);
+            const void *ctx;
+            {
+                std::unique_lock<std::mutex> lock(m_);
+                go_.wait(lock, [&] { return stop_ || generation_ != seen; });
+                if (stop_) return;
+                seen = generation_;
+                if (x >= n_) continue;
+                job = job_;
+                ctx = ctx_;
+            }
+            job(ctx, x);
+            std::lock_guard<std::mutex> lock(m_);
+            if (--pending_ == 0) done_.notify_one();
+        }
+    }
+    std::vector<std::thread> workers_;
+    std::mutex m_;
+    std::condition_variable go_, done_;
+    void (*job_)(const void *, int) = nullptr;
+    const void *ctx_ = nullptr;
+    int n_ = 0, pending_ = 0;
+    uint64_t generation_ = 0;
+    bool stop_ = false;
+};
+
 // Host side of the packing prefetch engine (espn_prefetch_packed), made on its first call.
 struct PackState {
     void *buf[2] = {nullptr, nullptr};          // pinned, kPackBytes each: rows on their way to a slot
@@ -118,6 +185,7 @@ struct PackState {
     hipEvent_t lists_sent = nullptr;            // the copies out of uniq / row0 have been enqueued
     bool lists_in_flight = false;
     std::vector<uint64_t> seen;                 // one bit per document of the table
+    PackPool pool;
 };
 
 struct espn_table {
@@ -137,9 +205,12 @@ struct espn_table {
     int32_t residency = 0;
     int32_t device = 0;
     int32_t fetch = ESPN_FETCH_AUTO;   // how rows of 128 bytes and more are fetched
-    float *share_host = nullptr;       // owned, pinned: the last estimate of how much a batch's lists overlap (-1: none yet)
+    float *share_host = nullptr;       // owned, pinned: where espn_table_sample's kernel leaves its result
     float *share_dev = nullptr;        // the same word as the device sees it
-    mutable std::atomic<uint64_t> scored{0};   // scoring launches so far (the estimate is renewed every kShareEvery)
+    float overlap = -1.f;              // the last espn_table_sample result (-1: none yet); read by plan_slices
+    hipStream_t lane[ESPN_BATCH_LANES] = {};      // owned: the streams espn_rerank_batches spreads its batches over
+    hipEvent_t fork = nullptr;                    // owned: the caller's stream has reached the call
+    hipEvent_t joined[ESPN_BATCH_LANES] = {};     // owned: a lane has finished the call's batches
     StagingSlot slot[espn::MAX_SLOTS];
     int n_slots = 0;
     uint64_t prefetches = 0;         // prefetches enqueued so far
@@ -159,7 +230,6 @@ ESPN_API const char *espn_status_string(int status)
         case ESPN_ERR_NOMEM: return "out of memory";
         case ESPN_ERR_HIP: return "HIP runtime error";
         case ESPN_ERR_UNSUPPORTED: return "unsupported shape";
-        case ESPN_ERR_BUSY: return "staging slot busy";
         default: return "unknown status";
     }
 }
@@ -169,6 +239,18 @@ ESPN_API const char *espn_last_error(void) { return g_err; }
 namespace {
 int load_table(const void *emb, const float *doc_scale_host, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
                int32_t residency, int32_t device, espn_table **out);
+
+void destroy_lanes(espn_table *t)
+{
+    for (int l = 0; l < ESPN_BATCH_LANES; ++l) {
+        if (t->lane[l]) (void)hipStreamDestroy(t->lane[l]);
+        if (t->joined[l]) (void)hipEventDestroy(t->joined[l]);
+        t->lane[l] = nullptr;
+        t->joined[l] = nullptr;
+    }
+    if (t->fork) (void)hipEventDestroy(t->fork);
+    t->fork = nullptr;
+}
 }
 
 ESPN_API int espn_table_load(const void *emb, const int64_t *offsets_host, int64_t n_docs, int32_t dim,
@@ -198,7 +280,7 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
     if (!offsets_host) return fail(ESPN_ERR_ARG, "offsets_host is NULL");
     if (n_docs < 0) return fail(ESPN_ERR_ARG, "n_docs = %lld is negative", (long long)n_docs);
     if (dim <= 0 || dim % 8 != 0) return fail(ESPN_ERR_ARG, "dim = %d is not a positive multiple of 8", dim);
-    if (residency != ESPN_RESIDENT_HBM && residency != ESPN_RESIDENT_HOST_PINNED)
+    if (residency != ESPN_RESIDENT_HBM && residency != ESPN_RESIDENT_HOST_PINNED && residency != ESPN_RESIDENT_HOST)
         return fail(ESPN_ERR_ARG, "residency = %d is not a known value", residency);
     if (offsets_host[0] != 0) return fail(ESPN_ERR_OFFSETS, "offsets[0] = %lld, expected 0", (long long)offsets_host[0]);
     for (int64_t i = 0; i < n_docs; ++i)
@@ -229,7 +311,11 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
         t->emb = dev_view;
         t->emb_host = static_cast<const uint8_t *>(emb);
     }
-    if (residency == ESPN_RESIDENT_HOST_PINNED) {
+    if (residency == ESPN_RESIDENT_HOST) {       // ordinary host memory: only the host ever reads it
+        t->emb = nullptr;
+        t->emb_host = static_cast<const uint8_t *>(emb);
+    }
+    if (residency != ESPN_RESIDENT_HBM) {
         t->off_host = new (std::nothrow) int64_t[(size_t)n_docs + 1];
         if (!t->off_host) {
             delete t;
@@ -257,6 +343,12 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
         *t->share_host = -1.f;
         e = hipHostGetDevicePointer(reinterpret_cast<void **>(&t->share_dev), t->share_host, 0);
     }
+    // the streams of espn_rerank_batches (default priority, not synchronising with the null stream) and its events
+    for (int l = 0; l < ESPN_BATCH_LANES && e == hipSuccess; ++l) {
+        e = hipStreamCreateWithFlags(&t->lane[l], hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&t->joined[l], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&t->fork, hipEventDisableTiming);
     if (e == hipSuccess && doc_scale_host) {
         e = hipMalloc(reinterpret_cast<void **>(&t->scale_dev), sizeof(float) * (size_t)(n_docs + 1));
         if (e == hipSuccess && n_docs > 0)
@@ -270,6 +362,7 @@ int load_table(const void *emb, const float *doc_scale_host, const int64_t *offs
         (void)hipFree(t->err_dev);
         (void)hipFree(t->scale_dev);
         if (t->share_host) (void)hipHostFree(t->share_host);
+        destroy_lanes(t);
         delete[] t->off_host;
         delete t;
         if (e == hipSuccess) return scratch_rc;           // the message is already set
@@ -326,6 +419,7 @@ ESPN_API int espn_table_free(espn_table *table)
     (void)hipFree(table->err_dev);
     (void)hipFree(table->scale_dev);
     if (table->share_host) (void)hipHostFree(table->share_host);
+    destroy_lanes(table);
     delete[] table->off_host;
     delete table;
     return ESPN_OK;
@@ -343,7 +437,26 @@ ESPN_API int espn_table_set_fetch(espn_table *table, int32_t mode)
 ESPN_API int espn_table_sharing_estimate(const espn_table *table, float *estimate)
 {
     if (!table || !estimate) return fail(ESPN_ERR_ARG, "NULL pointer");
-    *estimate = table->share_host ? *static_cast<volatile const float *>(table->share_host) : -1.f;
+    *estimate = table->overlap;
+    return ESPN_OK;
+}
+
+ESPN_API int espn_table_sample(espn_table *table, const int64_t *cand, int32_t B, int32_t K, void *stream)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (B < 0 || K < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d: negative size", B, K);
+    if (B > 0 && K > 0 && !cand) return fail(ESPN_ERR_ARG, "cand is NULL");
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    *table->share_host = 0.f;
+    if (B > 0 && K > 0) {
+        hipLaunchKernelGGL(espn::sharing_probe_kernel, dim3(1), dim3(1024), 0, st, cand, (int64_t)B * K, K, K,
+                           table->share_dev);
+        HIP_TRY(hipGetLastError());
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    table->overlap = *static_cast<volatile const float *>(table->share_host);
     return ESPN_OK;
 }
 
@@ -389,7 +502,6 @@ constexpr int kNarrowWaves128 = 4;
 // Lists of a batch are taken to share documents if more than this fraction of a sample of 4096 pairs repeats a
 // document of the sample (uniform lists over 2 M documents: 0.002; Zipf(1.1) lists: above 0.5)
 constexpr float kShareThreshold = 0.05f;
-constexpr uint64_t kShareEvery = 64;
 
 // How a batch is cut into workgroup slices, and whether the scoring kernel ranks as well.
 struct SlicePlan {
@@ -478,10 +590,9 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     // So, unless the caller has said which it wants: non-temporal when the batch cannot repeat documents much
     // (pairs <= half the documents of the table).  That is right for lists drawn uniformly and wrong for small
     // batches of lists that share popular documents (Zipf: cached loads win from 64 queries on).
-    // ... unless a sample of an earlier batch's lists has shown how much they overlap (sharing_probe_kernel,
-    // every kShareEvery-th scoring launch, written to pinned host memory and read here without waiting)
+    // ... unless the caller has had a batch's lists sampled (espn_table_sample) and so shown how much they overlap
     bool streaming = 2 * (int64_t)B * K <= t->n_docs;
-    const float overlap = t->share_host ? *static_cast<volatile const float *>(t->share_host) : -1.f;
+    const float overlap = t->overlap;
     if (overlap >= 0.f) streaming = overlap < kShareThreshold;
     // 64-byte rows are fetched lane-linearly either way, so only the hint is at stake: non-temporal unless a
     // sample has shown overlapping lists (uniform lists, 1024 queries: 1.9 % faster; Zipf lists: 27-36 % slower)
@@ -555,58 +666,68 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     return p;
 }
 
+// Waves per workgroup a launch runs with (the kernel's WAVES argument), for QG groups of 16 query rows in registers.
+// 64 query rows of 192 or 256 bytes take 122-154 VGPRs per lane: in workgroups of 4 waves three of them share a
+// compute unit, in workgroups of 8 only one would fit.
+int launched_waves(int D, int EB, int QG, const SlicePlan &plan)
+{
+    if (D == 128 && EB == 2 && QG == 2 && plan.waves == kNarrowWaves128) return kNarrowWaves128;
+    if (D == 32 && plan.waves == kNarrowWaves) return kNarrowWaves;
+    return (QG == 4 && D > 64) ? 4 : waves_per_workgroup(D);
+}
+constexpr int kPipeline = 4;                     // register pipeline depth in 16-row tiles (the kernel's P argument)
+
 // QG = groups of 16 query rows the kernel holds in registers: 2 (Q <= 32) or 4 (Q <= 64, rows up to 256 bytes)
 template <int D, int EB, bool RANK, int QG, bool LINEAR>
-void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
-                   float *scores, const espn::RankOut &ro, hipStream_t st)
+void launch_slices(const espn::DocSource &src, const espn::Batch &bt, const espn::BatchSet &set, const SlicePlan &plan,
+                   unsigned *err, const espn::RankOut &ro, hipStream_t st)
 {
-    // 64 query rows of 192 or 256 bytes take 122-154 VGPRs per lane: in workgroups of 4 waves three of them
-    // share a compute unit, in workgroups of 8 only one would fit
     constexpr int WAVES = (QG == 4 && D > 64) ? 4 : waves_per_workgroup(D);
-    constexpr int P = 4;                     // register pipeline depth in 16-row tiles
-    const dim3 grid((unsigned)plan.slices * B);
+    constexpr int P = kPipeline;
+    const dim3 grid((unsigned)plan.slices * (unsigned)set.n * (unsigned)set.B);
+    const int waves = launched_waves(D, EB, QG, plan);
     if constexpr (D == 128 && EB == 2 && QG == 2) {
-        if (plan.waves == kNarrowWaves128) {
+        if (waves == kNarrowWaves128) {
             hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves128, P, EB, RANK, QG, LINEAR>), grid,
-                               dim3(kNarrowWaves128 * 64), 0, st, src, bt, scores, err, plan.slice, ro);
+                               dim3(kNarrowWaves128 * 64), 0, st, src, bt, set, err, plan.slice, ro);
             return;
         }
     }
     if constexpr (D == 32) {
-        if (plan.waves == kNarrowWaves) {
+        if (waves == kNarrowWaves) {
             hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, kNarrowWaves, P, EB, RANK, QG, LINEAR>), grid,
-                               dim3(kNarrowWaves * 64), 0, st, src, bt, scores, err, plan.slice, ro);
+                               dim3(kNarrowWaves * 64), 0, st, src, bt, set, err, plan.slice, ro);
             return;
         }
     }
     hipLaunchKernelGGL((espn::maxsim_slice_kernel<D, WAVES, P, EB, RANK, QG, LINEAR>), grid, dim3(WAVES * 64), 0, st,
-                       src, bt, scores, err, plan.slice, ro);
+                       src, bt, set, err, plan.slice, ro);
 }
 
 template <int D, int EB, bool RANK, int QG>
-void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
-                   float *scores, const espn::RankOut &ro, hipStream_t st)
+void launch_slices(const espn::DocSource &src, const espn::Batch &bt, const espn::BatchSet &set, const SlicePlan &plan,
+                   unsigned *err, const espn::RankOut &ro, hipStream_t st)
 {
-    if (plan.linear) launch_slices<D, EB, RANK, QG, true>(src, bt, B, plan, err, scores, ro, st);
-    else launch_slices<D, EB, RANK, QG, false>(src, bt, B, plan, err, scores, ro, st);
+    if (plan.linear) launch_slices<D, EB, RANK, QG, true>(src, bt, set, plan, err, ro, st);
+    else launch_slices<D, EB, RANK, QG, false>(src, bt, set, plan, err, ro, st);
 }
 
 // rows longer than 256 bytes are held for 32 query rows only (their fragments would not fit the registers)
 constexpr bool takes_long_queries(int D) { return D <= 128; }
 
 template <int D, int EB>
-void launch_slices(const espn::DocSource &src, const espn::Batch &bt, int B, const SlicePlan &plan, unsigned *err,
-                   float *scores, const espn::RankOut &ro, hipStream_t st)
+void launch_slices(const espn::DocSource &src, const espn::Batch &bt, const espn::BatchSet &set, const SlicePlan &plan,
+                   unsigned *err, const espn::RankOut &ro, hipStream_t st)
 {
     if constexpr (takes_long_queries(D)) {
         if (bt.Q > 32) {
-            if (plan.rank) launch_slices<D, EB, true, 4>(src, bt, B, plan, err, scores, ro, st);
-            else launch_slices<D, EB, false, 4>(src, bt, B, plan, err, scores, ro, st);
+            if (plan.rank) launch_slices<D, EB, true, 4>(src, bt, set, plan, err, ro, st);
+            else launch_slices<D, EB, false, 4>(src, bt, set, plan, err, ro, st);
             return;
         }
     }
-    if (plan.rank) launch_slices<D, EB, true, 2>(src, bt, B, plan, err, scores, ro, st);
-    else launch_slices<D, EB, false, 2>(src, bt, B, plan, err, scores, ro, st);
+    if (plan.rank) launch_slices<D, EB, true, 2>(src, bt, set, plan, err, ro, st);
+    else launch_slices<D, EB, false, 2>(src, bt, set, plan, err, ro, st);
 }
 
 // 16-row query groups in registers: up to 32 query rows for every row length that is a multiple of 32
@@ -616,43 +737,60 @@ bool on_matrix_cores(const espn_table *t, int Q)
     return t->dim % 32 == 0 && t->dim <= 256 && (Q <= 32 || (Q <= 64 && takes_long_queries(t->dim)));
 }
 
-// Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot).
-// plan.rank: the kernel also writes the ranked top-k described by `ro`.
-int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::Batch &bt, int B, float *scores,
+// One batch as the set a launch scores.
+espn::BatchSet one_batch(const espn::Batch &bt, int B, float *scores, int64_t *out_ids = nullptr, float *out_scores = nullptr)
+{
+    espn::BatchSet set{};
+    set.n = 1;
+    set.B = B;
+    set.q[0] = bt.q;
+    set.cand[0] = bt.cand;
+    set.prior[0] = bt.prior;
+    set.scores[0] = scores;
+    set.out_ids[0] = out_ids;
+    set.out_scores[0] = out_scores;
+    return set;
+}
+
+// Enqueue the scoring kernel for documents found through `src` (the table itself or a staging slot): the batches
+// of `set`, all of the shape `bt` gives, in one launch of set.n * set.B queries that `plan` was made for.
+// plan.rank: the kernel also writes the ranked top-k, rows of the shape `ro`.
+int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::Batch &bt, const espn::BatchSet &set,
                   const SlicePlan &plan, const espn::RankOut &ro, hipStream_t st)
 {
     using namespace espn;
-    if (B == 0 || bt.K == 0) return ESPN_OK;
+    if (set.n == 0 || set.B == 0 || bt.K == 0) return ESPN_OK;
     if (t->elem_bytes == 1 && bt.Q > 64)
         return fail(ESPN_ERR_UNSUPPORTED, "E4M3 tables take at most 64 query rows, got %d", bt.Q);
     if (on_matrix_cores(t, bt.Q)) {
         if (t->elem_bytes == 1) {
-            if (t->dim == 32) launch_slices<32, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);
-            else launch_slices<128, 1>(src, bt, B, plan, t->err_dev, scores, ro, st);
+            if (t->dim == 32) launch_slices<32, 1>(src, bt, set, plan, t->err_dev, ro, st);
+            else launch_slices<128, 1>(src, bt, set, plan, t->err_dev, ro, st);
         } else {
             switch (t->dim) {
-                case 32: launch_slices<32, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                case 64: launch_slices<64, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                case 96: launch_slices<96, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                case 128: launch_slices<128, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                case 160: launch_slices<160, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                case 192: launch_slices<192, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                case 224: launch_slices<224, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
-                default: launch_slices<256, 2>(src, bt, B, plan, t->err_dev, scores, ro, st); break;
+                case 32: launch_slices<32, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                case 64: launch_slices<64, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                case 96: launch_slices<96, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                case 128: launch_slices<128, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                case 160: launch_slices<160, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                case 192: launch_slices<192, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                case 224: launch_slices<224, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
+                default: launch_slices<256, 2>(src, bt, set, plan, t->err_dev, ro, st); break;
             }
         }
     } else {
         const size_t lds = (size_t)bt.Q * t->dim * 2;
         if (lds > 64 * 1024)
             return fail(ESPN_ERR_UNSUPPORTED, "Q * dim * 2 = %zu bytes exceeds the 64 KiB the generic kernel holds", lds);
-        const dim3 grid((unsigned)((bt.K + 3) / 4) * B), block(256);
-        hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim, bt, scores, t->err_dev);
+        const dim3 grid((unsigned)((bt.K + 3) / 4) * set.B), block(256);
+        for (int i = 0; i < set.n; ++i) {       // the plain kernel takes one batch per launch
+            Batch one = bt;
+            one.q = set.q[i];
+            one.cand = set.cand[i];
+            one.prior = set.prior[i];
+            hipLaunchKernelGGL(maxsim_generic_kernel, grid, block, lds, st, src, t->dim, one, set.scores[i], t->err_dev);
+        }
     }
-    // every so often, look at how much this batch's lists overlap (for the choice of the next launches)
-    if (t->fetch == ESPN_FETCH_AUTO && on_matrix_cores(t, bt.Q) && !src.row_map && t->share_dev &&
-        t->scored.fetch_add(1, std::memory_order_relaxed) % kShareEvery == 0)
-        hipLaunchKernelGGL(sharing_probe_kernel, dim3(1), dim3(1024), 0, st, bt.cand, (int64_t)B * bt.K, bt.K, bt.ldc,
-                           t->share_dev);
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }
@@ -688,31 +826,64 @@ void launch_sort(const Lists &lists, int B, int n, int k, int ldo, int64_t *out_
                            out_scores);
 }
 
+// Which stand-alone kernel ranks lists of K entries for k ranks.
+// Few ranks: one wave per query keeps the list in registers and ranks the handful of entries
+// that can reach the top k (5 us for 64 lists of 1000, k = 10; its cost grows with k and it
+// falls back to k selection rounds once more than 64 entries survive its threshold).
+// More ranks: the whole list is sorted, at a cost independent of k (11 us for the same lists).
+// Lists beyond 4096 entries: k selection rounds over the list.
+enum class RankKernel { Wave4, Wave16, Wave32, Sort256, Sort1024, Sort2048, Sort4096, Rounds };
+RankKernel rank_kernel(int K, int k)
+{
+    if (k <= 32 && K <= 64 * 4) return RankKernel::Wave4;
+    if (k <= 32 && K <= 64 * 16) return RankKernel::Wave16;
+    if (k <= 32 && K <= 64 * 32) return RankKernel::Wave32;
+    if (K <= 256) return RankKernel::Sort256;
+    if (K <= 1024) return RankKernel::Sort1024;
+    if (K <= 2048) return RankKernel::Sort2048;
+    if (K <= kSortMax) return RankKernel::Sort4096;
+    return RankKernel::Rounds;
+}
+const char *rank_kernel_name(RankKernel r)
+{
+    switch (r) {
+        case RankKernel::Wave4: return "espn::topk_wave_kernel<4>";
+        case RankKernel::Wave16: return "espn::topk_wave_kernel<16>";
+        case RankKernel::Wave32: return "espn::topk_wave_kernel<32>";
+        case RankKernel::Sort256: return "espn::topk_sort_kernel<256, 64, espn::OneList>";
+        case RankKernel::Sort1024: return "espn::topk_sort_kernel<1024, 256, espn::OneList>";
+        case RankKernel::Sort2048: return "espn::topk_sort_kernel<2048, 512, espn::OneList>";
+        case RankKernel::Sort4096: return "espn::topk_sort_kernel<4096, 512, espn::OneList>";
+        default: return "espn::topk_rounds_kernel<16>";
+    }
+}
+
 // Ranks the first k of K scored candidates per query; cand rows have leading dimension ldc, output rows ldo.
 int enqueue_topk(const float *scores, const int64_t *cand, int ldc, int B, int K, int k, int ldo, int64_t *out_ids,
                  float *out_scores, hipStream_t st)
 {
     using namespace espn;
     if (B == 0 || k == 0) return ESPN_OK;
-    // Few ranks: one wave per query keeps the list in registers and ranks the handful of entries
-    // that can reach the top k (5 us for 64 lists of 1000, k = 10; its cost grows with k and it
-    // falls back to k selection rounds once more than 64 entries survive its threshold).
-    // More ranks: the whole list is sorted, at a cost independent of k (11 us for the same lists).
-    // Lists beyond 4096 entries: k selection rounds over the list.
-    if (k <= 32 && K <= 64 * 4)
-        hipLaunchKernelGGL((topk_wave_kernel<4>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
-                           out_scores);
-    else if (k <= 32 && K <= 64 * 16)
-        hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
-                           out_scores);
-    else if (k <= 32 && K <= 64 * 32)
-        hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
-                           out_scores);
-    else if (K <= kSortMax)
-        launch_sort(OneList{scores, cand, ldc, K}, B, K, k, ldo, out_ids, out_scores, st);
-    else
-        hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
-                           out_scores);
+    switch (rank_kernel(K, k)) {
+        case RankKernel::Wave4:
+            hipLaunchKernelGGL((topk_wave_kernel<4>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                               out_scores);
+            break;
+        case RankKernel::Wave16:
+            hipLaunchKernelGGL((topk_wave_kernel<16>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                               out_scores);
+            break;
+        case RankKernel::Wave32:
+            hipLaunchKernelGGL((topk_wave_kernel<32>), dim3(B), dim3(64), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                               out_scores);
+            break;
+        case RankKernel::Rounds:
+            hipLaunchKernelGGL((topk_rounds_kernel<16>), dim3(B), dim3(256), 0, st, scores, cand, ldc, K, k, ldo, out_ids,
+                               out_scores);
+            break;
+        default:
+            launch_sort(OneList{scores, cand, ldc, K}, B, K, k, ldo, out_ids, out_scores, st);
+    }
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }
@@ -728,8 +899,9 @@ ESPN_API int espn_score(espn_table *table, const void *q, const int64_t *cand, i
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     if (table->residency != ESPN_RESIDENT_HBM)
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
-    return enqueue_score(table, hbm_source(table), plain_batch(q, cand, Q, K), B, scores,
-                         plan_slices(table, B, K, 0), espn::RankOut{}, static_cast<hipStream_t>(stream));
+    const espn::Batch bt = plain_batch(q, cand, Q, K);
+    return enqueue_score(table, hbm_source(table), bt, one_batch(bt, B, scores), plan_slices(table, B, K, 0),
+                         espn::RankOut{}, static_cast<hipStream_t>(stream));
 }
 
 ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int32_t K, int32_t k, int64_t *out_ids,
@@ -779,8 +951,8 @@ int enqueue_rerank(espn_table *t, const espn::DocSource &src, const espn::Batch 
     SlicePlan plan = plan_slices(t, B, bt.K, k);
     if (!on_matrix_cores(t, bt.Q)) plan.rank = false;
     if (src.row_map) plan.linear = false;    // a staging slot holds each document once for all the queries that list it
-    const espn::RankOut ro{k, ldo, out_ids, out_scores};
-    if (int rc = enqueue_score(t, src, bt, B, scores, plan, ro, st)) return rc;
+    const espn::RankOut ro{k, ldo};
+    if (int rc = enqueue_score(t, src, bt, one_batch(bt, B, scores, out_ids, out_scores), plan, ro, st)) return rc;
     if (plan.rank) return ESPN_OK;
     return enqueue_topk(scores, bt.cand, bt.ldc, B, bt.K, k, ldo, out_ids, out_scores, st);
 }
@@ -810,6 +982,36 @@ ESPN_API int espn_rerank_plan(const espn_table *table, int32_t B, int32_t Q, int
     return ESPN_OK;
 }
 
+ESPN_API int espn_rerank_plan_kernels(const espn_table *table, int32_t B, int32_t Q, int32_t K, int32_t k, char *buf,
+                                      size_t buf_len)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (!buf || buf_len == 0) return fail(ESPN_ERR_ARG, "buf is NULL or empty");
+    if (B < 0 || K < 0 || k < 0 || Q < 1) return fail(ESPN_ERR_ARG, "B = %d, Q = %d, K = %d, k = %d", B, Q, K, k);
+    if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
+    buf[0] = 0;
+    if (B == 0 || K == 0) return ESPN_OK;
+    char text[256];
+    bool ranked = false;
+    if (on_matrix_cores(table, Q)) {
+        const SlicePlan plan = plan_slices(table, B, K, k);
+        const int QG = Q > 32 ? 4 : 2;
+        ranked = plan.rank;
+        snprintf(text, sizeof(text), "espn::maxsim_slice_kernel<%d, %d, %d, %d, %s, %d, %s>", table->dim,
+                 launched_waves(table->dim, table->elem_bytes, QG, plan), kPipeline, table->elem_bytes,
+                 plan.rank ? "true" : "false", QG, plan.linear ? "true" : "false");
+    } else {
+        snprintf(text, sizeof(text), "espn::maxsim_generic_kernel");
+    }
+    if (k > 0 && !ranked) {
+        const size_t at = std::strlen(text);
+        snprintf(text + at, sizeof(text) - at, ";%s", rank_kernel_name(rank_kernel(K, k)));
+    }
+    if (std::strlen(text) + 1 > buf_len) return fail(ESPN_ERR_SHAPE, "buf holds %zu bytes, %zu needed", buf_len, std::strlen(text) + 1);
+    std::memcpy(buf, text, std::strlen(text) + 1);
+    return ESPN_OK;
+}
+
 ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
                          int32_t k, int64_t *out_ids, float *out_scores, void *workspace, size_t workspace_bytes,
                          void *stream)
@@ -823,6 +1025,139 @@ ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace,
                           st);
+}
+
+namespace {
+// How espn_rerank_batches runs a queue of n batches of B queries.  Batches whose scoring launch would be short (few
+// workgroups: 64 queries x 8 slices = 512, a 30 us launch of which the launch gap and the dependent look-ups
+// at its start are a sixth) are scored `fuse` at a time by ONE launch and ranked by one more, which streams
+// like one batch of fuse * B queries; the chunks of `fuse` batches are dealt to the lanes in turn, so that one
+// chunk's ranking and the start of the next chunk's scoring overlap with the streaming of the chunk before.
+// Batches that fill the device many times over on their own (fuse = 1) are dealt to the lanes one by one.
+constexpr int64_t kFusedWorkgroups = 8192;      // aim of a fused launch: 16 batches of 512 workgroups
+struct QueuePlan {
+    int fuse = 1;           // batches per launch at most
+    int chunks = 0;         // launches of the scoring kernel
+    int lanes = 0;          // streams used (1: the caller's own)
+};
+QueuePlan plan_queue(const espn_table *t, int n_batches, int B, int Q, int K, int k)
+{
+    QueuePlan qp;
+    if (n_batches <= 0) return qp;
+    if (B > 0 && K > 0 && on_matrix_cores(t, Q)) {
+        const SlicePlan one = plan_slices(t, B, K, k);
+        const bool rank_fuses = k == 0 || one.rank || rank_kernel(K, k) <= RankKernel::Wave32;
+        const int64_t per_batch = (int64_t)B * one.slices;
+        if (rank_fuses && (int64_t)B * espn::MAX_FUSED * std::max(K, 1) <= (int64_t)0x7fffffff)
+            qp.fuse = (int)std::max<int64_t>(1, std::min<int64_t>(espn::MAX_FUSED, kFusedWorkgroups / per_batch));
+    }
+    qp.chunks = (n_batches + qp.fuse - 1) / qp.fuse;
+    qp.lanes = std::min(qp.chunks, (int)ESPN_BATCH_LANES);
+    return qp;
+}
+}  // namespace
+
+ESPN_API size_t espn_batches_workspace_bytes(const espn_table *table, int32_t n_batches, int32_t B, int32_t Q,
+                                             int32_t K, int32_t k)
+{
+    if (!table || n_batches <= 0 || Q < 1) return espn_workspace_bytes(B, K);
+    const QueuePlan qp = plan_queue(table, n_batches, B, Q, K, std::max(k, 0));
+    return (size_t)qp.lanes * (size_t)std::min(qp.fuse, n_batches) * espn_workspace_bytes(B, K);
+}
+
+ESPN_API int espn_rerank_batches(espn_table *table, int32_t n_batches, const void *const *q, const int64_t *const *cand,
+                                 int32_t B, int32_t Q, int32_t K, int32_t k, int64_t *const *out_ids,
+                                 float *const *out_scores, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (n_batches < 0) return fail(ESPN_ERR_ARG, "n_batches = %d is negative", n_batches);
+    if (n_batches == 0) return ESPN_OK;
+    if (!q || !cand) return fail(ESPN_ERR_ARG, "q or cand (the pointer lists) is NULL");
+    const bool ranked = k > 0 && B > 0;
+    if (ranked && (!out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "out_ids or out_scores (the pointer lists) is NULL");
+    if (Q < 1) return fail(ESPN_ERR_ARG, "Q = %d: a query needs at least one row", Q);
+    const size_t per_batch = espn_workspace_bytes(B, K);
+    const size_t needed = espn_batches_workspace_bytes(table, n_batches, B, Q, K, k);
+    if (B > 0 && K > 0 && workspace_bytes < needed)
+        return fail(ESPN_ERR_SHAPE, "workspace holds %zu bytes, %zu needed (espn_batches_workspace_bytes)", workspace_bytes, needed);
+    // everything is checked before anything is enqueued
+    for (int i = 0; i < n_batches; ++i) {
+        if (int rc = check_batch(table, q[i], cand[i], B, Q, K)) return rc;
+        if (int rc = check_rerank_outputs(B, K, k, ranked ? out_ids[i] : nullptr, ranked ? out_scores[i] : nullptr, workspace, per_batch))
+            return rc;
+    }
+    DeviceScope scope(table->device);
+    if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
+    if (table->residency != ESPN_RESIDENT_HBM)
+        return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
+    if (B == 0 || K == 0) return ESPN_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const espn::DocSource src = hbm_source(table);
+    const QueuePlan qp = plan_queue(table, n_batches, B, Q, K, k);
+    const size_t per_lane = (size_t)std::min(qp.fuse, n_batches) * per_batch;
+
+    // chunk c: batches [first, first + count), scored by one launch into the lane's part of the workspace, then ranked
+    auto run_chunk = [&](int first, int count, uint8_t *ws, hipStream_t on) -> int {
+        if (count == 1)
+            return enqueue_rerank(table, src, plain_batch(q[first], cand[first], Q, K), B, k, k, ranked ? out_ids[first] : nullptr,
+                                  ranked ? out_scores[first] : nullptr, ws, on);
+        const espn::Batch shape = plain_batch(nullptr, nullptr, Q, K);
+        espn::BatchSet set{};
+        espn::TopkSet lists{};
+        set.n = lists.n = count;
+        set.B = lists.B = B;
+        for (int x = 0; x < count; ++x) {
+            set.q[x] = static_cast<const uint16_t *>(q[first + x]);
+            set.cand[x] = lists.cand[x] = cand[first + x];
+            set.scores[x] = reinterpret_cast<float *>(ws + (size_t)x * per_batch);
+            lists.scores[x] = set.scores[x];
+            set.out_ids[x] = lists.out_ids[x] = ranked ? out_ids[first + x] : nullptr;
+            set.out_scores[x] = lists.out_scores[x] = ranked ? out_scores[first + x] : nullptr;
+        }
+        // the launch is planned as what it is: one batch of count * B queries
+        const SlicePlan plan = plan_slices(table, count * B, K, k);
+        if (int rc = enqueue_score(table, src, shape, set, plan, espn::RankOut{k, k}, on)) return rc;
+        if (k == 0 || plan.rank) return ESPN_OK;
+        const dim3 grid((unsigned)count * B);
+        switch (rank_kernel(K, k)) {
+            case RankKernel::Wave4: hipLaunchKernelGGL((espn::topk_wave_set_kernel<4>), grid, dim3(64), 0, on, lists, K, K, k, k); break;
+            case RankKernel::Wave16: hipLaunchKernelGGL((espn::topk_wave_set_kernel<16>), grid, dim3(64), 0, on, lists, K, K, k, k); break;
+            default: hipLaunchKernelGGL((espn::topk_wave_set_kernel<32>), grid, dim3(64), 0, on, lists, K, K, k, k); break;
+        }
+        HIP_TRY(hipGetLastError());
+        return ESPN_OK;
+    };
+    // chunks of equal size (to within one batch)
+    auto chunk_first = [&](int c) { return (int)((int64_t)n_batches * c / qp.chunks); };
+
+    if (qp.lanes == 1)      // one launch (or one batch): the caller's stream itself
+        return run_chunk(0, n_batches, static_cast<uint8_t *>(workspace), st);
+    // The lanes are streams of the library's own, created together, so that each has a hardware queue to itself
+    // (a process has few of those, and the caller's stream may share one with a lane: taking it as one of the lanes
+    // was measured at 32 us per batch instead of 27).  They start where the caller's stream is now - nothing to
+    // wait for if it is idle, which one query tells (an event record and a wait per lane cost about 5 us each on the
+    // host, at the start of the call, with the device idle) - and the caller's stream goes on when they are through
+    // (those records and waits are enqueued behind the call's own work).
+    const hipError_t idle = hipStreamQuery(st);
+    if (idle != hipSuccess) {
+        (void)hipGetLastError();                     // hipErrorNotReady is the expected answer, not an error
+        HIP_TRY(hipEventRecord(table->fork, st));
+        for (int l = 0; l < qp.lanes; ++l) HIP_TRY(hipStreamWaitEvent(table->lane[l], table->fork, 0));
+    }
+    int status = ESPN_OK;
+    for (int c = 0; c < qp.chunks && status == ESPN_OK; ++c) {
+        const int l = c % qp.lanes;
+        status = run_chunk(chunk_first(c), chunk_first(c + 1) - chunk_first(c),
+                           static_cast<uint8_t *>(workspace) + (size_t)l * per_lane, table->lane[l]);
+    }
+    // joined even after a failure, so that the caller's stream never runs ahead of work already enqueued
+    for (int l = 0; l < qp.lanes; ++l) {
+        const hipError_t e1 = hipEventRecord(table->joined[l], table->lane[l]);
+        const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(st, table->joined[l], 0) : e1;
+        if (e2 != hipSuccess && status == ESPN_OK)
+            status = fail(ESPN_ERR_HIP, "joining lane %d failed: %s", l, hipGetErrorString(e2));
+    }
+    return status;
 }
 
 ESPN_API int espn_rerank_noalloc(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q,
@@ -910,24 +1245,6 @@ ESPN_API double espn_batch_threshold(double bandwidth_bytes_per_s, double budget
 {
     if (!(bytes_per_query > 0.0)) return 0.0;
     return bandwidth_bytes_per_s * budget_s / bytes_per_query;
-}
-
-ESPN_API int espn_stream_read_probe(const void *src, size_t bytes, uint64_t *sink, void *stream)
-{
-    if (bytes == 0) return ESPN_OK;
-    if (!src || !sink) return fail(ESPN_ERR_ARG, "NULL pointer");
-    if (!aligned16(src) || bytes % 16 != 0) return fail(ESPN_ERR_ARG, "src and bytes must be multiples of 16");
-    int dev = 0, n_cu = 256;
-    HIP_TRY(hipGetDevice(&dev));
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
-    const size_t n = bytes / 16;
-    // eight workgroups per compute unit, each at least one full round of its 256 lanes' 8 loads
-    const size_t blocks = std::max<size_t>(1, std::min<size_t>((size_t)n_cu * 8, n / (8 * 256)));
-    const size_t per = (n + blocks - 1) / blocks;
-    hipLaunchKernelGGL(espn::stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const espn::uint4v *>(src), n, per, reinterpret_cast<unsigned long long *>(sink));
-    HIP_TRY(hipGetLastError());
-    return ESPN_OK;
 }
 
 ESPN_API int espn_table_check(espn_table *table, void *stream)
@@ -1018,6 +1335,8 @@ ESPN_API int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, in
     if (int rc = check_slot(table, slot)) return rc;
     if (B < 0 || K < 0) return fail(ESPN_ERR_ARG, "B = %d, K = %d: negative size", B, K);
     if (B > 0 && K > 0 && !cand) return fail(ESPN_ERR_ARG, "cand is NULL");
+    if (table->residency == ESPN_RESIDENT_HOST)
+        return fail(ESPN_ERR_UNSUPPORTED, "the table is in host memory the device cannot read (not pinned): use espn_prefetch_packed");
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     hipStream_t st = static_cast<hipStream_t>(side_stream);
@@ -1090,41 +1409,101 @@ int make_pack_state(espn_table *t)
     }
     try {
         p->seen.assign(((size_t)t->n_docs + 63) / 64, 0);
-    } catch (const std::bad_alloc &) {
+        p->pool.start(kPackThreads - 1);
+    } catch (...) {                     // bad_alloc, or no more threads to be had
         free_pack_state(t);
-        return fail(ESPN_ERR_NOMEM, "host allocation failed");
+        return fail(ESPN_ERR_NOMEM, "host allocation or thread creation failed");
     }
     return ESPN_OK;
 }
 
-// Copies documents uniq[first .. last) of the table into `dst` back to back, on several threads.
-void pack_documents(const espn_table *t, const int64_t *uniq, int64_t first, int64_t last, uint8_t *dst)
+// `bytes` from src to dst with stores that do not first read the destination's cache lines (the pack buffer is
+// written once and then read by the copy engine, never by this core again).  dst 32-byte aligned, bytes a
+// multiple of 32; anything else goes through memcpy.
+__attribute__((target("avx2"))) void copy_streaming_avx2(uint8_t *dst, const uint8_t *src, size_t bytes)
+{
+    typedef long long v4di __attribute__((vector_size(32), aligned(32)));
+    typedef long long v4di_u __attribute__((vector_size(32), aligned(1)));
+    for (size_t x = 0; x < bytes; x += 32)
+        __builtin_nontemporal_store(*reinterpret_cast<const v4di_u *>(src + x), reinterpret_cast<v4di *>(dst + x));
+}
+
+void copy_document(uint8_t *dst, const uint8_t *src, size_t bytes, bool avx2)
+{
+    if (avx2 && (reinterpret_cast<uintptr_t>(dst) & 31u) == 0 && bytes % 32 == 0) copy_streaming_avx2(dst, src, bytes);
+    else std::memcpy(dst, src, bytes);
+}
+
+// Copies documents uniq[first .. last) of the table into `dst` back to back, on the pool's threads.  Nothing
+// in here allocates or throws.
+void pack_documents(const espn_table *t, PackPool &pool, const int64_t *uniq, int64_t first, int64_t last, uint8_t *dst)
 {
     const size_t row_bytes = (size_t)t->dim * t->elem_bytes;
     const int64_t n = last - first;
-    const int n_threads = (int)std::min<int64_t>(kPackThreads, std::max<int64_t>(1, n / 64));
-    // thread x takes documents [cut[x], cut[x + 1]); where its part starts in dst follows from the lengths
-    std::vector<int64_t> cut(n_threads + 1);
-    std::vector<size_t> at(n_threads + 1, 0);
-    for (int x = 0; x <= n_threads; ++x) cut[x] = first + n * x / n_threads;
-    for (int x = 0; x < n_threads; ++x) {
-        size_t bytes = 0;
-        for (int64_t u = cut[x]; u < cut[x + 1]; ++u) bytes += (size_t)(t->off_host[uniq[u] + 1] - t->off_host[uniq[u]]);
-        at[x + 1] = at[x] + bytes * row_bytes;
+    const int parts = (int)std::min<int64_t>(std::min(pool.parts(), kPackThreads), std::max<int64_t>(1, n / 64));
+    // part x takes documents [cut[x], cut[x + 1]); where its bytes start in dst follows from the lengths
+    int64_t cut[kPackThreads + 1];
+    size_t at[kPackThreads + 1];
+    at[0] = 0;
+    for (int x = 0; x <= parts; ++x) cut[x] = first + n * x / parts;
+    for (int x = 0; x < parts; ++x) {
+        size_t rows = 0;
+        for (int64_t u = cut[x]; u < cut[x + 1]; ++u) rows += (size_t)(t->off_host[uniq[u] + 1] - t->off_host[uniq[u]]);
+        at[x + 1] = at[x] + rows * row_bytes;
     }
-    auto work = [&](int x) {
+    static const bool avx2 = __builtin_cpu_supports("avx2");
+    pool.run(parts, [&](int x) {
         uint8_t *out = dst + at[x];
         for (int64_t u = cut[x]; u < cut[x + 1]; ++u) {
             const int64_t id = uniq[u];
             const size_t bytes = (size_t)(t->off_host[id + 1] - t->off_host[id]) * row_bytes;
-            std::memcpy(out, t->emb_host + (size_t)t->off_host[id] * row_bytes, bytes);
+            if (u + 1 < cut[x + 1])          // the next document's first lines, while this one is copied
+                __builtin_prefetch(t->emb_host + (size_t)t->off_host[uniq[u + 1]] * row_bytes);
+            copy_document(out, t->emb_host + (size_t)t->off_host[id] * row_bytes, bytes, avx2);
             out += bytes;
         }
-    };
-    std::vector<std::thread> pool;
-    for (int x = 1; x < n_threads; ++x) pool.emplace_back(work, x);
-    work(0);
-    for (std::thread &th : pool) th.join();
+        __atomic_thread_fence(__ATOMIC_SEQ_CST);     // the streaming stores are out before the buffer is handed on
+    });
+}
+
+// Everything espn_prefetch_packed enqueues once the batch has been found valid.  The slot's bitmap and row map
+// are written LAST, after the row copies: if anything fails on the way the slot advertises no document.
+int enqueue_packed(espn_table *table, PackState &p, StagingSlot &s, int64_t n_uniq, int64_t rows, hipStream_t st)
+{
+    const int64_t *off = table->off_host;
+    const size_t row_bytes = (size_t)table->dim * table->elem_bytes;
+    if (n_uniq == 0) return ESPN_OK;
+    HIP_TRY(hipMemcpyAsync(s.uniq, p.uniq, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(s.other_row, p.row0, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(p.lists_sent, st));
+    p.lists_in_flight = true;
+    // rows: whole documents are packed into a pinned buffer while the previous buffer is on its way
+    int64_t u = 0;
+    int which = 0;
+    while (u < n_uniq) {
+        int64_t last = u;
+        size_t bytes = 0;
+        while (last < n_uniq) {
+            const size_t len = (size_t)(off[p.uniq[last] + 1] - off[p.uniq[last]]) * row_bytes;
+            if (bytes + len > kPackBytes) break;
+            bytes += len;
+            ++last;
+        }
+        if (p.in_flight[which]) HIP_TRY(hipEventSynchronize(p.sent[which]));      // the buffer is free again
+        pack_documents(table, p.pool, p.uniq, u, last, static_cast<uint8_t *>(p.buf[which]));
+        if (bytes > 0) {
+            HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(s.rows) + (size_t)p.row0[u] * row_bytes, p.buf[which], bytes,
+                                   hipMemcpyHostToDevice, st));
+            HIP_TRY(hipEventRecord(p.sent[which], st));
+            p.in_flight[which] = true;
+        }
+        u = last;
+        which ^= 1;
+    }
+    hipLaunchKernelGGL(espn::staging_publish_kernel, dim3((unsigned)((n_uniq + 255) / 256)), dim3(256), 0, st, s.uniq,
+                       s.other_row, n_uniq, (unsigned long long)rows, s.bits, s.row_map, s.counters);
+    HIP_TRY(hipGetLastError());
+    return ESPN_OK;
 }
 }  // namespace
 
@@ -1191,42 +1570,15 @@ ESPN_API int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, i
         if (i != slot) HIP_TRY(hipStreamWaitEvent(st, table->slot[i].ready, 0));
     s.filled_at = ++table->prefetches;
     const int64_t n_words = (table->n_docs + 31) / 32 + 1;
-    hipLaunchKernelGGL(espn::staging_clear_kernel, dim3((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024)),
-                       dim3(256), 0, st, s.bits, n_words, s.counters);
-    if (n_uniq > 0) {
-        HIP_TRY(hipMemcpyAsync(s.uniq, p.uniq, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
-        HIP_TRY(hipMemcpyAsync(s.other_row, p.row0, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
-        HIP_TRY(hipEventRecord(p.lists_sent, st));
-        p.lists_in_flight = true;
-        hipLaunchKernelGGL(espn::staging_publish_kernel, dim3((unsigned)((n_uniq + 255) / 256)), dim3(256), 0, st,
-                           s.uniq, s.other_row, n_uniq, (unsigned long long)rows, s.bits, s.row_map, s.counters);
-        HIP_TRY(hipGetLastError());
-    }
-    // rows: whole documents are packed into a pinned buffer while the previous buffer is on its way
-    int64_t u = 0;
-    int which = 0;
-    while (u < n_uniq) {
-        int64_t last = u;
-        size_t bytes = 0;
-        while (last < n_uniq) {
-            const size_t len = (size_t)(off[p.uniq[last] + 1] - off[p.uniq[last]]) * row_bytes;
-            if (bytes + len > kPackBytes) break;
-            bytes += len;
-            ++last;
-        }
-        if (p.in_flight[which]) HIP_TRY(hipEventSynchronize(p.sent[which]));      // the buffer is free again
-        pack_documents(table, p.uniq, u, last, static_cast<uint8_t *>(p.buf[which]));
-        if (bytes > 0) {
-            HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(s.rows) + (size_t)p.row0[u] * row_bytes, p.buf[which], bytes,
-                                   hipMemcpyHostToDevice, st));
-            HIP_TRY(hipEventRecord(p.sent[which], st));
-            p.in_flight[which] = true;
-        }
-        u = last;
-        which ^= 1;
-    }
-    HIP_TRY(hipEventRecord(s.ready, st));
-    return ESPN_OK;
+    const dim3 clear_grid((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024));
+    hipLaunchKernelGGL(espn::staging_clear_kernel, clear_grid, dim3(256), 0, st, s.bits, n_words, s.counters);
+    HIP_TRY(hipGetLastError());
+    status = enqueue_packed(table, p, s, n_uniq, rows, st);
+    // (the clear kernel has run by then and the publish kernel has not been enqueued: the slot holds nothing,
+    // and a staged re-rank of this batch reports ESPN_ERR_SHAPE through espn_table_check)
+    const hipError_t e = hipEventRecord(s.ready, st);
+    if (status == ESPN_OK && e != hipSuccess) status = fail(ESPN_ERR_HIP, "hipEventRecord failed: %s", hipGetErrorString(e));
+    return status;
 }
 
 ESPN_API int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, const int64_t *cand, int32_t B,

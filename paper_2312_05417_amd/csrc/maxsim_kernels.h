@@ -58,6 +58,20 @@ __device__ __forceinline__ float with_prior(const Batch &bt, int b, int j, float
     return bt.prior ? fmaf(bt.alpha, bt.prior[(size_t)b * bt.ldc + j], maxsim) : maxsim;
 }
 
+// The batches one launch of the matrix-core kernel scores: n batches of B queries each, all of the shape
+// that `Batch` describes (its own pointers are not used then).  Query g of the launch is query g % B of batch
+// g / B.  A queue of small batches scored by one launch streams like one large batch: no launch gaps, and
+// the look-ups of one batch's documents overlap with the row streaming of the batches before it.
+struct BatchSet {
+    int n, B;
+    const uint16_t *q[MAX_FUSED];       // each [B, Q, D]
+    const int64_t *cand[MAX_FUSED];     // each [B, ldc]
+    const float *prior[MAX_FUSED];      // each [B, ldc] or nullptr
+    float *scores[MAX_FUSED];           // each [B, K], written
+    int64_t *out_ids[MAX_FUSED];        // RANK: each [B, ldo], written
+    float *out_scores[MAX_FUSED];
+};
+
 // (first row, row count) of document `id`; count 0 and an error flag (if err is given) if it cannot
 // be read.
 __device__ __forceinline__ void locate_document(const DocSource &src, int64_t id, unsigned *err,
@@ -277,12 +291,10 @@ __device__ __forceinline__ half8 fragment_of(const unsigned *w)
     }
 }
 
-// Where a ranking kernel leaves its result (k = 0: no ranking).
+// Shape of what a ranking kernel leaves (k = 0: no ranking); the rows themselves are BatchSet's out_ids / out_scores.
 struct RankOut {
     int k;                  // entries per query
     int ldo;                // leading dimension of the output rows (>= k)
-    int64_t *out_ids;       // [B, ldo]
-    float *out_scores;      // [B, ldo]
 };
 
 // LDS a workgroup keeps for ranking its slice (nothing when it only scores)
@@ -298,8 +310,7 @@ struct RankLds<false> {};
 // grid = B * slices workgroups of WAVES * 64 threads: a workgroup takes one slice of one query's list
 template <int D, int WAVES, int P, int EB, bool RANK, int QG = 2, bool LINEAR = false>
 __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
-    const DocSource src, const Batch bt, float *__restrict__ scores, unsigned *__restrict__ err, int slice,
-    const RankOut ro)
+    const DocSource src, const Batch bt, const BatchSet set, unsigned *__restrict__ err, int slice, const RankOut ro)
 {
     static_assert(D % 32 == 0 && D >= 32 && D <= 256 && (EB == 2 || D == 32 || D == 128) && WAVES >= 1 && WAVES <= 16 &&
                       P >= 1 && (QG == 2 || (QG == 4 && D <= 128)), "unsupported shape");
@@ -315,7 +326,6 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     __shared__ uint4 s_tile[LINEAR && D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : (D == 32 && EB == 1) ? WAVES * 64 : 1];
 
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
-    const uint16_t *__restrict__ q = bt.q;
     const int Q = bt.Q, K = bt.K;
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     constexpr int TR = TileBuf<D, EB>::ROWS;   // rows per load tile
@@ -328,12 +338,22 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     // run on one XCD and share its copy of the query matrix.
     const unsigned slices = (unsigned)((K + slice - 1) / slice);
     const unsigned n_queries = gridDim.x / slices;
-    int b = (int)(blockIdx.x / slices), slice_index = (int)(blockIdx.x % slices);
+    int g = (int)(blockIdx.x / slices), slice_index = (int)(blockIdx.x % slices);      // g: query of the launch
     if ((n_queries & 7u) == 0u) {
         const unsigned within = blockIdx.x >> 3;                // position among the XCD's workgroups
-        b = (int)((blockIdx.x & 7u) + 8u * (within / slices));
+        g = (int)((blockIdx.x & 7u) + 8u * (within / slices));
         slice_index = (int)(within % slices);
     }
+    // which batch of the launch the query belongs to (wave-uniform: the pointers stay in scalar registers)
+    const int which = set.n > 1 ? g / set.B : 0;
+    const int b = g - which * set.B;
+    const uint16_t *__restrict__ q = set.q[which];
+    const int64_t *__restrict__ cand = set.cand[which];
+    const float *__restrict__ prior = set.prior[which];
+    float *__restrict__ scores = set.scores[which];
+    auto total_of = [&](int j, float maxsim) {                  // Sec. 3.1: MaxSim + alpha * first-stage score
+        return prior ? fmaf(bt.alpha, prior[(size_t)b * bt.ldc + j], maxsim) : maxsim;
+    };
     const int j_begin = slice_index * slice;
     const int n = min(slice, K - j_begin);  // >= 1 by construction of the grid
 
@@ -344,8 +364,8 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));     // in a scalar register
     const size_t cand0 = (size_t)b * bt.ldc + j_begin;
     int64_t id_own = -1, id_fill = -1;
-    if (wave < n) id_own = bt.cand[cand0 + wave];
-    if ((int)threadIdx.x < n) id_fill = bt.cand[cand0 + threadIdx.x];
+    if (wave < n) id_own = cand[cand0 + wave];
+    if ((int)threadIdx.x < n) id_fill = cand[cand0 + threadIdx.x];
     DocCursor ld, cs;
     ld.done = true;
     ld.idx = wave;
@@ -366,7 +386,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 
     // descriptors of the slice's documents; a document with nothing to read has its score here
     for (int i = threadIdx.x; i < n; i += WAVES * 64) {
-        const int64_t id = i == (int)threadIdx.x ? id_fill : bt.cand[cand0 + i];
+        const int64_t id = i == (int)threadIdx.x ? id_fill : cand[cand0 + i];
         int64_t row0;
         int ntok;
         locate_document(src, id, err, row0, ntok);
@@ -375,7 +395,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         if constexpr (EB == 1) s_scale[i] = ntok > 0 ? src.doc_scale[id] : 1.f;
         if constexpr (RANK) s_rank.id[i] = id;
         if (ntok == 0) {
-            const float none = with_prior(bt, b, j_begin + i, neg_inf());
+            const float none = total_of(j_begin + i, neg_inf());
             scores[(size_t)b * K + j_begin + i] = none;
             if constexpr (RANK) s_rank.key[i] = order_key(none);
         }
@@ -558,7 +578,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                         // one positive scale per document: max and sum commute with it
                         if constexpr (EB == 1) sum *= s_scale[cs.idx];
                         if (lane == 0) {
-                            const float total = with_prior(bt, b, j_begin + cs.idx, sum);
+                            const float total = total_of(j_begin + cs.idx, sum);
                             scores[(size_t)b * K + j_begin + cs.idx] = total;
                             if constexpr (RANK) s_rank.key[cs.idx] = order_key(total);
                         }
@@ -597,8 +617,8 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         }
         if (mine != 0u && (ahead | same) != 0) atomicAdd(&s_rank.count[e], (unsigned)ahead | ((unsigned)same << 16));
         __syncthreads();
-        int64_t *oi = ro.out_ids + (size_t)b * ro.ldo;
-        float *os = ro.out_scores + (size_t)b * ro.ldo;
+        int64_t *oi = set.out_ids[which] + (size_t)b * ro.ldo;
+        float *os = set.out_scores[which] + (size_t)b * ro.ldo;
         if (part == 0 && mine != 0u) {
             const unsigned found = s_rank.count[e];
             int rank = (int)(found & 0xffffu);

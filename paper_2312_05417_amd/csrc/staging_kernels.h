@@ -210,26 +210,4 @@ __global__ __launch_bounds__(1024) void sharing_probe_kernel(const int64_t *__re
     if (threadIdx.x == 0) *out = n ? (float)s_repeats / (float)n : 0.f;
 }
 
-// Plain contiguous read of n 16-byte chunks: workgroup x walks chunks [x * per, (x + 1) * per), 8 loads
-// in flight per lane, non-temporal (measured against ordinary loads and against a grid-strided walk,
-// this is the fastest plain read on this machine: 6.3 TB/s on 165 MB windows, 6.5 TB/s on 4.5 GB; ordinary
-// loads 5.8 and 6.0).  What is read only feeds an xor that is almost never stored.
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4v *__restrict__ src, size_t n, size_t per,
-                                                          unsigned long long *__restrict__ sink)
-{
-    const size_t begin = (size_t)blockIdx.x * per;
-    const size_t end = begin + per < n ? begin + per : n;
-    uint4v acc = {0u, 0u, 0u, 0u};
-    size_t i = begin + threadIdx.x;
-    for (; i + 7 * 256 < end; i += 8 * 256) {
-        uint4v v[8];
-#pragma unroll
-        for (int y = 0; y < 8; ++y) v[y] = __builtin_nontemporal_load(src + i + 256 * y);
-#pragma unroll
-        for (int y = 0; y < 8; ++y) acc ^= v[y];
-    }
-    for (; i < end; i += 256) acc ^= __builtin_nontemporal_load(src + i);
-    if ((acc.x & acc.y & acc.z & acc.w) == 0xffffffffu) *sink = ((unsigned long long)acc.x << 32) | acc.y;
-}
-
 }  // namespace espn

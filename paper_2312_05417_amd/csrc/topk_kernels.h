@@ -7,6 +7,9 @@
 
 namespace espn {
 
+// Batches of one shape that a single launch may take together (the pointers travel as kernel arguments).
+constexpr int MAX_FUSED = 16;
+
 // NaN test on the bit pattern (device code is built with -fno-honor-nans, which lets the compiler
 // fold x != x to false)
 __device__ __forceinline__ bool is_nan_bits(float x)
@@ -316,6 +319,25 @@ __global__ __launch_bounds__(64) void topk_wave_kernel(
     const int b = blockIdx.x;
     topk_wave_body<PER>(scores + (size_t)b * K, cand + (size_t)b * ldc, K, k, out_ids + (size_t)b * ldo,
                         out_scores + (size_t)b * ldo, (int)threadIdx.x, lds);
+}
+
+// The same for the queries of up to MAX_FUSED batches of one shape in one launch: workgroup x ranks query
+// x % B of batch x / B (a queue of small batches then costs one ranking launch, not one per batch).
+struct TopkSet {
+    int n, B;
+    const float *scores[MAX_FUSED];     // each [B, K]
+    const int64_t *cand[MAX_FUSED];     // each [B, ldc]
+    int64_t *out_ids[MAX_FUSED];        // each [B, ldo]
+    float *out_scores[MAX_FUSED];
+};
+
+template <int PER>
+__global__ __launch_bounds__(64) void topk_wave_set_kernel(const TopkSet set, int ldc, int K, int k, int ldo)
+{
+    __shared__ TopkWaveLds<PER> lds;
+    const int which = (int)blockIdx.x / set.B, b = (int)blockIdx.x - which * set.B;
+    topk_wave_body<PER>(set.scores[which] + (size_t)b * K, set.cand[which] + (size_t)b * ldc, K, k,
+                        set.out_ids[which] + (size_t)b * ldo, set.out_scores[which] + (size_t)b * ldo, (int)threadIdx.x, lds);
 }
 
 // ---------------------------------------------------------------------------------------------

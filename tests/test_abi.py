@@ -71,7 +71,8 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 def test_status_strings(lib):
     from paper_2312_05417_amd import binding
     assert binding.status_string(0) == "ok"
-    assert len({binding.status_string(i) for i in range(9)}) == 9
+    assert len({binding.status_string(i) for i in range(8)}) == 8
+    assert binding.status_string(8) == "unknown status"
 
 
 def test_host_side_argument_errors_need_no_gpu(lib):
@@ -96,6 +97,9 @@ def test_host_side_argument_errors_need_no_gpu(lib):
     assert lib.espn_topk(None, None, -1, 4, 2, None, None, None) == bd.ESPN_ERR_ARG
     assert lib.espn_score(None, None, None, 1, 32, 4, None, None) == bd.ESPN_ERR_ARG
     assert lib.espn_rerank(None, None, None, 1, 32, 4, 2, None, None, None, 0, None) == bd.ESPN_ERR_ARG
+    assert lib.espn_rerank_noalloc(None, None, None, 1, 32, 4, 2, None, None, None) == bd.ESPN_ERR_ARG
+    assert lib.espn_rerank_batches(None, 2, None, None, 1, 32, 4, 2, None, None, None, 0, None) == bd.ESPN_ERR_ARG
+    assert lib.espn_table_sample(None, None, 1, 4, None) == bd.ESPN_ERR_ARG
     assert lib.espn_table_check(None, None) == bd.ESPN_ERR_ARG
     assert lib.espn_table_free(None) == bd.ESPN_OK
 
@@ -105,6 +109,21 @@ def test_workspace_bytes(lib):
     assert lib.espn_workspace_bytes(1, 1) == 256
     assert lib.espn_workspace_bytes(0, 1000) == 256
     assert lib.espn_workspace_bytes(3, 100) % 256 == 0 and lib.espn_workspace_bytes(3, 100) >= 1200
+
+
+def test_batches_workspace_bytes_without_a_table(lib):
+    # no table: the size for one batch (the sizes for a table's queues are checked on the GPU)
+    assert lib.espn_batches_workspace_bytes(None, 5, 64, 32, 1000, 10) == lib.espn_workspace_bytes(64, 1000)
+
+
+def test_the_benchmark_probes_are_a_library_of_their_own(lib):
+    """bench.py's plain-read and plain-copy kernels are not exported by the product library."""
+    from paper_2312_05417_amd import benchprobe
+    assert not hasattr(lib, "espn_stream_read_probe") and not hasattr(lib, "espn_bench_stream_read")
+    probe = benchprobe.lib()
+    assert hasattr(probe, "espn_bench_stream_read") and hasattr(probe, "espn_bench_copy")
+    assert probe.espn_bench_stream_read(None, 16, None, None) == 1          # bad argument, found on the host
+    assert probe.espn_bench_copy(None, None, 0, None) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -1,0 +1,177 @@
+"""espn_rerank_batches: a queue of batches of one shape in one call, spread over the library's own streams.
+Checked against the fp64 oracle, against espn_rerank bit for bit, and for its ordering with the caller's
+stream (work enqueued before the call is seen by every batch; work enqueued after it sees every result)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_05417_amd import binding as espn
+from paper_2312_05417_amd import synth
+from tests.parity import assert_scores_close, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+@pytest.mark.parametrize("key,changes,n_batches", [
+    ("c1", {}, 7),                                            # 64-byte rows, short lists
+    ("c2", dict(n_docs=40_000, B=24, K=1000), 5),             # two launches per batch (scores, then ranking)
+    ("c3", dict(n_docs=5_000, B=6, K=300), 4),                # 256-byte rows
+    ("c2", dict(n_docs=20_000, B=40, K=64), 9),               # lists the scoring launch ranks itself
+    ("c1", {}, 40),                                           # three fused launches of 13, 13 and 14 batches
+    ("c2", dict(n_docs=40_000, B=24, K=1000), 35),            # the same with two launches per chunk
+    ("c2", dict(n_docs=20_000, B=40, K=64, k=64), 20),        # every rank of a short list, two chunks of 10
+    ("c1", dict(k=40), 5),                                    # more ranks than the one-wave kernel takes: sorted per batch
+])
+def test_a_queue_of_batches_matches_the_oracle_and_single_calls(key, changes, n_batches):
+    w = synth.scaled(synth.WORKLOADS[key], **changes)
+    say("batches %s d=%d B=%d K=%d x %d" % (w.name, w.dim, w.B, w.K, n_batches))
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    qs_d = [q.to(DEV) for q in qs]
+    cands_d = [torch.from_numpy(c).to(DEV) for c in cands]
+    ids, tops = espn.espn_rerank_batches(table, qs_d, cands_d, w.k)
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    for n in range(n_batches):
+        o_ids, o_top, o_all = oracle.rerank(emb.numpy(), off, qs[n].numpy(), cands[n], w.k)
+        for b in range(w.B):
+            assert_topk_matches(ids[n][b].cpu().numpy(), tops[n][b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+        one_ids, one_top = espn.espn_rerank(table, qs_d[n], cands_d[n], w.k)
+        assert torch.equal(one_ids, ids[n]), n
+        assert np.array_equal(one_top.cpu().numpy().view(np.int32), tops[n].cpu().numpy().view(np.int32)), n
+    table.free()
+
+
+def test_a_queue_over_a_compressed_table():
+    w = synth.scaled(synth.WORKLOADS["c2"], n_docs=15_000, B=12, K=400)
+    say("batches E4M3 d=%d" % w.dim)
+    emb, off = synth.table(w)
+    codes, scale = synth.compress_e4m3(emb, off)
+    table = espn.espn_table_load_e4m3(codes.to(DEV), scale, off)
+    n_batches = 18
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    ids, tops = espn.espn_rerank_batches(table, [q.to(DEV) for q in qs], [torch.from_numpy(c).to(DEV) for c in cands], w.k)
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    for n in range(n_batches):
+        o_all = oracle.scores_e4m3(codes.numpy(), scale, off, qs[n].numpy(), cands[n])
+        for b in range(w.B):
+            assert_topk_matches(ids[n][b].cpu().numpy(), tops[n][b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+    table.free()
+
+
+def test_workspace_of_a_queue():
+    """One part per batch of a fused launch, per stream used: small batches are scored up to 16 at a time on up to
+    three streams, batches that fill the device by themselves one at a time."""
+    t32 = espn.espn_table_load(torch.zeros((64, 32), dtype=torch.float16, device=DEV), np.array([0, 64], dtype=np.int64))
+    t128 = espn.espn_table_load(torch.zeros((64, 128), dtype=torch.float16, device=DEV), np.array([0, 64], dtype=np.int64))
+    one = espn.espn_workspace_bytes(64, 1000)
+    size = lambda t, n, B, K, k=10: espn.espn_batches_workspace_bytes(t, n, B, 32, K, k)
+    assert size(t32, 1, 64, 1000) == one
+    assert size(t32, 5, 64, 1000) == 5 * one                  # one launch of five
+    assert size(t32, 16, 64, 1000) == 16 * one
+    assert size(t32, 20, 64, 1000) == 2 * 16 * one            # two launches (of 10), a part of 16 per stream
+    assert size(t32, 400, 64, 1000) == 3 * 16 * one
+    assert size(t32, 400, 64, 1000, k=100) == 3 * one         # 100 ranks need the sort kernel: batch by batch
+    big = espn.espn_workspace_bytes(2048, 1000)
+    assert size(t128, 12, 2048, 1000) == 3 * big              # a batch that is 32 768 workgroups is not fused
+    assert size(t128, 2, 2048, 1000) == 2 * big
+    assert size(t128, 20, 256, 1000) == 3 * 2 * espn.espn_workspace_bytes(256, 1000)     # two at a time
+    t32.free()
+    t128.free()
+
+
+def test_the_call_is_one_operation_on_the_callers_stream():
+    """Inputs written on the caller's stream right before the call are the ones every batch reads, and a copy
+    enqueued on it right after the call copies finished results; repeated so that a missing wait would show."""
+    w = synth.scaled(synth.WORKLOADS["c2"], n_docs=30_000, B=16, K=500)
+    say("batches: ordering with the caller's stream")
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    n_batches = 38                                  # three fused launches, one per stream of the library
+    fresh_q = [synth.queries(w, batch=n).to(DEV) for n in range(n_batches)]
+    fresh_c = [torch.from_numpy(synth.candidates(w, batch=n)).to(DEV) for n in range(n_batches)]
+    want = [espn.espn_rerank(table, fresh_q[n], fresh_c[n], w.k) for n in range(n_batches)]
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    q_in = [torch.zeros_like(x) for x in fresh_q]
+    c_in = [torch.zeros_like(x) for x in fresh_c]
+    out_ids = [torch.empty((w.B, w.k), dtype=torch.int64, device=DEV) for _ in range(n_batches)]
+    out_sc = [torch.empty((w.B, w.k), dtype=torch.float32, device=DEV) for _ in range(n_batches)]
+    got_ids = [torch.empty_like(x) for x in out_ids]
+    got_sc = [torch.empty_like(x) for x in out_sc]
+    ws = torch.empty(espn.espn_batches_workspace_bytes(table, n_batches, w.B, w.Q, w.K, w.k), dtype=torch.uint8, device=DEV)
+    busy = torch.empty(1 << 24, dtype=torch.float32, device=DEV)
+    for rep in range(4):
+        for x in q_in + c_in + out_ids + out_sc:
+            x.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            busy.normal_()                          # something for the stream to be busy with first
+            for n in range(n_batches):
+                q_in[n].copy_(fresh_q[n])
+                c_in[n].copy_(fresh_c[n])
+            espn.espn_rerank_batches(table, q_in, c_in, w.k, out_ids, out_sc, workspace=ws, stream=stream)
+            for n in range(n_batches):
+                got_ids[n].copy_(out_ids[n])
+                got_sc[n].copy_(out_sc[n])
+        stream.synchronize()
+        for n in range(n_batches):
+            assert torch.equal(got_ids[n], want[n][0]), (rep, n)
+            assert torch.equal(got_sc[n], want[n][1]), (rep, n)
+    espn.espn_table_check(table)
+    table.free()
+
+
+def test_argument_errors_are_found_before_anything_runs():
+    w = synth.scaled(synth.WORKLOADS["c1"], n_docs=500)
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    lib = espn.lib()
+    qs = [synth.queries(w, batch=n).to(DEV) for n in range(3)]
+    cs = [torch.from_numpy(synth.candidates(w, batch=n)).to(DEV) for n in range(3)]
+    oi = [torch.full((w.B, w.k), -5, dtype=torch.int64, device=DEV) for _ in range(3)]
+    os_ = [torch.zeros((w.B, w.k), dtype=torch.float32, device=DEV) for _ in range(3)]
+    ws = torch.empty(espn.espn_batches_workspace_bytes(table, 3, w.B, w.Q, w.K, w.k), dtype=torch.uint8, device=DEV)
+    st = int(torch.cuda.current_stream().cuda_stream)
+    P = espn.pointer_list
+
+    def call(n, q, c, i, s, ws_bytes, k=w.k):
+        return lib.espn_rerank_batches(table.handle, n, q, c, w.B, w.Q, w.K, k, i, s, ws.data_ptr(), ws_bytes, st)
+
+    q_l, c_l, i_l, s_l = P(qs, torch.float16, "q"), P(cs, torch.int64, "c"), P(oi, torch.int64, "i"), P(os_, torch.float32, "s")
+    assert call(-1, q_l, c_l, i_l, s_l, ws.numel()) == espn.ESPN_ERR_ARG
+    assert call(0, None, None, None, None, 0) == espn.ESPN_OK                     # nothing to do
+    assert call(3, None, c_l, i_l, s_l, ws.numel()) == espn.ESPN_ERR_ARG
+    assert call(3, q_l, c_l, i_l, s_l, ws.numel() - 256) == espn.ESPN_ERR_SHAPE    # short of what three batches need
+    assert call(3, q_l, c_l, i_l, s_l, ws.numel(), k=w.K + 1) == espn.ESPN_ERR_SHAPE
+    broken = (ctypes.c_void_p * 3)(qs[0].data_ptr(), qs[1].data_ptr(), None)       # the LAST batch is bad
+    assert call(3, broken, c_l, i_l, s_l, ws.numel()) == espn.ESPN_ERR_ARG
+    torch.cuda.synchronize()
+    for x in oi:                                                                    # and nothing has run
+        assert int((x != -5).sum()) == 0
+    assert call(3, q_l, c_l, i_l, s_l, ws.numel()) == espn.ESPN_OK
+    torch.cuda.synchronize()
+    for n in range(3):
+        ref = espn.espn_rerank(table, qs[n], cs[n], w.k)
+        assert torch.equal(ref[0], oi[n]) and torch.equal(ref[1], os_[n])
+    # a host-resident table is refused like everywhere else
+    pinned = torch.empty(emb.shape, dtype=torch.float16, pin_memory=True)
+    pinned.copy_(emb)
+    host = espn.espn_table_load(pinned, off)
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_rerank_batches(host, qs, cs, w.k)
+    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+    host.free()
+    table.free()

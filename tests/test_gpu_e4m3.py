@@ -16,12 +16,15 @@ def say(msg):
     print("[case] " + msg, flush=True)
 
 
-def check(codes, scale, off, q, cand, k, Q):
-    """codes uint8 numpy, scale fp32 numpy, off, q fp16 numpy, cand int64 numpy."""
+def check(codes, scale, off, q, cand, k, Q, fetch=None):
+    """codes uint8 numpy, scale fp32 numpy, off, q fp16 numpy, cand int64 numpy; fetch: a mode for
+    espn_table_set_fetch, or None for the library's default."""
     o_all = oracle.scores_e4m3(codes, scale, off, q, cand)
     o_ids, o_top = oracle.topk(o_all, cand, k)
     codes_d = torch.from_numpy(codes).to(DEV) if codes.size else torch.zeros((0, codes.shape[1]), dtype=torch.uint8, device=DEV)
     table = espn.espn_table_load_e4m3(codes_d, scale, off)
+    if fetch is not None:
+        espn.espn_table_set_fetch(table, fetch)
     q_d, cand_d = torch.from_numpy(q).to(DEV), torch.from_numpy(cand).to(DEV)
     g_all = espn.espn_score(table, q_d, cand_d).cpu().numpy()
     g_ids, g_top = espn.espn_rerank(table, q_d, cand_d, k)
@@ -85,6 +88,11 @@ def test_ragged_documents_scales_and_empty_documents(d, Q):
     cand = np.stack([rng.permutation(counts.size)[:77] for _ in range(3)]).astype(np.int64)
     worst, g_all, o_all = check(codes, scale, off, q, cand, 77, Q)
     assert np.isneginf(g_all[counts[cand] == 0]).all()
+    # both ways of fetching the rows, forced (the default picks one from the batch's size): the lane-linear
+    # streaming loads with their partial last tiles and the ordinary loads give the same bits
+    for mode in (espn.ESPN_FETCH_STREAMING, espn.ESPN_FETCH_CACHED):
+        _, g_mode, _ = check(codes, scale, off, q, cand, 77, Q, fetch=mode)
+        assert np.array_equal(g_mode.view(np.int32), g_all.view(np.int32)), mode
 
 
 def test_host_resident_compressed_table():

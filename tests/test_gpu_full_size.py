@@ -32,8 +32,18 @@ def check_everything_cheap(scores, ids, top, cand, w):
     assert np.all((scores > kth).sum(axis=1) <= w.k - 1)
 
 
-@pytest.mark.parametrize("key,sample", [("c2", 64), ("c3", 48), ("c4", 48)])
+def spread_sample(B, n):
+    """n query indices spread over the batch, always with the first and last eight (the ends of the grid, and
+    every residue modulo 8: workgroups are renumbered per XCD by that residue)."""
+    ends = np.concatenate([np.arange(min(8, B)), np.arange(max(0, B - 8), B)])
+    return np.unique(np.concatenate([ends, np.linspace(0, B - 1, n).astype(int)]))
+
+
+@pytest.mark.parametrize("key,sample", [("c2", 64), ("c3", 96), ("c4", 128)])
 def test_full_size_hbm_workloads(key, sample):
+    """Through espn_rerank_batches, the call bench.py times: three batches in flight on the library's streams
+    (the first is checked against the oracle, the other two are the same batch again and must give the same
+    bits), and through espn_rerank, which must agree bit for bit."""
     w = synth.WORKLOADS[key]
     say("%s full size: N=%d d=%d B=%d K=%d" % (w.name, w.n_docs, w.dim, w.B, w.K))
     emb, off = synth.table(w, device=DEV)
@@ -41,14 +51,23 @@ def test_full_size_hbm_workloads(key, sample):
     cand = synth.candidates(w)
     cand_d = torch.from_numpy(cand).to(DEV)
     q = synth.queries(w, device=DEV)
-    ws = torch.empty(espn.espn_workspace_bytes(w.B, w.K), dtype=torch.uint8, device=DEV)
-    ids, top = espn.espn_rerank(table, q, cand_d, w.k, workspace=ws)
+    part = espn.espn_workspace_bytes(w.B, w.K)
+    ws = torch.empty(espn.espn_batches_workspace_bytes(table, 3, w.B, w.Q, w.K, w.k), dtype=torch.uint8, device=DEV)
+    many_ids, many_top = espn.espn_rerank_batches(table, [q] * 3, [cand_d] * 3, w.k, workspace=ws)
+    torch.cuda.synchronize()
     espn.espn_table_check(table)
-    scores = ws[: 4 * w.B * w.K].view(torch.float32).view(w.B, w.K).cpu().numpy()
-    ids, top = ids.cpu().numpy(), top.cpu().numpy()
+    first = ws[: 4 * w.B * w.K].view(torch.float32).view(w.B, w.K)       # a queue of three leaves batch 0's scores here
+    scores = first.cpu().numpy()
+    for l in (1, 2):
+        assert torch.equal(many_ids[l], many_ids[0]) and torch.equal(many_top[l].view(torch.int32), many_top[0].view(torch.int32))
+    one_ids, one_top = espn.espn_rerank(table, q, cand_d, w.k, workspace=ws[:part])
+    assert torch.equal(one_ids, many_ids[0]) and torch.equal(one_top.view(torch.int32), many_top[0].view(torch.int32))
+    assert torch.equal(first.view(torch.int32), torch.from_numpy(scores).to(DEV).view(torch.int32))
+    ids, top = many_ids[0].cpu().numpy(), many_top[0].cpu().numpy()
     check_everything_cheap(scores, ids, top, cand, w)
-    # oracle on a sample of queries spread over the batch (first, last and in between)
-    pick = np.unique(np.linspace(0, w.B - 1, sample).astype(int))
+    # oracle on a sample of queries spread over the batch (its ends, every residue modulo 8, and in between)
+    pick = spread_sample(w.B, sample)
+    assert pick.size >= min(sample, w.B) and set(pick % 8) == set(range(8))
     sub, loc_off, loc_cand, _ = synth.subtable(emb, off, cand[pick])
     o_ids, o_top, o_all = oracle.rerank(sub, loc_off, q[torch.from_numpy(pick).to(DEV)].cpu().numpy(), loc_cand, w.k)
     worst = assert_scores_close(scores[pick], o_all, w.Q)
@@ -86,7 +105,7 @@ def test_host_resident_workload_at_full_batch_shape():
         scores = ws[: 4 * w.B * w.K].view(torch.float32).view(w.B, w.K).cpu().numpy()
         ids, top = ids.cpu().numpy(), top.cpu().numpy()
         check_everything_cheap(scores, ids, top, cands[n], w)
-        pick = np.array([0, 511, 1023])
+        pick = spread_sample(w.B, 8)                 # 16 to 24 queries per batch
         sub, loc_off, loc_cand, _ = synth.subtable(emb, off, cands[n][pick])
         o_ids, o_top, o_all = oracle.rerank(sub, loc_off, qs[n][torch.from_numpy(pick).to(DEV)].cpu().numpy(),
                                             loc_cand, w.k)

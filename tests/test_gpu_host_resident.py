@@ -350,3 +350,60 @@ def test_the_packing_engine_reports_its_errors_before_enqueuing_anything():
         espn.espn_prefetch_packed(hbm, cand_h, 0)
     assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
     hbm.free()
+
+
+def test_a_table_in_ordinary_host_memory_is_served_by_the_packing_engine():
+    """ESPN_RESIDENT_HOST: the table is not pinned, so only the host reads it (espn_prefetch_packed packs its
+    documents into the library's own pinned buffers); double-buffered batches against the oracle, bit for bit
+    against the same table pinned, and the gather engine (which would need the device to read the table) refused."""
+    w = synth.scaled(synth.WORKLOADS["c5"], n_docs=30_000, B=24, K=400)
+    say("pageable host table d=%d N=%d B=%d K=%d" % (w.dim, w.n_docs, w.B, w.K))
+    emb, off = synth.table(w)                                  # ordinary host memory
+    assert not emb.is_pinned()
+    with pytest.raises(TypeError):
+        espn.espn_table_load(emb, off)                         # the binding wants to be told
+    table = espn.espn_table_load(emb, off, pageable=True)
+    assert table.info()["residency"] == espn.ESPN_RESIDENT_HOST
+    pinned_emb, _ = host_table(w)
+    pinned = espn.espn_table_load(pinned_emb, off)
+    for t in (table, pinned):
+        espn.espn_staging_create(t, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    n_batches = 4
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    cands_h = [torch.from_numpy(c) for c in cands]
+    cands_d = [c.to(DEV) for c in cands_h]
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    qs_d = [x.to(DEV) for x in qs]
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_prefetch(table, cands_d[0], 0)
+    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_rerank(table, qs_d[0], cands_d[0], w.k)
+    assert ei.value.status == espn.ESPN_ERR_UNSUPPORTED
+    side = torch.cuda.Stream()
+    outs = []
+    espn.espn_prefetch_packed(table, cands_h[0], 0, side)
+    for n in range(n_batches):
+        outs.append(espn.espn_rerank_staged(table, n % 2, qs_d[n], cands_d[n], w.k))
+        if n + 1 < n_batches:
+            espn.espn_prefetch_packed(table, cands_h[n + 1], (n + 1) % 2, side)
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    e = emb.numpy()
+    for n in range(n_batches):
+        ids, top, ws = outs[n]
+        o_ids, o_top, o_all = oracle.rerank(e, off, qs[n].numpy(), cands[n], w.k)
+        assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
+        for b in range(w.B):
+            assert_topk_matches(ids[b].cpu().numpy(), top[b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+        espn.espn_prefetch(pinned, cands_d[n], 0)
+        p_ids, p_top, p_ws = espn.espn_rerank_staged(pinned, 0, qs_d[n], cands_d[n], w.k)
+        assert torch.equal(p_ids, ids) and torch.equal(p_top.view(torch.int32), top.view(torch.int32))
+        assert np.array_equal(scores_of(p_ws, w.B, w.K).view(np.int32), scores_of(ws, w.B, w.K).view(np.int32))
+    c = espn.espn_staging_counters(table, (n_batches - 1) % 2)
+    uniq = np.unique(cands[-1])
+    rows = int((off[uniq + 1] - off[uniq]).sum())
+    assert c["distinct_docs"] == uniq.size and c["rows"] == rows and c["pcie_bytes"] == rows * w.dim * 2
+    espn.espn_table_check(pinned)
+    pinned.free()
+    table.free()

@@ -171,3 +171,45 @@ def test_plan_of_typical_shapes():
         espn.espn_rerank_plan(t32, 4, 32, 10, 11)
     for t in (t32, t128, t72):
         t.free()
+
+
+def test_plans_and_kernels_of_the_workloads_are_pinned():
+    """The slice plan and the kernel instantiations of every benchmark workload, as espn_rerank_plan and
+    espn_rerank_plan_kernels report them: later tuning of the planner cannot change them unnoticed.  (The fetch
+    mode is set by hand because these one-document tables are too small for the library's own rule.)"""
+    say("plans of the workloads")
+    S, C = espn.ESPN_FETCH_STREAMING, espn.ESPN_FETCH_CACHED
+    t32 = espn.espn_table_load(torch.zeros((64, 32), dtype=torch.float16, device=DEV), np.array([0, 64], dtype=np.int64))
+    t128 = espn.espn_table_load(torch.zeros((64, 128), dtype=torch.float16, device=DEV), np.array([0, 64], dtype=np.int64))
+    c32 = espn.espn_table_load_e4m3(torch.zeros((64, 32), dtype=torch.uint8, device=DEV), np.ones(1, dtype=np.float32),
+                                    np.array([0, 64], dtype=np.int64))
+    c128 = espn.espn_table_load_e4m3(torch.zeros((64, 128), dtype=torch.uint8, device=DEV), np.ones(1, dtype=np.float32),
+                                     np.array([0, 64], dtype=np.int64))
+    want = [
+        # workload, table, fetch, B, K scored, k -> slices, slice, launches, kernels
+        ("c1", t32, S, 8, 100, 10, 6, 17, 2, ["espn::maxsim_slice_kernel<32, 16, 4, 2, false, 2, true>", "espn::topk_wave_kernel<4>"]),
+        ("c2", t32, S, 64, 1000, 10, 8, 125, 2, ["espn::maxsim_slice_kernel<32, 16, 4, 2, false, 2, true>", "espn::topk_wave_kernel<16>"]),
+        ("c3", t128, S, 256, 1000, 10, 16, 63, 2, ["espn::maxsim_slice_kernel<128, 4, 4, 2, false, 2, true>", "espn::topk_wave_kernel<16>"]),
+        ("c4", t128, C, 2048, 1000, 10, 16, 63, 2, ["espn::maxsim_slice_kernel<128, 4, 4, 2, false, 2, false>", "espn::topk_wave_kernel<16>"]),
+        ("c5 (a staged batch is scored like c4 at half the queries)", t128, C, 1024, 1000, 10, 16, 63, 2,
+         ["espn::maxsim_slice_kernel<128, 4, 4, 2, false, 2, false>", "espn::topk_wave_kernel<16>"]),
+        ("c2p64", t32, S, 1024, 64, 10, 1, 64, 1, ["espn::maxsim_slice_kernel<32, 8, 4, 2, true, 2, true>"]),
+        ("c3p64", t128, S, 4096, 64, 10, 1, 64, 1, ["espn::maxsim_slice_kernel<128, 4, 4, 2, true, 2, true>"]),
+        ("c2e4m3", c32, S, 64, 1000, 10, 8, 125, 2, ["espn::maxsim_slice_kernel<32, 16, 4, 1, false, 2, true>", "espn::topk_wave_kernel<16>"]),
+        ("c3e4m3", c128, S, 256, 1000, 10, 16, 63, 2, ["espn::maxsim_slice_kernel<128, 8, 4, 1, false, 2, true>", "espn::topk_wave_kernel<16>"]),
+    ]
+    wrong = []
+    for name, table, fetch, B, K, k, slices, slice_, launches, kernels in want:
+        espn.espn_table_set_fetch(table, fetch)
+        got = (espn.espn_rerank_plan(table, B, 32, K, k), espn.espn_rerank_plan_kernels(table, B, 32, K, k))
+        if got != ({"slices": slices, "slice": slice_, "launches": launches}, kernels):
+            wrong.append((name, got))
+    assert not wrong, wrong
+    # scoring alone (k = 0) names one kernel, an empty batch none, other shapes the plain kernel or a sort
+    assert espn.espn_rerank_plan_kernels(t32, 64, 32, 1000, 0) == ["espn::maxsim_slice_kernel<32, 16, 4, 2, false, 2, true>"]
+    assert espn.espn_rerank_plan_kernels(t32, 0, 32, 1000, 10) == []
+    assert espn.espn_rerank_plan_kernels(t32, 64, 65, 1000, 100) == ["espn::maxsim_generic_kernel",
+                                                                    "espn::topk_sort_kernel<1024, 256, espn::OneList>"]
+    assert espn.espn_rerank_plan_kernels(t128, 3, 48, 5000, 10)[1] == "espn::topk_rounds_kernel<16>"
+    for t in (t32, t128, c32, c128):
+        t.free()

@@ -148,10 +148,11 @@ def test_few_pairs_against_a_large_table_take_the_lane_linear_loads(d, Q):
     table.free()
 
 
-def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
-    """Under the default fetch mode every 64th scoring call samples the batch's candidate lists; the estimate (the
-    share of sampled pairs that repeat a document) separates uniformly drawn lists from lists that share popular
-    documents, and scores are the same whichever way the rows are then fetched."""
+def test_the_library_is_told_whether_the_lists_of_a_batch_share_documents():
+    """espn_table_sample looks at a batch's candidate lists when the caller asks for it (never on its own); the
+    estimate (the share of sampled pairs that repeat a document) separates uniformly drawn lists from lists that
+    share popular documents, decides how the default fetch mode loads the rows from then on, and the scores are
+    the same whichever way that is."""
     say("sharing estimate")
     rng = np.random.default_rng(21)
     N, d, B, K = 30_000, 128, 8, 200            # 1600 uniform pairs over 30 000 documents: about 2.7 % repeat
@@ -163,29 +164,29 @@ def test_the_library_notices_whether_the_lists_of_a_batch_share_documents():
     table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
     assert espn.espn_table_sharing_estimate(table) == -1.0
     q_d = torch.from_numpy(q).to(DEV)
-    results = {}
-    for name, cand in (("uniform", uniform), ("shared", shared), ("uniform again", uniform)):
-        cand_d = torch.from_numpy(cand).to(DEV)
-        for call in range(64):                                  # the sample is taken on the first of every 64 calls
-            scores = espn.espn_score(table, q_d, cand_d)
-        torch.cuda.synchronize()
-        results[name] = (espn.espn_table_sharing_estimate(table), scores.cpu().numpy())
-    espn.espn_table_check(table)
-    assert 0.0 <= results["uniform"][0] < 0.05, results["uniform"][0]
-    assert results["shared"][0] > 0.5, results["shared"][0]
-    assert 0.0 <= results["uniform again"][0] < 0.05
-    # the first 64 calls on uniform lists were planned before any sample, the last 64 after the "shared" sample:
-    # whatever was chosen, the scores are the same bit for bit, and right
-    assert np.array_equal(results["uniform"][1].view(np.int32), results["uniform again"][1].view(np.int32))
-    assert_scores_close(results["shared"][1], oracle.scores(emb, off, q, shared), 32)
-    assert_scores_close(results["uniform"][1], oracle.scores(emb, off, q, uniform), 32)
-    # a caller's choice switches the sampling off
-    espn.espn_table_set_fetch(table, espn.ESPN_FETCH_CACHED)
-    before = espn.espn_table_sharing_estimate(table)
+    # scoring never samples by itself, however often it is called
     for call in range(70):
         espn.espn_score(table, q_d, torch.from_numpy(shared).to(DEV))
     torch.cuda.synchronize()
-    assert espn.espn_table_sharing_estimate(table) == before
+    assert espn.espn_table_sharing_estimate(table) == -1.0
+    results = {}
+    for name, cand in (("uniform", uniform), ("shared", shared), ("uniform again", uniform)):
+        cand_d = torch.from_numpy(cand).to(DEV)
+        before = espn.espn_score(table, q_d, cand_d).cpu().numpy()      # planned with the previous estimate
+        est = espn.espn_table_sample(table, cand_d)
+        assert est == espn.espn_table_sharing_estimate(table)
+        after = espn.espn_score(table, q_d, cand_d).cpu().numpy()       # planned with this one
+        assert np.array_equal(before.view(np.int32), after.view(np.int32)), name
+        results[name] = (est, after)
+    espn.espn_table_check(table)
+    assert 0.0 <= results["uniform"][0] < 0.05, results["uniform"][0]
+    assert results["shared"][0] > 0.5, results["shared"][0]
+    assert results["uniform again"][0] == results["uniform"][0]          # the same lists, the same sample
+    assert np.array_equal(results["uniform"][1].view(np.int32), results["uniform again"][1].view(np.int32))
+    assert_scores_close(results["shared"][1], oracle.scores(emb, off, q, shared), 32)
+    assert_scores_close(results["uniform"][1], oracle.scores(emb, off, q, uniform), 32)
+    # an empty batch is a sample of nothing
+    assert espn.espn_table_sample(table, torch.zeros((0, 5), dtype=torch.int64, device=DEV)) == 0.0
     table.free()
 
 

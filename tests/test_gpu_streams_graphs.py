@@ -95,15 +95,26 @@ def test_read_probe_reads_whatever_it_is_given_and_stores_nothing():
     say("read probe")
     buf = torch.arange(0, 1 << 22, dtype=torch.int32, device=DEV)              # 16 MiB, xor of the words is 0
     sink = torch.full((1,), 7, dtype=torch.int64, device=DEV)
+    from paper_2312_05417_amd import benchprobe
+    st = int(torch.cuda.current_stream().cuda_stream)
+
+    def read(t):
+        benchprobe.stream_read(t.data_ptr(), t.numel() * t.element_size(), sink.data_ptr(), st)
+
     for n_words in (4, 8, 1 << 10, (1 << 22) - 4, 1 << 22):
-        espn.espn_stream_read_probe(buf[:n_words], sink)
+        read(buf[:n_words])
     torch.cuda.synchronize()
     assert int(sink.item()) == 7
     ones = torch.full((4,), -1, dtype=torch.int32, device=DEV)                 # one chunk of all ones: stored
-    espn.espn_stream_read_probe(ones, sink)
+    read(ones)
     torch.cuda.synchronize()
     assert int(sink.item()) == -1
-    with pytest.raises(espn.EspnError):
-        espn.espn_stream_read_probe(buf[:3], sink)                             # 12 bytes
-    with pytest.raises(espn.EspnError):
-        espn.espn_stream_read_probe(buf[1:5], sink)                            # not 16-byte aligned
+    with pytest.raises(ValueError):
+        read(buf[:3])                                                          # 12 bytes
+    with pytest.raises(ValueError):
+        read(buf[1:5])                                                         # not 16-byte aligned
+    # the calibration copy copies
+    dst = torch.zeros(1 << 20, dtype=torch.int32, device=DEV)
+    benchprobe.copy(buf.data_ptr(), dst.data_ptr(), dst.numel() * 4, st)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, buf[: 1 << 20])
