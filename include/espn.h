@@ -205,6 +205,15 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
  */
 #define ESPN_BATCH_LANES 3
 size_t espn_batches_workspace_bytes(const espn_table *table, int32_t n_batches, int32_t B, int32_t Q, int32_t K, int32_t k);
+
+/*
+ * How espn_rerank_batches would run a queue of this shape: `fuse` batches per scoring launch at most (the queue is
+ * cut into `launches` chunks whose sizes differ by one at most), dealt to `streams` streams (1: the caller's own),
+ * and the profiler names of the kernels of one chunk, separated by ';' (kernels: HOST, 256 bytes always suffice;
+ * may be NULL, as any other out pointer).  Host arithmetic only.  Errors: ARG, SHAPE.
+ */
+int espn_batches_plan(const espn_table *table, int32_t n_batches, int32_t B, int32_t Q, int32_t K, int32_t k,
+                      int32_t *fuse, int32_t *launches, int32_t *streams, char *kernels, size_t kernels_len);
 int espn_rerank_batches(espn_table *table, int32_t n_batches, const void *const *q, const int64_t *const *cand,
                         int32_t B, int32_t Q, int32_t K, int32_t k,
                         int64_t *const *out_ids, float *const *out_scores,

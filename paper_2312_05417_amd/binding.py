@@ -43,6 +43,8 @@ SIGNATURES = {
     "espn_rerank_plan_kernels": (ctypes.c_int, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, ctypes.c_char_p, _c_sz]),
     "espn_rerank": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "espn_batches_workspace_bytes": (_c_sz, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32]),
+    "espn_batches_plan": (ctypes.c_int, [_c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, ctypes.POINTER(_c_i32),
+                                         ctypes.POINTER(_c_i32), ctypes.POINTER(_c_i32), ctypes.c_char_p, _c_sz]),
     "espn_rerank_batches": (ctypes.c_int, [_c_p, _c_i32, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p,
                                            _c_sz, _c_p]),
     "espn_rerank_noalloc": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i32, _c_i32, _c_i32, _c_i32, _c_p, _c_p, _c_p]),
@@ -293,6 +295,17 @@ def espn_rerank(table: Table, q: torch.Tensor, cand: torch.Tensor, k: int, out_i
 
 def espn_batches_workspace_bytes(table: Table, n_batches: int, B: int, Q: int, K: int, k: int) -> int:
     return int(lib().espn_batches_workspace_bytes(table.handle, n_batches, B, Q, K, k))
+
+
+def espn_batches_plan(table: Table, n_batches: int, B: int, Q: int, K: int, k: int) -> dict:
+    """How a queue of this shape would run: batches per launch, launches, streams, kernel names of one chunk."""
+    fuse, launches, streams = _c_i32(), _c_i32(), _c_i32()
+    buf = ctypes.create_string_buffer(256)
+    _check(lib().espn_batches_plan(table.handle, n_batches, B, Q, K, k, ctypes.byref(fuse), ctypes.byref(launches),
+                                   ctypes.byref(streams), buf, 256))
+    text = buf.value.decode()
+    return {"fuse": fuse.value, "launches": launches.value, "streams": streams.value,
+            "kernels": text.split(";") if text else []}
 
 
 def pointer_list(tensors, dtype, name: str):

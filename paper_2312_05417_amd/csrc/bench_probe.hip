@@ -11,7 +11,7 @@
 
 #include <algorithm>
 
-namespace {
+namespace espn_bench {
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 // Workgroup x walks 16-byte chunks [x * per, (x + 1) * per), 8 loads in flight per lane, non-temporal (against
@@ -48,7 +48,8 @@ int n_compute_units()
     if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
     return n_cu;
 }
-}  // namespace
+}  // namespace espn_bench
+using namespace espn_bench;
 
 #define PROBE_API extern "C" __attribute__((visibility("default")))
 

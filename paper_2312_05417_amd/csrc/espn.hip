@@ -503,6 +503,18 @@ constexpr int kNarrowWaves128 = 4;
 // document of the sample (uniform lists over 2 M documents: 0.002; Zipf(1.1) lists: above 0.5)
 constexpr float kShareThreshold = 0.05f;
 
+// The planner's numbers, all per compute unit (n_cu comes from the device) or per workgroup:
+constexpr int kResidentPerCu = 2;        // workgroups of the scoring kernel a compute unit holds at once (32 waves: 2 x 16 or 2 x 8 + registers)
+constexpr int kThreePerCu = 3;           // the cut that gives three workgroups per compute unit (171-192 queries)
+constexpr int kFewestFitted = 4;         // 193-255 queries: slice counts tried for the best fit to whole rounds of
+constexpr int kMostFitted = 12;          //   one workgroup per compute unit ...
+constexpr double kPerSlicePenalty = 0.02;    // ... fewer slices preferred: a slice more must fill 2 % more of its last round
+constexpr int kLongestCutSlice = 256;    // a cut that fills the device once may make slices of up to this many candidates
+constexpr int kFixedSlice32 = 125;       // slice of launches beyond one round: candidates of 64-byte rows (2.5 KB each)
+constexpr int kFixedSlice128 = 63;       //   and of 256-byte rows (18 KB each); +/- a factor 2 costs 1-2 %
+constexpr int kNarrowFrom = 4;           // workgroups per compute unit from which 64-byte rows run in workgroups of kNarrowWaves
+constexpr int kNarrowFrom128 = 8;        //   and 256-byte binary16 rows in workgroups of kNarrowWaves128
+
 // How a batch is cut into workgroup slices, and whether the scoring kernel ranks as well.
 struct SlicePlan {
     int slice = 0;          // candidates per workgroup
@@ -603,7 +615,7 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
                         (t->fetch == ESPN_FETCH_STREAMING || (t->fetch == ESPN_FETCH_AUTO && streaming));
 
     const int waves = waves_per_workgroup(t->dim);
-    const int slots = 2 * t->n_cu;
+    const int slots = kResidentPerCu * t->n_cu;       // workgroups the device holds at once
     // Rows longer than 64 bytes: the cut aims at ONE workgroup per compute unit, and it may leave half the waves of
     // a workgroup without a document.  Every slice count timed for batches of 8 to 256 queries, 256-byte rows: the
     // best is floor(n_cu / B) throughout, with a cliff right behind it (20 queries of 128 candidates: 17.9 us with
@@ -620,21 +632,21 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     int one_round = (wide ? t->n_cu : slots) / std::max(B, 1);
     if (one_round < 2) one_round = slots / std::max(B, 1);
     bool fixed = false;
-    if (one_round == 2 && B <= t->n_cu && (wide || 3 * t->n_cu / B >= 4)) {
+    if (one_round == 2 && B <= t->n_cu && (wide || kThreePerCu * t->n_cu / B >= kFewestFitted)) {
         // (171 to 192 queries: 4 slices for 64-byte rows too: 1000 candidates 83.7-90.1 us against 86.6-91.2 with
         // the fixed slices, 300 candidates 33.3-35.4 against 36.5-37.3 with 2; under Zipf lists 67.5-69.0 against
         // 72.4-72.5 and 27.0-27.5 against 29.4-30.0; as E4M3 codes 58.5-61.7 against 59.2-60.8 and 26.3-26.9
         // against 27.3-27.5.  From 193 queries on no count is better for them in all three settings.)
-        one_round = 3 * t->n_cu / B;
-        if (one_round < 4) {
+        one_round = kThreePerCu * t->n_cu / B;
+        if (one_round < kFewestFitted) {
             // the count of 4 to 12 slices whose workgroups come closest, from below, to a whole number per compute
             // unit, fewer slices preferred (196-200 queries: 5, 980-1000 workgroups; 210: 6; 240: 4); a full device's
             // worth of queries keeps the fixed slices
             fixed = B == t->n_cu;
             double best = -1.;
-            for (int s = 4; s <= 12 && !fixed; ++s) {
+            for (int s = kFewestFitted; s <= kMostFitted && !fixed; ++s) {
                 const int64_t groups = (int64_t)B * s, rounds = (groups + t->n_cu - 1) / t->n_cu;
-                const double score = (double)groups / (double)(rounds * t->n_cu) - 0.02 * s;
+                const double score = (double)groups / (double)(rounds * t->n_cu) - kPerSlicePenalty * s;
                 if (score > best) {
                     best = score;
                     one_round = s;
@@ -647,10 +659,10 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     const bool uncut = k >= 1 && K <= espn::RANK_MAX && (K + waves - 1) / waves <= uncut_rounds(t->dim, t->elem_bytes, linear, B, t->n_cu);
     int slices;
     if (uncut) slices = 1;
-    else if (!fixed && (K + one_round - 1) / one_round <= 256) slices = std::min(one_round, most_slices);
+    else if (!fixed && (K + one_round - 1) / one_round <= kLongestCutSlice) slices = std::min(one_round, most_slices);
     else {
         // fixed slices: 125 candidates of 64-byte rows, 63 of 256-byte rows, in between by row bytes
-        const int per_slice = t->dim == 32 ? 125 : std::max(16, 63 * 128 / t->dim);
+        const int per_slice = t->dim == 32 ? kFixedSlice32 : std::max(16, kFixedSlice128 * 128 / t->dim);
         slices = (K + per_slice - 1) / per_slice;
     }
     slices = std::max(slices, (K + espn::MAX_SLICE - 1) / espn::MAX_SLICE);
@@ -660,8 +672,8 @@ SlicePlan plan_slices(const espn_table *t, int B, int K, int k)
     p.rank = p.slices == 1 && K <= espn::RANK_MAX && k >= 1;
     const int64_t workgroups = (int64_t)B * p.slices;
     p.waves = waves;
-    if (t->dim == 32 && workgroups >= 4 * (int64_t)t->n_cu) p.waves = kNarrowWaves;
-    if (t->dim == 128 && t->elem_bytes == 2 && workgroups >= 8 * (int64_t)t->n_cu) p.waves = kNarrowWaves128;     // Q <= 32 only
+    if (t->dim == 32 && workgroups >= kNarrowFrom * (int64_t)t->n_cu) p.waves = kNarrowWaves;
+    if (t->dim == 128 && t->elem_bytes == 2 && workgroups >= kNarrowFrom128 * (int64_t)t->n_cu) p.waves = kNarrowWaves128;     // Q <= 32 only
     p.linear = linear;
     return p;
 }
@@ -982,6 +994,38 @@ ESPN_API int espn_rerank_plan(const espn_table *table, int32_t B, int32_t Q, int
     return ESPN_OK;
 }
 
+namespace {
+// Profiler names of the kernels one launch pair of the path runs for `queries` queries in one launch (a batch, or a
+// fused chunk of a queue: `fused` then names the ranking kernel that takes a set of batches).  text: 256 bytes.
+void kernel_names(const espn_table *table, int queries, int Q, int K, int k, bool fused, char *text, size_t len)
+{
+    bool ranked = false;
+    if (on_matrix_cores(table, Q)) {
+        const SlicePlan plan = plan_slices(table, queries, K, k);
+        const int QG = Q > 32 ? 4 : 2;
+        ranked = plan.rank;
+        snprintf(text, len, "espn::maxsim_slice_kernel<%d, %d, %d, %d, %s, %d, %s>", table->dim,
+                 launched_waves(table->dim, table->elem_bytes, QG, plan), kPipeline, table->elem_bytes,
+                 plan.rank ? "true" : "false", QG, plan.linear ? "true" : "false");
+    } else {
+        snprintf(text, len, "espn::maxsim_generic_kernel");
+    }
+    if (k > 0 && !ranked) {
+        const size_t at = std::strlen(text);
+        const RankKernel r = rank_kernel(K, k);
+        if (fused) snprintf(text + at, len - at, ";espn::topk_wave_set_kernel<%d>", r == RankKernel::Wave4 ? 4 : r == RankKernel::Wave16 ? 16 : 32);
+        else snprintf(text + at, len - at, ";%s", rank_kernel_name(r));
+    }
+}
+
+int copy_out(const char *text, char *buf, size_t buf_len)
+{
+    if (std::strlen(text) + 1 > buf_len) return fail(ESPN_ERR_SHAPE, "buf holds %zu bytes, %zu needed", buf_len, std::strlen(text) + 1);
+    std::memcpy(buf, text, std::strlen(text) + 1);
+    return ESPN_OK;
+}
+}  // namespace
+
 ESPN_API int espn_rerank_plan_kernels(const espn_table *table, int32_t B, int32_t Q, int32_t K, int32_t k, char *buf,
                                       size_t buf_len)
 {
@@ -992,24 +1036,8 @@ ESPN_API int espn_rerank_plan_kernels(const espn_table *table, int32_t B, int32_
     buf[0] = 0;
     if (B == 0 || K == 0) return ESPN_OK;
     char text[256];
-    bool ranked = false;
-    if (on_matrix_cores(table, Q)) {
-        const SlicePlan plan = plan_slices(table, B, K, k);
-        const int QG = Q > 32 ? 4 : 2;
-        ranked = plan.rank;
-        snprintf(text, sizeof(text), "espn::maxsim_slice_kernel<%d, %d, %d, %d, %s, %d, %s>", table->dim,
-                 launched_waves(table->dim, table->elem_bytes, QG, plan), kPipeline, table->elem_bytes,
-                 plan.rank ? "true" : "false", QG, plan.linear ? "true" : "false");
-    } else {
-        snprintf(text, sizeof(text), "espn::maxsim_generic_kernel");
-    }
-    if (k > 0 && !ranked) {
-        const size_t at = std::strlen(text);
-        snprintf(text + at, sizeof(text) - at, ";%s", rank_kernel_name(rank_kernel(K, k)));
-    }
-    if (std::strlen(text) + 1 > buf_len) return fail(ESPN_ERR_SHAPE, "buf holds %zu bytes, %zu needed", buf_len, std::strlen(text) + 1);
-    std::memcpy(buf, text, std::strlen(text) + 1);
-    return ESPN_OK;
+    kernel_names(table, B, Q, K, k, false, text, sizeof(text));
+    return copy_out(text, buf, buf_len);
 }
 
 ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, int32_t B, int32_t Q, int32_t K,
@@ -1063,6 +1091,30 @@ ESPN_API size_t espn_batches_workspace_bytes(const espn_table *table, int32_t n_
     if (!table || n_batches <= 0 || Q < 1) return espn_workspace_bytes(B, K);
     const QueuePlan qp = plan_queue(table, n_batches, B, Q, K, std::max(k, 0));
     return (size_t)qp.lanes * (size_t)std::min(qp.fuse, n_batches) * espn_workspace_bytes(B, K);
+}
+
+ESPN_API int espn_batches_plan(const espn_table *table, int32_t n_batches, int32_t B, int32_t Q, int32_t K, int32_t k,
+                               int32_t *fuse, int32_t *launches, int32_t *streams, char *kernels, size_t kernels_len)
+{
+    if (!table) return fail(ESPN_ERR_ARG, "table is NULL");
+    if (n_batches < 0 || B < 0 || K < 0 || k < 0 || Q < 1)
+        return fail(ESPN_ERR_ARG, "n_batches = %d, B = %d, Q = %d, K = %d, k = %d", n_batches, B, Q, K, k);
+    if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
+    const bool nothing = n_batches == 0 || B == 0 || K == 0;
+    const QueuePlan qp = nothing ? QueuePlan{} : plan_queue(table, n_batches, B, Q, K, k);
+    const int per_launch = nothing ? 0 : (n_batches + qp.chunks - 1) / qp.chunks;       // the larger of the two chunk sizes
+    if (fuse) *fuse = per_launch;
+    if (launches) *launches = qp.chunks;
+    if (streams) *streams = qp.lanes;
+    if (kernels && kernels_len > 0) {
+        kernels[0] = 0;
+        if (!nothing) {
+            char text[256];
+            kernel_names(table, per_launch * B, Q, K, k, per_launch > 1, text, sizeof(text));
+            return copy_out(text, kernels, kernels_len);
+        }
+    }
+    return ESPN_OK;
 }
 
 ESPN_API int espn_rerank_batches(espn_table *table, int32_t n_batches, const void *const *q, const int64_t *const *cand,

@@ -88,6 +88,19 @@ def test_workspace_of_a_queue():
     assert size(t128, 12, 2048, 1000) == 3 * big              # a batch that is 32 768 workgroups is not fused
     assert size(t128, 2, 2048, 1000) == 2 * big
     assert size(t128, 20, 256, 1000) == 3 * 2 * espn.espn_workspace_bytes(256, 1000)     # two at a time
+    # ... and the plan behind those sizes, with the kernels a profiler would show for one chunk
+    assert espn.espn_batches_plan(t32, 20, 64, 32, 1000, 10) == {
+        "fuse": 10, "launches": 2, "streams": 2,
+        "kernels": ["espn::maxsim_slice_kernel<32, 8, 4, 2, false, 2, true>", "espn::topk_wave_set_kernel<16>"]}
+    assert espn.espn_batches_plan(t32, 400, 64, 32, 1000, 10)["fuse"] == 16
+    assert espn.espn_batches_plan(t32, 1, 64, 32, 1000, 10) == {
+        "fuse": 1, "launches": 1, "streams": 1,
+        "kernels": ["espn::maxsim_slice_kernel<32, 16, 4, 2, false, 2, true>", "espn::topk_wave_kernel<16>"]}
+    espn.espn_table_set_fetch(t128, espn.ESPN_FETCH_CACHED)
+    assert espn.espn_batches_plan(t128, 12, 2048, 32, 1000, 10) == {
+        "fuse": 1, "launches": 12, "streams": 3,
+        "kernels": ["espn::maxsim_slice_kernel<128, 4, 4, 2, false, 2, false>", "espn::topk_wave_kernel<16>"]}
+    assert espn.espn_batches_plan(t32, 0, 64, 32, 1000, 10) == {"fuse": 0, "launches": 0, "streams": 0, "kernels": []}
     t32.free()
     t128.free()
 

@@ -101,9 +101,13 @@ def test_random_shape_with_long_queries(seed):
 
 @pytest.mark.parametrize("seed", range(8))
 def test_random_shape_compressed(seed):
-    d, Q, B, K, k, N, emb, off, q, cand = draw_case(100 + seed)
-    if emb.shape[0] == 0 or d not in (32, 128):
-        pytest.skip("nothing to compress, or a row length compressed tables do not take")
+    # the first draw of this seed's sequence that a compressed table can hold (rows of 32 or 128 components, not empty)
+    for attempt in range(200):
+        d, Q, B, K, k, N, emb, off, q, cand = draw_case(100 + seed + 1000 * attempt)
+        if emb.shape[0] > 0 and d in (32, 128):
+            break
+    else:
+        raise AssertionError("no compressible shape in 200 draws")
     say("e4m3 seed %d: d=%d Q=%d B=%d K=%d k=%d N=%d" % (seed, d, Q, B, K, k, N))
     codes, scale = synth.compress_e4m3(torch.from_numpy(emb), off)
     table = espn.espn_table_load_e4m3(codes.to(DEV), scale, off)
@@ -123,9 +127,12 @@ def test_random_shape_compressed(seed):
 def test_random_shape_partial_and_with_a_prior(seed):
     """The same shapes through partial re-ranking (Sec. 4.4; a random prefix length R) and through the
     aggregated score (Sec. 3.1; a random prior and weight)."""
-    d, Q, B, K, k, N, emb, off, q, cand = draw_case(300 + seed)
-    if emb.shape[0] == 0:
-        pytest.skip("an empty table")
+    for attempt in range(200):          # the first draw of this seed's sequence whose table is not empty
+        d, Q, B, K, k, N, emb, off, q, cand = draw_case(300 + seed + 1000 * attempt)
+        if emb.shape[0] > 0:
+            break
+    else:
+        raise AssertionError("no non-empty table in 200 draws")
     rng = np.random.default_rng(31000 + seed)
     B = min(B, 50)
     cand, q = np.ascontiguousarray(cand[:B]), np.ascontiguousarray(q[:B])
