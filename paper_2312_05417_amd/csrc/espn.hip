@@ -1190,8 +1190,15 @@ ESPN_API int espn_rerank_batches(espn_table *table, int32_t n_batches, const voi
     // wait for if it is idle, which one query tells (an event record and a wait per lane cost about 5 us each on the
     // host, at the start of the call, with the device idle) - and the caller's stream goes on when they are through
     // (those records and waits are enqueued behind the call's own work).
-    const hipError_t idle = hipStreamQuery(st);
-    if (idle != hipSuccess) {
+    // (a stream that is being captured into a graph may not be queried: there the dependency is always recorded,
+    // which is also what pulls the library's streams into the capture; the join below brings them back)
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &capturing) != hipSuccess) {
+        (void)hipGetLastError();
+        capturing = hipStreamCaptureStatusNone;
+    }
+    const bool idle = capturing == hipStreamCaptureStatusNone && hipStreamQuery(st) == hipSuccess;
+    if (!idle) {
         (void)hipGetLastError();                     // hipErrorNotReady is the expected answer, not an error
         HIP_TRY(hipEventRecord(table->fork, st));
         for (int l = 0; l < qp.lanes; ++l) HIP_TRY(hipStreamWaitEvent(table->lane[l], table->fork, 0));

@@ -82,9 +82,11 @@ def kernel_trace(args) -> None:
         f.write("Command (from /tmp with TMPDIR=/tmp, R = repository root):\n\n")
         for c in args.command:
             f.write("    %s\n" % c)
-        f.write("\n`--kernels-only`: every leg of bench.py runs on ONE stream, launches back to back (the timed region of the\n"
-                "queue entry point, whose launches overlap on three streams, is left out: overlapped launches would blur the\n"
-                "per-kernel averages).  Warm-up launches are included in the counts.\n\n")
+        if any("--kernels-only" in c for c in args.command):
+            f.write("\n`--kernels-only`: every leg of bench.py runs on ONE stream, launches back to back (the timed region of the\n"
+                    "queue entry point, whose launches overlap on three streams, is left out: overlapped launches would blur the\n"
+                    "per-kernel averages).  Warm-up launches are included in the counts.\n")
+        f.write("\n")
         f.write("| kernel | calls | total ns | average ns | % of GPU time | min ns | max ns | stddev |\n|---|---|---|---|---|---|---|---|\n")
         for r in rows[:6]:
             f.write("| `%s` | %s | %s | %.0f | %s | %s | %s | %.0f |\n" % (

@@ -66,6 +66,47 @@ def test_captured_graph_replays_match_eager_results(key, changes):
     table.free()
 
 
+def test_a_queue_of_batches_can_be_captured_too():
+    """espn_rerank_batches inside a captured graph: its fork to the library's streams and the join back are event
+    records and waits, which a capture turns into graph edges.  Replayed with eager work and synchronisations of
+    the program in between, every replay checked against the eager results."""
+    w = synth.scaled(synth.WORKLOADS["c3"], n_docs=3000, B=6, K=250)
+    say("graph capture of a queue")
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    n = 20
+    plan = espn.espn_batches_plan(table, n, w.B, w.Q, w.K, w.k)
+    assert plan["launches"] == 2 and plan["streams"] == 2              # so that there is a fork and a join to capture
+    sets = [[(synth.queries(w, batch=10 * r + i).to(DEV), torch.from_numpy(synth.candidates(w, batch=10 * r + i)).to(DEV))
+             for i in range(n)] for r in range(2)]
+    eager = [[tuple(t.clone() for t in espn.espn_rerank(table, q, c, w.k)) for q, c in one] for one in sets]
+    torch.cuda.synchronize()
+    q_buf = [sets[0][i][0].clone() for i in range(n)]
+    c_buf = [sets[0][i][1].clone() for i in range(n)]
+    ids_buf = [torch.empty((w.B, w.k), dtype=torch.int64, device=DEV) for _ in range(n)]
+    sc_buf = [torch.empty((w.B, w.k), dtype=torch.float32, device=DEV) for _ in range(n)]
+    ws = torch.empty(espn.espn_batches_workspace_bytes(table, n, w.B, w.Q, w.K, w.k), dtype=torch.uint8, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        espn.espn_rerank_batches(table, q_buf, c_buf, w.k, ids_buf, sc_buf, workspace=ws)
+    for rep in range(4):
+        which = rep % 2
+        for i in range(n):
+            q_buf[i].copy_(sets[which][i][0])
+            c_buf[i].copy_(sets[which][i][1])
+            ids_buf[i].fill_(-3)
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(n):
+            assert torch.equal(ids_buf[i], eager[which][i][0]) and torch.equal(sc_buf[i], eager[which][i][1]), (rep, i)
+        again = espn.espn_rerank_batches(table, [x[0] for x in sets[which]], [x[1] for x in sets[which]], w.k)   # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(again[0][3], eager[which][3][0])
+    espn.espn_table_check(table)
+    del graph
+    table.free()
+
+
 def test_two_tables_and_two_streams_do_not_disturb_each_other():
     say("two tables, two streams")
     wa = synth.scaled(synth.WORKLOADS["c1"], n_docs=2000)
