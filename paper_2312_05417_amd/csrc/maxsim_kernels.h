@@ -159,7 +159,9 @@ __device__ __forceinline__ float row16_sum(float v)
 //   D = 32   a 16-row tile is 1 KiB; lane l loads bytes [16 l, 16 l + 16) of it (one fully
 //            coalesced, non-temporal instruction), then four ds_bpermute_b32 move chunk c of row r
 //            from lane 4r + c to lane r + 16c.  Loading in the MFMA layout directly (16 B per lane at
-//            a 64 B stride) was measured ~30 % slower on the same gather.
+//            a 64 B stride) was measured ~30 % slower on the same gather.  Tiles of binary16 rows start
+//            on 128-byte lines: a document that starts in the middle of a line takes the row before it
+//            into its first tile and never uses it (the bpermute source is clamped from below as well).
 //   D >= 64  two ways (template argument LINEAR), chosen per launch by the host:
 //            LINEAR  the tile, 16 * D * EB contiguous bytes, is loaded lane-linearly, 1 KiB per
 //            instruction, so that every cache line is asked for exactly once and by one
@@ -209,8 +211,9 @@ constexpr int RANK_MAX = 256;        // candidates per query at most for ranking
 
 // Position of a wave in the sequence of tiles it streams (wave-uniform).
 struct DocCursor {
-    int64_t row0;       // first table row of the current document
-    int t;              // its row count
+    int64_t row0;       // first table row of the current document (ALIGN: of the cache line it starts in)
+    int t;              // its row count (ALIGN: counted from row0, i.e. with the `lead` rows before it)
+    int lead;           // ALIGN: rows of the first tile that precede the document (they share its first cache line)
     int tile;           // first row of the current tile (a multiple of the rows per tile)
     int idx;            // index of the current document in the slice
     bool done;          // moved past the last tile (position stays on the last tile)
@@ -327,6 +330,12 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const int Q = bt.Q, K = bt.K;
+    // 64-byte binary16 rows: tiles start on 128-byte lines (a document that starts in the middle of a line takes
+    // the row before it into its first tile and ignores it), so that no line is part of two tiles: a tile's load
+    // is non-temporal, and a line that two tiles share was fetched twice (2.6 % of the bytes; a queue of 400
+    // batches of 64 queries: 25.7 instead of 26.0 us per batch, measured twice each on one machine).  32-byte
+    // rows (E4M3) lose by it: more tiles per document.
+    constexpr bool ALIGN = D == 32 && EB == 2;
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     constexpr int TR = TileBuf<D, EB>::ROWS;   // rows per load tile
     const int lane = threadIdx.x & 63;
@@ -376,6 +385,12 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         if (wave < n) locate_document(src, id_own, nullptr, row0, ntok);   // flags are raised by the table fill
         ld.t = __builtin_amdgcn_readfirstlane(ntok);
         ld.row0 = readlane64(row0, 0);
+        ld.lead = 0;
+        if constexpr (ALIGN) {
+            ld.lead = ld.t > 0 ? (int)(ld.row0 & 1) : 0;
+            ld.row0 -= ld.lead;
+            ld.t += ld.lead;
+        }
     }
     const bool own_first = ld.t > 0;
     TileBuf<D, EB> buf[P];
@@ -435,6 +450,12 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         cur.t = __builtin_amdgcn_readfirstlane(s_ntok[i]);
         cur.row0 = readlane64(s_row0[i], 0);
         cur.tile = 0;
+        cur.lead = 0;
+        if constexpr (ALIGN) {          // (only documents with rows are entered)
+            cur.lead = (int)(cur.row0 & 1);
+            cur.row0 -= cur.lead;
+            cur.t += cur.lead;
+        }
     };
 
     // The load cursor runs P tiles ahead of the compute cursor; lane (s & 63) of `ring` remembers
@@ -524,7 +545,8 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                         if constexpr (D == 32) {
                             // lane (r, c) takes piece c of tile row min(r, rows-1) from lane 4*row + c
                             const int rows = min(16, cs.t - cs.tile);
-                            const int from = (4 * min(r, rows - 1) + c) * 4;
+                            const int first = cs.tile == 0 ? cs.lead : 0;      // ALIGN: the row before the document is not its own
+                            const int from = (4 * max(min(r, rows - 1), first) + c) * 4;
                             unsigned w[TileBuf<D, EB>::NW];
 #pragma unroll
                             for (int x = 0; x < TileBuf<D, EB>::NW; ++x)
