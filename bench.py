@@ -435,6 +435,17 @@ class HbmCase:
         self.table.free()
 
 
+def host_memory_available():
+    """MemAvailable of /proc/meminfo in bytes, or None."""
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable:"):
+                return int(line.split()[1]) * 1024
+    except OSError:
+        pass
+    return None
+
+
 def release_pinned_cache(torch):
     """Pinned host blocks that torch has freed stay pinned in its allocator's cache; this machine pins 64 GiB per
     process at most, so they are handed back before a table is pinned."""
@@ -484,6 +495,11 @@ def run_host_resident(args, key, seed, steps, warmup):
             log("cannot pin %.1f GB for %d docs (%s)" % (rows * row_bytes / 1e9, w.n_docs, str(exc).splitlines()[0]))
             if key != "c5pinned":
                 # the stated size, then, in ordinary host memory: only the host can read it, so the host packs
+                free = host_memory_available()
+                if free is not None and rows * row_bytes + (48 << 30) > free:
+                    log("only %.0f GB of host memory are free: shrinking the table by 20 %%" % (free / 1e9))
+                    w = synth.scaled(w, n_docs=int(w.n_docs * 0.8))
+                    continue
                 emb = torch.empty((rows, w.dim), dtype=dtype)
                 pinned, engine = False, "packed"
                 break
@@ -802,9 +818,23 @@ def main():
 
     # ---- HBM-resident workloads: set all of them up, then their timed regions back to back
     tables, cases, results = {}, [], {}
+
+    def guarded(key, fn):
+        """Runs fn(); a failure of a configuration beside the headline is reported in its place, not raised."""
+        try:
+            return fn()
+        except Exception as exc:        # noqa: BLE001
+            if key == keys[0]:
+                raise
+            log("%s failed: %r" % (key, exc))
+            results[key] = {"config": {"workload": key}, "error": repr(exc)}
+            return None
+
     for key in keys:
         if key not in HOST_WORKLOADS:
-            cases.append(HbmCase(args, key, seed, steps_of(key), warmup_of(key), tables))
+            c = guarded(key, lambda: HbmCase(args, key, seed, steps_of(key), warmup_of(key), tables))
+            if c is not None:
+                cases.append(c)
     woken = 0
     if cases and wake_ms > 0:
         c = cases[0]
@@ -814,14 +844,17 @@ def main():
                 c.rerank(woken + i)
             torch.cuda.synchronize()
             woken += 4
-    for c in cases:
+
+    def timed_part(c):
         if args.kernels_only:
             c.legs()
             c.batched = False
             c.wall, c.ms_per_step = c.sequential_wall_ms * 1e-3 * c.steps, c.sequential_wall_ms
         else:
             c.timed()
-    for c in cases:
+        return True
+
+    def rest(c):
         if not args.kernels_only:
             c.legs()
         if not args.no_cpu_baseline:
@@ -830,15 +863,27 @@ def main():
         results[c.key]["wake_up_steps"] = woken if c is cases[0] else 0
         if args.kernels_only:
             results[c.key]["config"]["entry_point"] = "espn_rerank, one call per batch on one stream (--kernels-only)"
+        return True
+
+    cases = [c for c in cases if guarded(c.key, lambda: timed_part(c))]
+    for c in cases:
+        guarded(c.key, lambda: rest(c))
         c.free()
     del cases
     tables.clear()
     torch.cuda.empty_cache()
 
-    # ---- host-resident workloads, one after the other (each holds up to 156 GB of host memory)
+    # ---- host-resident workloads, one after the other (each holds up to 156 GB of host memory).  A failure in one
+    # of the configurations beside the headline is reported in its place and does not cost the line.
     for key in keys:
         if key in HOST_WORKLOADS:
-            results[key] = run_host_resident(args, key, seed, steps_of(key), args.warmup if args.warmup is not None else 1)
+            try:
+                results[key] = run_host_resident(args, key, seed, steps_of(key), args.warmup if args.warmup is not None else 1)
+            except Exception as exc:        # noqa: BLE001
+                if key == keys[0]:
+                    raise
+                log("%s failed: %r" % (key, exc))
+                results[key] = {"config": {"workload": key}, "error": repr(exc)}
             torch.cuda.empty_cache()
 
     head = results[keys[0]]

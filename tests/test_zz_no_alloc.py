@@ -80,3 +80,38 @@ def test_noalloc_refuses_more_pairs_than_the_scratch_holds():
     torch.cuda.synchronize()
     espn.espn_table_check(table)
     table.free()
+
+
+def test_noalloc_inside_a_captured_graph():
+    """What the entry point is for: a caller under HIP graph capture, where nothing may be allocated.  Replayed
+    with other calls on the shared array in between; every replay against the eager result."""
+    from paper_2312_05417_amd import binding as espn, synth
+    dev = torch.device("cuda:0")
+    w = synth.scaled(synth.WORKLOADS["c2"], n_docs=20000, B=8, K=600)
+    emb, off = synth.table(w, 11, device=dev)
+    table = espn.espn_table_load(emb, off)
+    qs = [synth.queries(w, 11, n, device=dev) for n in range(3)]
+    cs = [torch.from_numpy(synth.candidates(w, 11, n)).to(dev) for n in range(3)]
+    eager = [tuple(t.clone() for t in espn.espn_rerank(table, q, c, w.k)) for q, c in zip(qs, cs)]
+    torch.cuda.synchronize()
+    q_buf, c_buf = qs[0].clone(), cs[0].clone()
+    ids_buf = torch.empty((w.B, w.k), dtype=torch.int64, device=dev)
+    sc_buf = torch.empty((w.B, w.k), dtype=torch.float32, device=dev)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        espn.espn_rerank_noalloc(table, q_buf, c_buf, w.k, ids_buf, sc_buf)
+    other_ids, other_sc = torch.empty_like(ids_buf), torch.empty_like(sc_buf)
+    for rep in range(2):
+        for n in range(3):
+            q_buf.copy_(qs[n])
+            c_buf.copy_(cs[n])
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(ids_buf, eager[n][0]) and torch.equal(sc_buf, eager[n][1]), (rep, n)
+            # an eager call on the same array between replays
+            espn.espn_rerank_noalloc(table, qs[(n + 1) % 3], cs[(n + 1) % 3], w.k, other_ids, other_sc)
+            torch.cuda.synchronize()
+            assert torch.equal(other_ids, eager[(n + 1) % 3][0])
+    espn.espn_table_check(table)
+    del graph
+    table.free()
