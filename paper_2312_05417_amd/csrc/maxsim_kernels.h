@@ -334,8 +334,10 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     // the row before it into its first tile and ignores it), so that no line is part of two tiles: a tile's load
     // is non-temporal, and a line that two tiles share was fetched twice (2.6 % of the bytes; a queue of 400
     // batches of 64 queries: 25.7 instead of 26.0 us per batch, measured twice each on one machine).  32-byte
-    // rows (E4M3) lose by it: more tiles per document.
+    // rows (E4M3) lose 1-3 % by it (measured again in long launches), although a quarter of what they fetch is
+    // such waste: that path is not bound by fetched bytes.
     constexpr bool ALIGN = D == 32 && EB == 2;
+    constexpr int LINE_ROWS = 128 / (D * EB) > 0 ? 128 / (D * EB) : 1;      // rows per 128-byte line
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
     constexpr int TR = TileBuf<D, EB>::ROWS;   // rows per load tile
     const int lane = threadIdx.x & 63;
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         ld.row0 = readlane64(row0, 0);
         ld.lead = 0;
         if constexpr (ALIGN) {
-            ld.lead = ld.t > 0 ? (int)(ld.row0 & 1) : 0;
+            ld.lead = ld.t > 0 ? (int)(ld.row0 & (LINE_ROWS - 1)) : 0;
             ld.row0 -= ld.lead;
             ld.t += ld.lead;
         }
@@ -452,7 +454,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         cur.tile = 0;
         cur.lead = 0;
         if constexpr (ALIGN) {          // (only documents with rows are entered)
-            cur.lead = (int)(cur.row0 & 1);
+            cur.lead = (int)(cur.row0 & (LINE_ROWS - 1));
             cur.row0 -= cur.lead;
             cur.t += cur.lead;
         }
@@ -529,8 +531,9 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         const int rows = min(TR, cs.t - cs.tile);
+                        const int first = cs.tile == 0 ? cs.lead : 0;          // ALIGN: rows before the document are not its own
                         const uint2 *pieces = reinterpret_cast<const uint2 *>(scr);
-                        const uint2 lo = pieces[4 * min(r, rows - 1) + c];
+                        const uint2 lo = pieces[4 * max(min(r, rows - 1), first) + c];
                         const uint2 hi = pieces[4 * min(16 + r, rows - 1) + c];
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                         __builtin_amdgcn_wave_barrier();
