@@ -191,7 +191,8 @@ int espn_rerank(espn_table *table, const void *q, const int64_t *cand,
  * own (created with the table, default priority), so that the ranking of one chunk and the start of the next
  * overlap with the streaming of the one before.  The library's streams wait for everything enqueued on `stream`
  * before the call (nothing, if it is idle), and `stream` waits for all of the call's batches: to the caller it is
- * one asynchronous operation on `stream`, results valid when it is through.
+ * one asynchronous operation on `stream`, results valid when it is through.  The call may be captured into a HIP
+ * graph (the hand-over to the library's streams and back becomes graph edges).
  *
  *   q, cand, out_ids, out_scores  HOST arrays of n_batches DEVICE pointers, each as in espn_rerank; the arrays
  *                                 themselves are read before the call returns.
