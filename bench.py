@@ -446,6 +446,22 @@ def host_memory_available():
     return None
 
 
+def advise_huge_pages(t):
+    """Ask for transparent huge pages under a large host tensor before it is first touched (the packing engine
+    reads documents from all over a 156 GB table: fewer TLB misses).  Best effort."""
+    import ctypes
+    try:
+        libc = ctypes.CDLL(None, use_errno=True)
+        page = 2 << 20
+        start = (t.data_ptr() + page - 1) // page * page
+        length = (t.data_ptr() + t.numel() * t.element_size() - start) // page * page
+        if length > 0:
+            rc = libc.madvise(ctypes.c_void_p(start), ctypes.c_size_t(length), 14)      # MADV_HUGEPAGE
+            log("madvise(MADV_HUGEPAGE) on %.1f GB: %s" % (length / 1e9, "ok" if rc == 0 else "errno %d" % ctypes.get_errno()))
+    except Exception as exc:        # noqa: BLE001
+        log("madvise not available: %r" % (exc,))
+
+
 def release_pinned_cache(torch):
     """Pinned host blocks that torch has freed stay pinned in its allocator's cache; this machine pins 64 GiB per
     process at most, so they are handed back before a table is pinned."""
@@ -501,6 +517,7 @@ def run_host_resident(args, key, seed, steps, warmup):
                     w = synth.scaled(w, n_docs=int(w.n_docs * 0.8))
                     continue
                 emb = torch.empty((rows, w.dim), dtype=dtype)
+                advise_huge_pages(emb)
                 pinned, engine = False, "packed"
                 break
             if w.n_docs < 200_000:
