@@ -29,6 +29,8 @@ def say(msg):
     ("c2", dict(n_docs=40_000, B=24, K=1000), 35),            # the same with two launches per chunk
     ("c2", dict(n_docs=20_000, B=40, K=64, k=64), 20),        # every rank of a short list, two chunks of 10
     ("c1", dict(k=40), 5),                                    # more ranks than the one-wave kernel takes: sorted per batch
+    ("c1", dict(B=5), 3),                                     # 15 queries in the launch: not a multiple of eight
+    ("c3", dict(n_docs=5_000, B=3, K=70, Q=48), 11),          # 33 queries of 48 rows
 ])
 def test_a_queue_of_batches_matches_the_oracle_and_single_calls(key, changes, n_batches):
     w = synth.scaled(synth.WORKLOADS[key], **changes)
@@ -49,6 +51,48 @@ def test_a_queue_of_batches_matches_the_oracle_and_single_calls(key, changes, n_
         one_ids, one_top = espn.espn_rerank(table, qs_d[n], cands_d[n], w.k)
         assert torch.equal(one_ids, ids[n]), n
         assert np.array_equal(one_top.cpu().numpy().view(np.int32), tops[n].cpu().numpy().view(np.int32)), n
+    table.free()
+
+
+def test_empty_documents_and_bad_ids_in_a_fused_launch():
+    """The degenerate cases of the method inside a launch that scores several batches: an empty document scores
+    -inf and ranks last, an id outside the table scores -inf, is never read, and is reported by espn_table_check."""
+    say("batches: empty documents, ids out of range")
+    rng = np.random.default_rng(3)
+    counts = rng.integers(0, 40, size=600)
+    counts[::7] = 0                                           # every seventh document is empty
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    emb = rng.normal(size=(int(off[-1]), 32)).astype(np.float16)
+    table = espn.espn_table_load(torch.from_numpy(emb).to(DEV), off)
+    B, K, k, n_batches = 6, 32, 32, 5
+    qs = [rng.normal(size=(B, 32, 32)).astype(np.float16) for _ in range(n_batches)]
+    cands = [np.stack([rng.permutation(600)[:K] for _ in range(B)]).astype(np.int64) for _ in range(n_batches)]
+    assert espn.espn_batches_plan(table, n_batches, B, 32, K, k)["launches"] == 1
+    ids, tops = espn.espn_rerank_batches(table, [torch.from_numpy(q).to(DEV) for q in qs],
+                                         [torch.from_numpy(c).to(DEV) for c in cands], k)
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    for n in range(n_batches):
+        o_all = oracle.scores(emb, off, qs[n], cands[n])
+        for b in range(B):
+            got_ids, got_top = ids[n][b].cpu().numpy(), tops[n][b].cpu().numpy()
+            assert_topk_matches(got_ids, got_top, o_all[b], cands[n][b], k, 32)
+            n_empty = int((counts[cands[n][b]] == 0).sum())
+            assert np.isneginf(got_top[K - n_empty:]).all() and np.isfinite(got_top[:K - n_empty]).all()
+            assert np.array_equal(got_ids[K - n_empty:], np.sort(cands[n][b][counts[cands[n][b]] == 0]))
+    # two ids outside the table, in different batches of the launch
+    bad = [c.copy() for c in cands]
+    bad[1][2, 5] = 600
+    bad[4][0, 0] = -1
+    ids, tops = espn.espn_rerank_batches(table, [torch.from_numpy(q).to(DEV) for q in qs],
+                                         [torch.from_numpy(c).to(DEV) for c in bad], k)
+    torch.cuda.synchronize()
+    with pytest.raises(espn.EspnError) as ei:
+        espn.espn_table_check(table)
+    assert ei.value.status == espn.ESPN_ERR_ID_RANGE
+    assert int(ids[1][2][-1]) == 600 and np.isneginf(float(tops[1][2][-1]))       # the largest id among the -inf entries
+    assert int(ids[4][0][K - 1 - int((counts[bad[4][0][1:]] == 0).sum())]) == -1   # the smallest id among them
+    espn.espn_table_check(table)                                                   # the flag is cleared by the report
     table.free()
 
 
