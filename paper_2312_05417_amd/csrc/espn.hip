@@ -15,6 +15,7 @@
 
 #include "../../include/espn.h"
 #include "maxsim_kernels.h"
+#include "order_kernels.h"
 #include "staging_kernels.h"
 #include "topk_kernels.h"
 
@@ -208,6 +209,8 @@ struct espn_table {
     float *share_host = nullptr;       // owned, pinned: where espn_table_sample's kernel leaves its result
     float *share_dev = nullptr;        // the same word as the device sees it
     float overlap = -1.f;              // the last espn_table_sample result (-1: none yet); read by plan_slices
+    unsigned *popular_dev = nullptr;   // owned, one bit per document: listed by many queries of the sampled batch
+    bool popular_valid = false;        // the last sample found overlapping lists and filled popular_dev
     hipStream_t lane[ESPN_BATCH_LANES] = {};      // owned: the streams espn_rerank_batches spreads its batches over
     hipEvent_t fork = nullptr;                    // owned: the caller's stream has reached the call
     hipEvent_t joined[ESPN_BATCH_LANES] = {};     // owned: a lane has finished the call's batches
@@ -419,11 +422,26 @@ ESPN_API int espn_table_free(espn_table *table)
     (void)hipFree(table->err_dev);
     (void)hipFree(table->scale_dev);
     if (table->share_host) (void)hipHostFree(table->share_host);
+    (void)hipFree(table->popular_dev);
     destroy_lanes(table);
     delete[] table->off_host;
     delete table;
     return ESPN_OK;
 }
+
+namespace {
+// Lists of a batch are taken to share documents if more than this fraction of a sample of 4096 pairs repeats a
+// document of the sample (uniform lists over 2 M documents: 0.002; Zipf(1.1) lists: above 0.5)
+constexpr float kShareThreshold = 0.05f;
+// ... and a document is popular (fetched through the caches by launches that stream the rest) if at least this many
+// of the sampled batch's lists name it, and at least one list in kPopularShare.  (2048 Zipf(1.1) lists of 1000 over
+// 2 M documents, the 3 000 to 30 000 most listed documents marked: the same speed to within 2 %; 100 000: 3 % slower.)
+constexpr int kPopularListings = 2;
+constexpr int kPopularShare = 256;
+// Launches of at least this many workgroups per compute unit take lists that overlap in id order (the ordering pass
+// is a launch of its own, of about 1 % of such a scoring launch)
+constexpr int kOrderFrom = 4;
+}  // namespace
 
 ESPN_API int espn_table_set_fetch(espn_table *table, int32_t mode)
 {
@@ -457,6 +475,28 @@ ESPN_API int espn_table_sample(espn_table *table, const int64_t *cand, int32_t B
     }
     HIP_TRY(hipStreamSynchronize(st));
     table->overlap = *static_cast<volatile const float *>(table->share_host);
+    // overlapping lists: which documents they keep coming back to
+    table->popular_valid = false;
+    if (table->overlap >= kShareThreshold && table->residency == ESPN_RESIDENT_HBM) {
+        const int64_t words = (table->n_docs + 31) / 32;
+        if (!table->popular_dev) HIP_TRY(hipMalloc(&table->popular_dev, sizeof(unsigned) * (size_t)words));
+        unsigned *counts = nullptr;
+        HIP_TRY(hipMalloc(&counts, sizeof(unsigned) * (size_t)table->n_docs));
+        const int64_t n_pairs = (int64_t)B * K;
+        const unsigned at_least = (unsigned)std::max(kPopularListings, B / kPopularShare);
+        hipError_t e = hipMemsetAsync(counts, 0, sizeof(unsigned) * (size_t)table->n_docs, st);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(espn::listings_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, cand,
+                               n_pairs, K, K, table->n_docs, counts);
+            hipLaunchKernelGGL(espn::popular_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, counts,
+                               table->n_docs, at_least, table->popular_dev);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        (void)hipFree(counts);
+        HIP_TRY(e);
+        table->popular_valid = true;
+    }
     return ESPN_OK;
 }
 
@@ -499,9 +539,6 @@ constexpr int kNarrowWaves = 8;
 // compute unit instead of two of 8 (measured: c3 764 -> 760 us, c4 4.80 -> 4.68 ms; E4M3 rows of the
 // same length lose 4 % with it and keep 8 waves).
 constexpr int kNarrowWaves128 = 4;
-// Lists of a batch are taken to share documents if more than this fraction of a sample of 4096 pairs repeats a
-// document of the sample (uniform lists over 2 M documents: 0.002; Zipf(1.1) lists: above 0.5)
-constexpr float kShareThreshold = 0.05f;
 
 // The planner's numbers, all per compute unit (n_cu comes from the device) or per workgroup:
 constexpr int kResidentPerCu = 2;        // workgroups of the scoring kernel a compute unit holds at once (32 waves: 2 x 16 or 2 x 8 + registers)
@@ -810,12 +847,13 @@ int enqueue_score(const espn_table *t, const espn::DocSource &src, const espn::B
 // A batch whose lists are scored whole, without a prior.
 espn::Batch plain_batch(const void *q, const int64_t *cand, int Q, int K)
 {
-    return espn::Batch{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, K};
+    return espn::Batch{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, K, 0};
 }
 
 espn::DocSource hbm_source(const espn_table *t)
 {
-    return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs, t->scale_dev};
+    return espn::DocSource{t->emb, t->off_dev, nullptr, nullptr, t->n_docs, t->scale_dev,
+                           t->popular_valid ? t->popular_dev : nullptr};
 }
 
 // Whole-list sort of n <= kSortMax entries per query (one list, or two taken together).
@@ -925,17 +963,29 @@ ESPN_API int espn_topk(const float *scores, const int64_t *cand, int32_t B, int3
     return enqueue_topk(scores, cand, K, B, K, k, k, out_ids, out_scores, static_cast<hipStream_t>(stream));
 }
 
-ESPN_API size_t espn_workspace_bytes(int32_t B, int32_t K)
+namespace {
+// the two parts of a batch's workspace: its scores [B, K], then its lists in id order [B, K] (8 bytes per entry)
+size_t score_bytes(int32_t B, int32_t K)
 {
     if (B <= 0 || K <= 0) return kAlign;
     const size_t bytes = sizeof(float) * (size_t)B * (size_t)K;
     return (bytes + kAlign - 1) / kAlign * kAlign;
 }
+size_t order_bytes(int32_t B, int32_t K)
+{
+    if (B <= 0 || K <= 0) return 0;
+    const size_t bytes = sizeof(int64_t) * (size_t)B * (size_t)K;
+    return (bytes + kAlign - 1) / kAlign * kAlign;
+}
+}  // namespace
+
+ESPN_API size_t espn_workspace_bytes(int32_t B, int32_t K) { return score_bytes(B, K) + order_bytes(B, K); }
 
 namespace {
 int check_rerank_outputs(int32_t B, int32_t K, int32_t k, const int64_t *out_ids, const float *out_scores,
-                         const void *workspace, size_t workspace_bytes)
+                         const void *workspace, size_t workspace_bytes, bool scores_only = false)
 {
+    const size_t needed = scores_only ? score_bytes(B, K) : espn_workspace_bytes(B, K);
     if (k < 0) return fail(ESPN_ERR_ARG, "k = %d is negative", k);
     if (k > K) return fail(ESPN_ERR_SHAPE, "k = %d exceeds K = %d", k, K);
     if (B > 0 && k > 0 && (!out_ids || !out_scores)) return fail(ESPN_ERR_ARG, "output pointer is NULL");
@@ -943,9 +993,8 @@ int check_rerank_outputs(int32_t B, int32_t K, int32_t k, const int64_t *out_ids
         if (!workspace) return fail(ESPN_ERR_ARG, "workspace is NULL");
         if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
             return fail(ESPN_ERR_ARG, "workspace is not %zu-byte aligned", kAlign);
-        if (workspace_bytes < espn_workspace_bytes(B, K))
-            return fail(ESPN_ERR_SHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes,
-                        espn_workspace_bytes(B, K));
+        if (workspace_bytes < needed)
+            return fail(ESPN_ERR_SHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes, needed);
     }
     return ESPN_OK;
 }
@@ -953,10 +1002,37 @@ int check_rerank_outputs(int32_t B, int32_t K, int32_t k, const int64_t *out_ids
 
 namespace {
 
+// Whether a batch of whole lists, planned as `plan`, is scored in id order (an ordering launch first): the table
+// is in HBM, a sample has shown lists that overlap (and named the popular documents), and the scoring launch is
+// long - many workgroups per compute unit, taken slice by slice.
+bool scored_in_id_order(const espn_table *t, const SlicePlan &plan, int B, int Q, int K)
+{
+    return t->popular_valid && t->residency == ESPN_RESIDENT_HBM && on_matrix_cores(t, Q) && !plan.linear && !plan.rank &&
+           plan.slices > 1 && K <= kSortMax && (int64_t)B * plan.slices >= (int64_t)kOrderFrom * t->n_cu &&
+           t->n_docs < ((int64_t)1 << (63 - espn::SLOT_BITS));
+}
+
+int enqueue_order(const int64_t *cand, int B, int K, int64_t n_docs, int64_t *ordered, hipStream_t st)
+{
+    using namespace espn;
+    if (K <= 256) hipLaunchKernelGGL((order_lists_kernel<256, 64>), dim3(B), dim3(64), 0, st, cand, K, K, n_docs, ordered);
+    else if (K <= 1024) hipLaunchKernelGGL((order_lists_kernel<1024, 256>), dim3(B), dim3(256), 0, st, cand, K, K, n_docs, ordered);
+    else if (K <= 2048) hipLaunchKernelGGL((order_lists_kernel<2048, 512>), dim3(B), dim3(512), 0, st, cand, K, K, n_docs, ordered);
+    else hipLaunchKernelGGL((order_lists_kernel<4096, 512>), dim3(B), dim3(512), 0, st, cand, K, K, n_docs, ordered);
+    HIP_TRY(hipGetLastError());
+    return ESPN_OK;
+}
+const char *order_kernel_name(int K)
+{
+    return K <= 256 ? "espn::order_lists_kernel<256, 64>" : K <= 1024 ? "espn::order_lists_kernel<1024, 256>" :
+           K <= 2048 ? "espn::order_lists_kernel<2048, 512>" : "espn::order_lists_kernel<4096, 512>";
+}
+
 // Score bt.K candidates per query into the workspace and write the first k of their ranking to
 // rows of leading dimension ldo: in one launch where the scoring kernel can rank, else in two.
+// `ordered`: room for the batch's lists in id order ([B, K] entries of 8 bytes), or nullptr: scored as they come.
 int enqueue_rerank(espn_table *t, const espn::DocSource &src, const espn::Batch &bt, int B, int k, int ldo,
-                   int64_t *out_ids, float *out_scores, void *workspace, hipStream_t st)
+                   int64_t *out_ids, float *out_scores, void *workspace, int64_t *ordered, hipStream_t st)
 {
     if (B == 0 || bt.K == 0) return ESPN_OK;
     float *scores = static_cast<float *>(workspace);
@@ -964,7 +1040,13 @@ int enqueue_rerank(espn_table *t, const espn::DocSource &src, const espn::Batch 
     if (!on_matrix_cores(t, bt.Q)) plan.rank = false;
     if (src.row_map) plan.linear = false;    // a staging slot holds each document once for all the queries that list it
     const espn::RankOut ro{k, ldo};
-    if (int rc = enqueue_score(t, src, bt, one_batch(bt, B, scores, out_ids, out_scores), plan, ro, st)) return rc;
+    espn::Batch scored = bt;
+    if (ordered && !src.row_map && !bt.prior && bt.ldc == bt.K && scored_in_id_order(t, plan, B, bt.Q, bt.K)) {
+        if (int rc = enqueue_order(bt.cand, B, bt.K, t->n_docs, ordered, st)) return rc;
+        scored.cand = ordered;
+        scored.order = espn::ORDER_BY_ID;
+    }
+    if (int rc = enqueue_score(t, src, scored, one_batch(scored, B, scores, out_ids, out_scores), plan, ro, st)) return rc;
     if (plan.rank) return ESPN_OK;
     return enqueue_topk(scores, bt.cand, bt.ldc, B, bt.K, k, ldo, out_ids, out_scores, st);
 }
@@ -986,7 +1068,7 @@ ESPN_API int espn_rerank_plan(const espn_table *table, int32_t B, int32_t Q, int
             plan.slices = K;                 // the generic kernel: one wave per candidate, never ranks
             plan.slice = 1;
         }
-        n = 1 + ((k > 0 && !plan.rank) ? 1 : 0);
+        n = 1 + ((k > 0 && !plan.rank) ? 1 : 0) + (scored_in_id_order(table, plan, B, Q, K) ? 1 : 0);
     }
     if (slices) *slices = plan.slices;
     if (slice) *slice = plan.slice;
@@ -1009,6 +1091,10 @@ void kernel_names(const espn_table *table, int queries, int Q, int K, int k, boo
                  plan.rank ? "true" : "false", QG, plan.linear ? "true" : "false");
     } else {
         snprintf(text, len, "espn::maxsim_generic_kernel");
+    }
+    if (!fused && on_matrix_cores(table, Q) && scored_in_id_order(table, plan_slices(table, queries, K, k), queries, Q, K)) {
+        const size_t at = std::strlen(text);
+        snprintf(text + at, len - at, ";%s", order_kernel_name(K));
     }
     if (k > 0 && !ranked) {
         const size_t at = std::strlen(text);
@@ -1051,8 +1137,9 @@ ESPN_API int espn_rerank(espn_table *table, const void *q, const int64_t *cand, 
     if (table->residency != ESPN_RESIDENT_HBM)
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
     hipStream_t st = static_cast<hipStream_t>(stream);
+    int64_t *ordered = reinterpret_cast<int64_t *>(static_cast<uint8_t *>(workspace) + score_bytes(B, K));
     return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace,
-                          st);
+                          ordered, st);
 }
 
 namespace {
@@ -1152,7 +1239,7 @@ ESPN_API int espn_rerank_batches(espn_table *table, int32_t n_batches, const voi
     auto run_chunk = [&](int first, int count, uint8_t *ws, hipStream_t on) -> int {
         if (count == 1)
             return enqueue_rerank(table, src, plain_batch(q[first], cand[first], Q, K), B, k, k, ranked ? out_ids[first] : nullptr,
-                                  ranked ? out_scores[first] : nullptr, ws, on);
+                                  ranked ? out_scores[first] : nullptr, ws, reinterpret_cast<int64_t *>(ws + score_bytes(B, K)), on);
         const espn::Batch shape = plain_batch(nullptr, nullptr, Q, K);
         espn::BatchSet set{};
         espn::TopkSet lists{};
@@ -1227,13 +1314,13 @@ ESPN_API int espn_rerank_noalloc(espn_table *table, const void *q, const int64_t
         return fail(ESPN_ERR_SHAPE, "B * K = %lld pairs exceed the %lld the static scratch holds", (long long)B * K,
                     (long long)ESPN_NOALLOC_MAX_PAIRS);
     void *ws = table->static_scratch;
-    if (int rc = check_rerank_outputs(B, K, k, out_ids, out_scores, ws, sizeof(float) * (size_t)ESPN_NOALLOC_MAX_PAIRS))
+    if (int rc = check_rerank_outputs(B, K, k, out_ids, out_scores, ws, sizeof(float) * (size_t)ESPN_NOALLOC_MAX_PAIRS, true))
         return rc;
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     if (table->residency != ESPN_RESIDENT_HBM)
         return fail(ESPN_ERR_UNSUPPORTED, "table is host-resident: use espn_prefetch + espn_rerank_staged");
-    return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, ws,
+    return enqueue_rerank(table, hbm_source(table), plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, ws, nullptr,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -1253,8 +1340,8 @@ ESPN_API int espn_rerank_partial(espn_table *table, const void *q, const int64_t
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const espn::Batch bt{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, R};
-    if (int rc = enqueue_rerank(table, hbm_source(table), bt, B, std::min(k, R), k, out_ids, out_scores, workspace, st))
+    const espn::Batch bt{static_cast<const uint16_t *>(q), cand, nullptr, 0.f, K, Q, R, 0};
+    if (int rc = enqueue_rerank(table, hbm_source(table), bt, B, std::min(k, R), k, out_ids, out_scores, workspace, nullptr, st))
         return rc;
     if (B > 0 && k > R) {
         hipLaunchKernelGGL(espn::append_unranked_kernel, dim3(B, (k - R + 255) / 256), dim3(256), 0, st, cand, K, R, k,
@@ -1276,8 +1363,8 @@ ESPN_API int espn_rerank_prior(espn_table *table, const void *q, const int64_t *
     DeviceScope scope(table->device);
     if (!scope.ok) return fail(ESPN_ERR_HIP, "cannot select device %d", table->device);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const espn::Batch bt{static_cast<const uint16_t *>(q), cand, prior, alpha, K, Q, K};
-    return enqueue_rerank(table, hbm_source(table), bt, B, k, k, out_ids, out_scores, workspace, st);
+    const espn::Batch bt{static_cast<const uint16_t *>(q), cand, prior, alpha, K, Q, K, 0};
+    return enqueue_rerank(table, hbm_source(table), bt, B, k, k, out_ids, out_scores, workspace, nullptr, st);
 }
 
 ESPN_API int espn_merge_topk(const int64_t *ids_a, const float *scores_a, int32_t ka, const int64_t *ids_b,
@@ -1652,8 +1739,8 @@ ESPN_API int espn_rerank_staged(espn_table *table, int32_t slot, const void *q, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     StagingSlot &s = table->slot[slot];
     HIP_TRY(hipStreamWaitEvent(st, s.ready, 0));
-    const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs, table->scale_dev};
-    if (int rc = enqueue_rerank(table, src, plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace, st))
+    const espn::DocSource src{s.rows, table->off_dev, s.row_map, s.bits, table->n_docs, table->scale_dev, nullptr};
+    if (int rc = enqueue_rerank(table, src, plain_batch(q, cand, Q, K), B, k, k, out_ids, out_scores, workspace, nullptr, st))
         return rc;
     HIP_TRY(hipEventRecord(s.consumed, st));
     return ESPN_OK;

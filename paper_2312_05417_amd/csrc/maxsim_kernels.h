@@ -37,12 +37,29 @@ struct DocSource {
     const unsigned *staged_bits;
     int64_t n_docs;
     const float *doc_scale;        // nullptr: binary16 rows
+    const unsigned *popular;       // one bit per document or nullptr: see is_popular()
 };
+
+// Documents that many queries of a batch list (Sec. 4.2 observes that candidate lists of nearby queries repeat
+// documents; a sample of the workload's lists names them) are fetched through the caches, where a later query of
+// the launch finds them; the others are streamed past the caches (each of their lines is wanted once) and so leave
+// the popular ones there.  No map: every document goes through the caches.
+__device__ __forceinline__ bool is_popular(const DocSource &src, int64_t id)
+{
+    if (src.popular == nullptr || id < 0 || id >= src.n_docs) return true;
+    return ((src.popular[id >> 5] >> (id & 31)) & 1u) != 0u;
+}
 
 // One batch of queries and their candidate lists.
 //   cand  [B, ldc] ids, of which the first K of every row are scored (ldc >= K: partial re-ranking
 //         scores a prefix of each list)
 //   prior [B, ldc] first-stage scores or nullptr; score = MaxSim + alpha * prior (Sec. 3.1)
+//   order ORDER_BY_ID: `cand` is not the caller's list but order_lists_kernel's copy of it, each list sorted by
+//         document id, an entry = id << SLOT_BITS | position in the caller's list (ldc = K, no prior); scores go
+//         to the caller's positions.  The workgroups then run slice by slice (the first slice of every query,
+//         then the second ...), not query by query: the workgroups resident at one time walk the same range of
+//         ids in the same direction, so a document that several of them list is asked for by all of them within
+//         a short time, and only the first request leaves the L2.
 struct Batch {
     const uint16_t *q;      // [B, Q, D]
     const int64_t *cand;
@@ -51,7 +68,11 @@ struct Batch {
     int ldc;
     int Q;
     int K;
+    int order;              // 0 or ORDER_BY_ID
 };
+constexpr int ORDER_BY_ID = 1;
+constexpr int SLOT_BITS = 20;                               // lists of up to 2^20 entries, ids below 2^43
+constexpr int64_t SLOT_MASK = ((int64_t)1 << SLOT_BITS) - 1;
 
 __device__ __forceinline__ float with_prior(const Batch &bt, int b, int j, float maxsim)
 {
@@ -217,6 +238,7 @@ struct DocCursor {
     int tile;           // first row of the current tile (a multiple of the rows per tile)
     int idx;            // index of the current document in the slice
     bool done;          // moved past the last tile (position stays on the last tile)
+    bool cached;        // the document is fetched through the caches (rows of 128 bytes and more: in the MFMA layout)
     __device__ __forceinline__ bool last_tile(int rows_per_tile) const { return tile + rows_per_tile >= t; }
 };
 
@@ -239,7 +261,7 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
                                                 const DocCursor &cur, int lane)
 {
     constexpr int ROW = D * EB;                    // bytes per row
-    if constexpr (D > 32 && LINEAR) {
+    if (D > 32 && (LINEAR || !cur.cached)) {
         // lane-linear: the tile is 16 * ROW contiguous bytes; instruction x takes its x-th KiB, lane l the
         // l-th 16-byte piece of that.  Every byte is asked for exactly once, whole cache lines by one
         // instruction each: non-temporal loads.  Past the document's end: the last valid piece.
@@ -260,7 +282,7 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
         const int npiece = min(TileBuf<D, EB>::ROWS, cur.t - cur.tile) * (ROW / 16);
         const uint4v *p = reinterpret_cast<const uint4v *>(emb + ((size_t)cur.row0 + cur.tile) * ROW);
         uint4v v;
-        if constexpr (LINEAR) v = __builtin_nontemporal_load(p + min(lane, npiece - 1));
+        if (LINEAR || !cur.cached) v = __builtin_nontemporal_load(p + min(lane, npiece - 1));
         else v = p[min(lane, npiece - 1)];
         buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
     } else {
@@ -320,13 +342,14 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     __shared__ int64_t s_row0[MAX_SLICE];
     __shared__ int s_ntok[MAX_SLICE];
     __shared__ float s_scale[EB == 1 ? MAX_SLICE : 1];
+    __shared__ int s_slot[MAX_SLICE];       // position in the query's list, | CACHED_BIT: fetched through the caches
     __shared__ int s_next;
     __shared__ RankLds<RANK> s_rank;
     // LINEAR: where a wave turns a tile from the order it was loaded in into the order the MFMA wants;
     // rows are one piece apart from a multiple of the bank period, so that the 16 rows a read touches
     // fall on different banks
     constexpr int ROW_PIECES = D * EB / 16;
-    __shared__ uint4 s_tile[LINEAR && D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : (D == 32 && EB == 1) ? WAVES * 64 : 1];
+    __shared__ uint4 s_tile[D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : (D == 32 && EB == 1) ? WAVES * 64 : 1];
 
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const int Q = bt.Q, K = bt.K;
@@ -339,6 +362,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     constexpr bool ALIGN = D == 32 && EB == 2;
     constexpr int LINE_ROWS = 128 / (D * EB) > 0 ? 128 / (D * EB) : 1;      // rows per 128-byte line
     constexpr int KS = D / 32;              // MFMA steps per 16-row tile
+    constexpr int CACHED_BIT = 1 << 30;
     constexpr int TR = TileBuf<D, EB>::ROWS;   // rows per load tile
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
@@ -350,10 +374,16 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const unsigned slices = (unsigned)((K + slice - 1) / slice);
     const unsigned n_queries = gridDim.x / slices;
     int g = (int)(blockIdx.x / slices), slice_index = (int)(blockIdx.x % slices);      // g: query of the launch
+    const bool by_id = bt.order == ORDER_BY_ID;
+    if (by_id) {                                                // slice by slice
+        g = (int)(blockIdx.x % n_queries);
+        slice_index = (int)(blockIdx.x / n_queries);
+    }
     if ((n_queries & 7u) == 0u) {
         const unsigned within = blockIdx.x >> 3;                // position among the XCD's workgroups
-        g = (int)((blockIdx.x & 7u) + 8u * (within / slices));
-        slice_index = (int)(within % slices);
+        const unsigned per_xcd = n_queries >> 3;                // queries of an XCD
+        g = (int)((blockIdx.x & 7u) + 8u * (by_id ? within % per_xcd : within / slices));
+        slice_index = (int)(by_id ? within / per_xcd : within % slices);
     }
     // which batch of the launch the query belongs to (wave-uniform: the pointers stay in scalar registers)
     const int which = set.n > 1 ? g / set.B : 0;
@@ -377,6 +407,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     int64_t id_own = -1, id_fill = -1;
     if (wave < n) id_own = cand[cand0 + wave];
     if ((int)threadIdx.x < n) id_fill = cand[cand0 + threadIdx.x];
+    if (by_id) id_own >>= SLOT_BITS;                            // (arithmetic: an id out of range is stored as -1)
     DocCursor ld, cs;
     ld.done = true;
     ld.idx = wave;
@@ -388,6 +419,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         ld.t = __builtin_amdgcn_readfirstlane(ntok);
         ld.row0 = readlane64(row0, 0);
         ld.lead = 0;
+        ld.cached = __builtin_amdgcn_readfirstlane((int)is_popular(src, id_own)) != 0;
         if constexpr (ALIGN) {
             ld.lead = ld.t > 0 ? (int)(ld.row0 & (LINE_ROWS - 1)) : 0;
             ld.row0 -= ld.lead;
@@ -403,17 +435,23 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
 
     // descriptors of the slice's documents; a document with nothing to read has its score here
     for (int i = threadIdx.x; i < n; i += WAVES * 64) {
-        const int64_t id = i == (int)threadIdx.x ? id_fill : cand[cand0 + i];
+        int64_t id = i == (int)threadIdx.x ? id_fill : cand[cand0 + i];
+        int slot = j_begin + i;
+        if (by_id) {
+            slot = (int)(id & SLOT_MASK);
+            id >>= SLOT_BITS;
+        }
         int64_t row0;
         int ntok;
         locate_document(src, id, err, row0, ntok);
         s_row0[i] = row0;
         s_ntok[i] = ntok;
+        s_slot[i] = slot | (is_popular(src, id) ? CACHED_BIT : 0);
         if constexpr (EB == 1) s_scale[i] = ntok > 0 ? src.doc_scale[id] : 1.f;
         if constexpr (RANK) s_rank.id[i] = id;
         if (ntok == 0) {
-            const float none = total_of(j_begin + i, neg_inf());
-            scores[(size_t)b * K + j_begin + i] = none;
+            const float none = total_of(slot, neg_inf());
+            scores[(size_t)b * K + slot] = none;
             if constexpr (RANK) s_rank.key[i] = order_key(none);
         }
     }
@@ -453,6 +491,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
         cur.row0 = readlane64(s_row0[i], 0);
         cur.tile = 0;
         cur.lead = 0;
+        cur.cached = (__builtin_amdgcn_readfirstlane(s_slot[i]) & CACHED_BIT) != 0;
         if constexpr (ALIGN) {          // (only documents with rows are entered)
             cur.lead = (int)(cur.row0 & (LINE_ROWS - 1));
             cur.row0 -= cur.lead;
@@ -555,7 +594,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                             for (int x = 0; x < TileBuf<D, EB>::NW; ++x)
                                 w[x] = (unsigned)__builtin_amdgcn_ds_bpermute(from, (int)buf[p].w[x]);
                             a[0] = fragment_of<EB>(w);
-                        } else if constexpr (LINEAR) {         // D > 32
+                        } else if (LINEAR || !cs.cached) {      // D > 32, loaded lane-linearly
                             // piece q of the tile (row q / ROW_PIECES, position q % ROW_PIECES) is in register
                             // group q / 64 of lane q % 64; lane (r, c) wants pieces c * NW/4 .. of row min(r, rows-1)
                             constexpr int NX = TileBuf<D, EB>::NW / 4;
@@ -603,8 +642,9 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                         // one positive scale per document: max and sum commute with it
                         if constexpr (EB == 1) sum *= s_scale[cs.idx];
                         if (lane == 0) {
-                            const float total = total_of(j_begin + cs.idx, sum);
-                            scores[(size_t)b * K + j_begin + cs.idx] = total;
+                            const int slot = s_slot[cs.idx] & ~CACHED_BIT;
+                            const float total = total_of(slot, sum);
+                            scores[(size_t)b * K + slot] = total;
                             if constexpr (RANK) s_rank.key[cs.idx] = order_key(total);
                         }
                     }

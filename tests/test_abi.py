@@ -37,7 +37,7 @@ def test_header_is_plain_c_and_links_from_c(lib, tmp_path):
 #include <string.h>
 #include "espn.h"
 int main(void) {
-    if (espn_workspace_bytes(64, 1000) != 256000u) return 1;
+    if (espn_workspace_bytes(64, 1000) != 256000u + 512000u) return 1;
     if (espn_batch_threshold(2.0e9, 0.5, 1.0e6) != 1000.0) return 2;
     if (strcmp(espn_status_string(ESPN_ERR_SHAPE), "inconsistent sizes") != 0) return 3;
     if (espn_topk(NULL, NULL, 1, 4, 5, NULL, NULL, NULL) != ESPN_ERR_SHAPE) return 4;
@@ -105,10 +105,11 @@ def test_host_side_argument_errors_need_no_gpu(lib):
 
 
 def test_workspace_bytes(lib):
-    assert lib.espn_workspace_bytes(64, 1000) == 256000
-    assert lib.espn_workspace_bytes(1, 1) == 256
+    # the scores (4 bytes per pair) and the lists in id order (8 bytes per pair), each rounded up to 256 bytes
+    assert lib.espn_workspace_bytes(64, 1000) == 256000 + 512000
+    assert lib.espn_workspace_bytes(1, 1) == 256 + 256
     assert lib.espn_workspace_bytes(0, 1000) == 256
-    assert lib.espn_workspace_bytes(3, 100) % 256 == 0 and lib.espn_workspace_bytes(3, 100) >= 1200
+    assert lib.espn_workspace_bytes(3, 100) % 256 == 0 and lib.espn_workspace_bytes(3, 100) >= 3600
 
 
 def test_batches_workspace_bytes_without_a_table(lib):
