@@ -124,7 +124,8 @@ int espn_table_set_fetch(espn_table *table, int32_t mode);
  * had named already is kept with the table for ESPN_FETCH_AUTO (and espn_table_sharing_estimate).  Uniform lists
  * over 2 M documents give 0.002, Zipf(1.1) lists 0.3 and more.
  *
- * If the lists overlap (more than 5 % of the sampled pairs) and the table is in HBM, the call also notes which
+ * If the lists overlap (more than 5 % of the sampled pairs) and the table is in HBM with rows of 128 bytes or more
+ * (64-byte rows were measured to gain nothing from what follows), the call also notes which
  * documents are popular: listed by at least two of the batch's queries and by at least one in 256 (counted over
  * the whole batch, one bit per document kept with the table; n_docs * 4 bytes of device memory are allocated and
  * freed inside the call).  From then on

@@ -30,7 +30,8 @@ def ordered(table, w, B=None):
 @pytest.mark.parametrize("key,changes", [
     ("c3", dict(n_docs=6_000, B=320, K=600)),                 # 256-byte rows, 10 slices of 60: 3200 workgroups
     ("c3", dict(n_docs=6_000, B=323, K=600)),                 # a query count that is no multiple of eight
-    ("c2", dict(n_docs=30_000, B=256, K=1000)),               # 64-byte rows, 8 slices of 125
+    ("c3", dict(n_docs=6_000, B=320, K=600, dim=64)),         # 128-byte rows
+    ("c3", dict(n_docs=4_000, B=264, K=520, dim=256)),        # 512-byte rows
     ("c3", dict(n_docs=6_000, B=280, K=600, Q=48)),           # 48 query rows
     ("c3", dict(n_docs=9_000, B=64, K=4096, k=100)),          # the longest lists that are ordered; ranked by a sort
 ])
@@ -186,3 +187,10 @@ def test_what_is_not_ordered():
     espn.espn_table_check(table)
     table.free()
     fresh.free()
+    # 64-byte rows: measured to gain nothing from it
+    w32 = synth.scaled(synth.WORKLOADS["c2"], cand_law="zipf", n_docs=30_000, B=256, K=1000)
+    emb, off = synth.table(w32)
+    narrow = espn.espn_table_load(emb.to(DEV), off)
+    assert espn.espn_table_sample(narrow, torch.from_numpy(synth.candidates(w32)).to(DEV)) > 0.05
+    assert espn.espn_rerank_plan(narrow, 256, 32, 1000, 10) == {"slices": 8, "slice": 125, "launches": 2}
+    narrow.free()
