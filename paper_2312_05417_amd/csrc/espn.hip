@@ -439,8 +439,10 @@ constexpr float kShareThreshold = 0.05f;
 constexpr int kPopularListings = 2;
 constexpr int kPopularShare = 256;
 // Launches of at least this many workgroups per compute unit take lists that overlap in id order (the ordering pass
-// is a launch of its own, of about 1 % of such a scoring launch)
-constexpr int kOrderFrom = 4;
+// is a launch of its own, of about 1 % of a long scoring launch).  One call per batch, Zipf lists of 1000 over 2 M
+// documents, 256-byte rows: 128 queries (768 workgroups) 294 against 307 us, 192 queries (768) 411 against 448, 2048
+// queries 3.80 against 4.66 ms; 64 queries (256 workgroups) 172 against 165, 32 queries 113 against 92.
+constexpr int kOrderFrom = 3;
 }  // namespace
 
 ESPN_API int espn_table_set_fetch(espn_table *table, int32_t mode)
@@ -477,7 +479,7 @@ ESPN_API int espn_table_sample(espn_table *table, const int64_t *cand, int32_t B
     table->overlap = *static_cast<volatile const float *>(table->share_host);
     // overlapping lists: which documents they keep coming back to
     table->popular_valid = false;
-    if (table->overlap >= kShareThreshold && table->residency == ESPN_RESIDENT_HBM) {
+    if (table->overlap >= kShareThreshold && table->residency == ESPN_RESIDENT_HBM && table->dim != 32) {
         const int64_t words = (table->n_docs + 31) / 32;
         if (!table->popular_dev) HIP_TRY(hipMalloc(&table->popular_dev, sizeof(unsigned) * (size_t)words));
         unsigned *counts = nullptr;

@@ -51,6 +51,11 @@ def test_full_size_hbm_workloads(key, sample):
     cand = synth.candidates(w)
     cand_d = torch.from_numpy(cand).to(DEV)
     q = synth.queries(w, device=DEV)
+    # as bench.py does once per workload: the library is shown a batch's lists (c4's overlap, so its batches are
+    # scored in id order, popular documents through the caches; the others' do not)
+    espn.espn_table_sample(table, cand_d)
+    kernels = espn.espn_rerank_plan_kernels(table, w.B, w.Q, w.K, w.k)
+    assert any("order_lists_kernel" in name for name in kernels) == (key == "c4"), kernels
     part = espn.espn_workspace_bytes(w.B, w.K)
     ws = torch.empty(espn.espn_batches_workspace_bytes(table, 3, w.B, w.Q, w.K, w.k), dtype=torch.uint8, device=DEV)
     many_ids, many_top = espn.espn_rerank_batches(table, [q] * 3, [cand_d] * 3, w.k, workspace=ws)
