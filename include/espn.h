@@ -131,8 +131,9 @@ int espn_table_set_fetch(espn_table *table, int32_t mode);
  * freed inside the call).  From then on
  *   - launches that fetch through the caches do so for the popular documents only and stream the others past
  *     them, so that the popular ones stay there;
- *   - espn_rerank and espn_rerank_batches take batches of whole lists that fill the device many times over (at
- *     least three workgroups per compute unit, lists of up to 4096 candidates) in the order of their document ids:
+ *   - espn_rerank and espn_rerank_batches take batches of whole lists that fill the device many times over (a
+ *     batch, or the batches of a queue that one launch scores together: at least three workgroups per compute
+ *     unit, lists of up to 4096 candidates) in the order of their document ids:
  *     one more launch sorts a copy of every list by id, and the scoring launch walks all lists in that order at
  *     once, slice by slice, so that the queries that list a document ask for it at about the same time
  *     (2048 queries x 1000 Zipf candidates, 256-byte rows: 3.80 instead of 4.66 ms per batch).

@@ -1016,13 +1016,14 @@ bool scored_in_id_order(const espn_table *t, const SlicePlan &plan, int B, int Q
            t->n_docs < ((int64_t)1 << (63 - espn::SLOT_BITS));
 }
 
-int enqueue_order(const int64_t *cand, int B, int K, int64_t n_docs, int64_t *ordered, hipStream_t st)
+int enqueue_order(const espn::OrderSet &set, int K, int64_t n_docs, hipStream_t st)
 {
     using namespace espn;
-    if (K <= 256) hipLaunchKernelGGL((order_lists_kernel<256, 64>), dim3(B), dim3(64), 0, st, cand, K, K, n_docs, ordered);
-    else if (K <= 1024) hipLaunchKernelGGL((order_lists_kernel<1024, 256>), dim3(B), dim3(256), 0, st, cand, K, K, n_docs, ordered);
-    else if (K <= 2048) hipLaunchKernelGGL((order_lists_kernel<2048, 512>), dim3(B), dim3(512), 0, st, cand, K, K, n_docs, ordered);
-    else hipLaunchKernelGGL((order_lists_kernel<4096, 512>), dim3(B), dim3(512), 0, st, cand, K, K, n_docs, ordered);
+    const dim3 grid((unsigned)set.n * (unsigned)set.B);
+    if (K <= 256) hipLaunchKernelGGL((order_lists_kernel<256, 64>), grid, dim3(64), 0, st, set, K, K, n_docs);
+    else if (K <= 1024) hipLaunchKernelGGL((order_lists_kernel<1024, 256>), grid, dim3(256), 0, st, set, K, K, n_docs);
+    else if (K <= 2048) hipLaunchKernelGGL((order_lists_kernel<2048, 512>), grid, dim3(512), 0, st, set, K, K, n_docs);
+    else hipLaunchKernelGGL((order_lists_kernel<4096, 512>), grid, dim3(512), 0, st, set, K, K, n_docs);
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }
@@ -1046,7 +1047,12 @@ int enqueue_rerank(espn_table *t, const espn::DocSource &src, const espn::Batch 
     const espn::RankOut ro{k, ldo};
     espn::Batch scored = bt;
     if (ordered && !src.row_map && !bt.prior && bt.ldc == bt.K && scored_in_id_order(t, plan, B, bt.Q, bt.K)) {
-        if (int rc = enqueue_order(bt.cand, B, bt.K, t->n_docs, ordered, st)) return rc;
+        espn::OrderSet lists{};
+        lists.n = 1;
+        lists.B = B;
+        lists.cand[0] = bt.cand;
+        lists.ordered[0] = ordered;
+        if (int rc = enqueue_order(lists, bt.K, t->n_docs, st)) return rc;
         scored.cand = ordered;
         scored.order = espn::ORDER_BY_ID;
     }
@@ -1096,7 +1102,7 @@ void kernel_names(const espn_table *table, int queries, int Q, int K, int k, boo
     } else {
         snprintf(text, len, "espn::maxsim_generic_kernel");
     }
-    if (!fused && on_matrix_cores(table, Q) && scored_in_id_order(table, plan_slices(table, queries, K, k), queries, Q, K)) {
+    if (on_matrix_cores(table, Q) && scored_in_id_order(table, plan_slices(table, queries, K, k), queries, Q, K)) {
         const size_t at = std::strlen(text);
         snprintf(text + at, len - at, ";%s", order_kernel_name(K));
     }
@@ -1244,7 +1250,7 @@ ESPN_API int espn_rerank_batches(espn_table *table, int32_t n_batches, const voi
         if (count == 1)
             return enqueue_rerank(table, src, plain_batch(q[first], cand[first], Q, K), B, k, k, ranked ? out_ids[first] : nullptr,
                                   ranked ? out_scores[first] : nullptr, ws, reinterpret_cast<int64_t *>(ws + score_bytes(B, K)), on);
-        const espn::Batch shape = plain_batch(nullptr, nullptr, Q, K);
+        espn::Batch shape = plain_batch(nullptr, nullptr, Q, K);
         espn::BatchSet set{};
         espn::TopkSet lists{};
         set.n = lists.n = count;
@@ -1259,6 +1265,18 @@ ESPN_API int espn_rerank_batches(espn_table *table, int32_t n_batches, const voi
         }
         // the launch is planned as what it is: one batch of count * B queries
         const SlicePlan plan = plan_slices(table, count * B, K, k);
+        if (scored_in_id_order(table, plan, count * B, Q, K)) {
+            espn::OrderSet order{};
+            order.n = count;
+            order.B = B;
+            for (int x = 0; x < count; ++x) {
+                order.cand[x] = cand[first + x];
+                order.ordered[x] = reinterpret_cast<int64_t *>(ws + (size_t)x * per_batch + score_bytes(B, K));
+                set.cand[x] = order.ordered[x];
+            }
+            if (int rc = enqueue_order(order, K, table->n_docs, on)) return rc;
+            shape.order = espn::ORDER_BY_ID;
+        }
         if (int rc = enqueue_score(table, src, shape, set, plan, espn::RankOut{k, k}, on)) return rc;
         if (k == 0 || plan.rank) return ESPN_OK;
         const dim3 grid((unsigned)count * B);

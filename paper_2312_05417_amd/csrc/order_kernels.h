@@ -40,16 +40,26 @@ __global__ __launch_bounds__(256) void popular_kernel(const unsigned *__restrict
     bits[word] = w;
 }
 
-// One workgroup per query: the K <= N entries of its list as id << SLOT_BITS | position (an id outside the table
-// as -1: it is scored as such, raises the same flag, and can alias nothing), sorted ascending in LDS (bitonic,
-// N a power of two, padded with entries that sort last), written to ordered[b * K ..].
+// The lists of the batches one launch orders (the batches one scoring launch takes together)
+struct OrderSet {
+    int n, B;
+    const int64_t *cand[MAX_FUSED];     // each [B, ldc]
+    int64_t *ordered[MAX_FUSED];        // each [B, K], written
+};
+
+// One workgroup per query (query g of the launch is query g % B of batch g / B): the K <= N entries of its list as
+// id << SLOT_BITS | position (an id outside the table as -1: it is scored as such, raises the same flag, and can
+// alias nothing), sorted ascending in LDS (bitonic, N a power of two, padded with entries that sort last), written
+// to ordered[b * K ..].
 template <int N, int T>
-__global__ __launch_bounds__(T) void order_lists_kernel(const int64_t *__restrict__ cand, int ldc, int K, int64_t n_docs,
-                                                        int64_t *__restrict__ ordered)
+__global__ __launch_bounds__(T) void order_lists_kernel(const OrderSet set, int ldc, int K, int64_t n_docs)
 {
     static_assert((N & (N - 1)) == 0 && N >= 2 * T && N <= (1 << SLOT_BITS), "one thread per pair of entries, or several");
     __shared__ uint64_t s_key[N];
-    const int b = blockIdx.x;
+    const int which = set.n > 1 ? (int)blockIdx.x / set.B : 0;
+    const int b = (int)blockIdx.x - which * set.B;
+    const int64_t *__restrict__ cand = set.cand[which];
+    int64_t *__restrict__ ordered = set.ordered[which];
     for (int i = threadIdx.x; i < N; i += T) {
         uint64_t key = ~(uint64_t)0;
         if (i < K) {

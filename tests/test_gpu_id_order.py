@@ -78,6 +78,36 @@ def test_lists_in_id_order_match_the_oracle_and_the_plain_order(key, changes):
     table.free()
 
 
+def test_a_fused_launch_of_small_batches_in_id_order():
+    """Small batches that the queue entry point scores several per launch: the launch is long, so their lists are
+    ordered as well (one ordering launch for all of them)."""
+    w = synth.scaled(synth.WORKLOADS["c3"], cand_law="zipf", n_docs=6_000, B=48, K=600)
+    n_batches = 19
+    say("id order, fused: %s B=%d K=%d x %d" % (w.name, w.B, w.K, n_batches))
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    qs_d = [q.to(DEV) for q in qs]
+    cands_d = [torch.from_numpy(c).to(DEV) for c in cands]
+    plain_ids, plain_top = espn.espn_rerank_batches(table, qs_d, cands_d, w.k)
+    torch.cuda.synchronize()
+    assert espn.espn_table_sample(table, cands_d[0]) > 0.05
+    plan = espn.espn_batches_plan(table, n_batches, w.B, w.Q, w.K, w.k)
+    assert plan["fuse"] == 10 and plan["launches"] == 2 and "espn::order_lists_kernel<1024, 256>" in plan["kernels"], plan
+    assert not ordered(table, w)                              # one batch alone is a short launch
+    ids, top = espn.espn_rerank_batches(table, qs_d, cands_d, w.k)
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    for n in range(n_batches):
+        assert torch.equal(ids[n], plain_ids[n]) and np.array_equal(bits(top[n]), bits(plain_top[n])), n
+    for n in (0, 9, 10, 18):
+        o_all = oracle.scores(emb.numpy(), off, qs[n].numpy(), cands[n])
+        for b in range(w.B):
+            assert_topk_matches(ids[n][b].cpu().numpy(), top[n][b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+    table.free()
+
+
 def test_id_order_with_empty_documents_bad_ids_and_repeats():
     """An id outside the table is ordered as -1 whatever its value (so it can alias nothing), scores -inf and raises
     the flag; an empty document scores -inf; an id listed twice by a query is scored twice."""
