@@ -108,6 +108,41 @@ def test_a_fused_launch_of_small_batches_in_id_order():
     table.free()
 
 
+def test_the_ordered_path_in_a_captured_graph():
+    """The ordering launch is an ordinary kernel on the caller's stream: a captured call replays with new lists in
+    the same buffers, with eager calls and synchronisations in between."""
+    w = synth.scaled(synth.WORKLOADS["c3"], cand_law="zipf", n_docs=6_000, B=320, K=600)
+    say("id order under graph capture")
+    emb, off = synth.table(w)
+    table = espn.espn_table_load(emb.to(DEV), off)
+    sets = [(synth.queries(w, batch=r).to(DEV), torch.from_numpy(synth.candidates(w, batch=r)).to(DEV)) for r in range(2)]
+    assert espn.espn_table_sample(table, sets[0][1]) > 0.05 and ordered(table, w)
+    eager = [tuple(t.clone() for t in espn.espn_rerank(table, q, c, w.k)) for q, c in sets]
+    torch.cuda.synchronize()
+    q_buf, c_buf = sets[0][0].clone(), sets[0][1].clone()
+    ids_buf = torch.empty((w.B, w.k), dtype=torch.int64, device=DEV)
+    sc_buf = torch.empty((w.B, w.k), dtype=torch.float32, device=DEV)
+    ws = torch.empty(espn.espn_workspace_bytes(w.B, w.K), dtype=torch.uint8, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        espn.espn_rerank(table, q_buf, c_buf, w.k, ids_buf, sc_buf, workspace=ws)
+    for rep in range(4):
+        which = rep % 2
+        q_buf.copy_(sets[which][0])
+        c_buf.copy_(sets[which][1])
+        ids_buf.fill_(-3)
+        ws.fill_(0xff)                                         # nothing may depend on what the workspace held
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids_buf, eager[which][0]) and np.array_equal(bits(sc_buf), bits(eager[which][1])), rep
+        again = espn.espn_rerank(table, *sets[1 - which], w.k)      # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(again[0], eager[1 - which][0])
+    espn.espn_table_check(table)
+    del graph
+    table.free()
+
+
 def test_id_order_with_empty_documents_bad_ids_and_repeats():
     """An id outside the table is ordered as -1 whatever its value (so it can alias nothing), scores -inf and raises
     the flag; an empty document scores -inf; an id listed twice by a query is scored twice."""
