@@ -389,9 +389,12 @@ int espn_prefetch(espn_table *table, const int64_t *cand, int32_t B, int32_t K, 
  * The same prefetch done the other way round (the second of the two ways to bring a batch's documents
  * from the slow tier into GPU memory ahead of scoring, Sec. 4.1 / 4.2): the HOST finds the distinct
  * documents, packs their rows back to back into pinned buffers (16 threads, two buffers of 64 MiB) and
- * sends each buffer with one plain copy on `side_stream`, packing the next buffer meanwhile.  Nothing is
- * taken from other slots.  The slot ends up in the same state as after espn_prefetch (espn_rerank_staged,
- * espn_staging_counters and later espn_prefetch calls into other slots work on it unchanged).
+ * sends each buffer with one plain copy on `side_stream`, packing the next buffer meanwhile.  Documents that an
+ * earlier call of this function left in another slot, and that slot still holds, are not packed and sent again
+ * but copied from there inside HBM (the host keeps, per document, where its newest packed prefetch put it: 12
+ * bytes per document of the table; a slot refilled by espn_prefetch is not trusted).  The slot ends up in the same
+ * state as after espn_prefetch (espn_rerank_staged, espn_staging_counters and later espn_prefetch calls into
+ * other slots work on it unchanged).
  *   cand_host  [B, K] int64, HOST; read before the call returns.
  * The table may be in pinned or in ordinary host memory (ESPN_RESIDENT_HOST_PINNED, ESPN_RESIDENT_HOST).
  * Unlike espn_prefetch this call BLOCKS the host until all but the last two buffers have been sent, and

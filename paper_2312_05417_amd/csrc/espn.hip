@@ -103,6 +103,7 @@ struct StagingSlot {
     unsigned *bits = nullptr;              // [ceil(n_docs / 32)] documents held by the slot
     int64_t *uniq = nullptr;               // [capacity_docs] distinct documents of the batch
     int64_t *other_row = nullptr;          // [capacity_docs] where each one's rows come from: a row of another slot, or -1 (host)
+    int64_t *handed = nullptr;             // [capacity_docs] the same for the packing engine (which keeps slot rows in other_row)
     unsigned long long *counters = nullptr;  // [4]: distinct documents, rows reserved, rows taken from other slots
     uint64_t filled_at = 0;                // sequence number of the last prefetch into the slot (0: never)
     hipEvent_t ready = nullptr;            // recorded when a prefetch into the slot has been enqueued
@@ -183,6 +184,13 @@ struct PackState {
     bool in_flight[2] = {false, false};
     int64_t *uniq = nullptr;                    // pinned, [capacity_docs]: distinct documents of the batch
     int64_t *row0 = nullptr;                    // pinned, [capacity_docs]: first slot row of each
+    int64_t *from = nullptr;                    // pinned, [capacity_docs]: slot << OTHER_SHIFT | row it can be taken from, or -1
+    // Which slot holds a document since the newest packed prefetch that brought it (slot << OTHER_SHIFT | first row
+    // there; -1: none), and that slot's prefetch number then: the entry holds while the slot has not been refilled.
+    std::vector<int64_t> where;
+    std::vector<uint32_t> where_gen;
+    std::vector<int64_t> scratch;               // [3 * capacity_docs]: the lists while they are put in order
+    std::vector<int64_t> found;                 // [2 * pairs of the largest batch so far]: (id, length) as the threads find them
     hipEvent_t lists_sent = nullptr;            // the copies out of uniq / row0 have been enqueued
     bool lists_in_flight = false;
     std::vector<uint64_t> seen;                 // one bit per document of the table
@@ -388,6 +396,7 @@ void free_pack_state(espn_table *t)
     }
     if (p->uniq) (void)hipHostFree(p->uniq);
     if (p->row0) (void)hipHostFree(p->row0);
+    if (p->from) (void)hipHostFree(p->from);
     if (p->lists_sent) (void)hipEventDestroy(p->lists_sent);
     delete p;
     t->pack = nullptr;
@@ -402,6 +411,7 @@ void free_staging(espn_table *t)
         (void)hipFree(s.bits);
         (void)hipFree(s.uniq);
         (void)hipFree(s.other_row);
+        (void)hipFree(s.handed);
         (void)hipFree(s.counters);
         if (s.ready) (void)hipEventDestroy(s.ready);
         if (s.consumed) (void)hipEventDestroy(s.consumed);
@@ -1465,6 +1475,7 @@ ESPN_API int espn_staging_create_ring(espn_table *table, int32_t n_slots, int64_
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.bits), sizeof(unsigned) * n_words);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.uniq), sizeof(int64_t) * (size_t)capacity_docs);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.other_row), sizeof(int64_t) * (size_t)capacity_docs);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.handed), sizeof(int64_t) * (size_t)capacity_docs);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s.counters), kAlign);
         if (e == hipSuccess) e = hipMemset(s.bits, 0, sizeof(unsigned) * n_words);
         if (e == hipSuccess) e = hipMemset(s.counters, 0, kAlign);
@@ -1569,6 +1580,7 @@ int make_pack_state(espn_table *t)
     const size_t list_bytes = sizeof(int64_t) * (size_t)t->capacity_docs;
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&p->uniq), list_bytes, hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&p->row0), list_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&p->from), list_bytes, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->lists_sent, hipEventDisableTiming);
     if (e != hipSuccess) {
         free_pack_state(t);
@@ -1577,6 +1589,9 @@ int make_pack_state(espn_table *t)
     }
     try {
         p->seen.assign(((size_t)t->n_docs + 63) / 64, 0);
+        p->where.assign((size_t)t->n_docs, -1);
+        p->where_gen.assign((size_t)t->n_docs, 0);
+        p->scratch.resize(3 * (size_t)t->capacity_docs);
         p->pool.start(kPackThreads - 1);
     } catch (...) {                     // bad_alloc, or no more threads to be had
         free_pack_state(t);
@@ -1636,22 +1651,37 @@ void pack_documents(const espn_table *t, PackPool &pool, const int64_t *uniq, in
 
 // Everything espn_prefetch_packed enqueues once the batch has been found valid.  The slot's bitmap and row map
 // are written LAST, after the row copies: if anything fails on the way the slot advertises no document.
-int enqueue_packed(espn_table *table, PackState &p, StagingSlot &s, int64_t n_uniq, int64_t rows, hipStream_t st)
+// Documents [0, n_packed) of the lists are packed and sent, documents [n_packed, n_uniq) are copied from the other
+// slots that hold them (`handed_rows` rows in all).
+int enqueue_packed(espn_table *table, PackState &p, StagingSlot &s, int64_t n_packed, int64_t n_uniq, int64_t rows,
+                   int64_t handed_rows, hipStream_t st)
 {
     const int64_t *off = table->off_host;
     const size_t row_bytes = (size_t)table->dim * table->elem_bytes;
     if (n_uniq == 0) return ESPN_OK;
     HIP_TRY(hipMemcpyAsync(s.uniq, p.uniq, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(s.other_row, p.row0, sizeof(int64_t) * (size_t)n_uniq, hipMemcpyHostToDevice, st));
+    if (n_uniq > n_packed)
+        HIP_TRY(hipMemcpyAsync(s.handed + n_packed, p.from + n_packed, sizeof(int64_t) * (size_t)(n_uniq - n_packed),
+                               hipMemcpyHostToDevice, st));
     HIP_TRY(hipEventRecord(p.lists_sent, st));
     p.lists_in_flight = true;
+    if (n_uniq > n_packed) {
+        // first, while the host packs: what the other slots hold moves inside HBM
+        espn::SlotRows all{};
+        for (int x = 0; x < table->n_slots; ++x) all.rows[x] = static_cast<const uint4 *>(table->slot[x].rows);
+        const unsigned blocks = (unsigned)std::min<int64_t>((n_uniq - n_packed + 3) / 4, 4096);
+        hipLaunchKernelGGL(espn::staging_handover_kernel, dim3(blocks), dim3(256), 0, st, all, table->off_dev, s.uniq,
+                           s.other_row, s.handed, n_packed, n_uniq, static_cast<uint4 *>(s.rows), (int)(row_bytes / 16));
+        HIP_TRY(hipGetLastError());
+    }
     // rows: whole documents are packed into a pinned buffer while the previous buffer is on its way
     int64_t u = 0;
     int which = 0;
-    while (u < n_uniq) {
+    while (u < n_packed) {
         int64_t last = u;
         size_t bytes = 0;
-        while (last < n_uniq) {
+        while (last < n_packed) {
             const size_t len = (size_t)(off[p.uniq[last] + 1] - off[p.uniq[last]]) * row_bytes;
             if (bytes + len > kPackBytes) break;
             bytes += len;
@@ -1669,7 +1699,8 @@ int enqueue_packed(espn_table *table, PackState &p, StagingSlot &s, int64_t n_un
         which ^= 1;
     }
     hipLaunchKernelGGL(espn::staging_publish_kernel, dim3((unsigned)((n_uniq + 255) / 256)), dim3(256), 0, st, s.uniq,
-                       s.other_row, n_uniq, (unsigned long long)rows, s.bits, s.row_map, s.counters);
+                       s.other_row, n_uniq, (unsigned long long)rows, (unsigned long long)handed_rows, s.bits, s.row_map,
+                       s.counters);
     HIP_TRY(hipGetLastError());
     return ESPN_OK;
 }
@@ -1697,39 +1728,131 @@ ESPN_API int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, i
         HIP_TRY(hipEventSynchronize(p.lists_sent));
         p.lists_in_flight = false;
     }
-    // distinct documents in order of first appearance, and the slot row each will start at
+    // The distinct documents of the batch and their lengths.  The threads take a share of the pairs each and claim
+    // documents in the bitmap (1 M pairs, 325 000 distinct documents of an 8.8 M table: 11 ms on one thread, most of
+    // it waiting for the documents' offsets); a thread's finds go to its own stretch of `found` (id, length), and
+    // the stretches are then put together in thread order.  Which thread claims a document that several list is a
+    // race with one winner: the order of the documents in the slot may differ from run to run, nothing else.
     const int64_t n_pairs = (int64_t)B * K;
-    int64_t n_uniq = 0, rows = 0;
-    int status = ESPN_OK;
-    for (int64_t i = 0; i < n_pairs; ++i) {
-        const int64_t id = cand_host[i];
-        if (id < 0 || id >= table->n_docs) {
-            status = fail(ESPN_ERR_ID_RANGE, "candidate %lld of the batch is %lld, outside [0, %lld)", (long long)i,
-                          (long long)id, (long long)table->n_docs);
-            break;
-        }
-        uint64_t &word = p.seen[(size_t)id >> 6];
-        const uint64_t bit = 1ull << (id & 63);
-        if (word & bit) continue;
-        const int64_t len = off[id + 1] - off[id];
-        if ((size_t)len * row_bytes > kPackBytes) {
-            status = fail(ESPN_ERR_UNSUPPORTED, "document %lld holds %zu bytes, more than a pack buffer", (long long)id,
-                          (size_t)len * row_bytes);
-            break;
-        }
-        if (n_uniq >= table->capacity_docs || rows + len > table->capacity_rows) {
-            status = fail(ESPN_ERR_NOMEM, "the batch needs more than the %lld rows / %lld documents a staging slot holds",
-                          (long long)table->capacity_rows, (long long)table->capacity_docs);
-            break;
-        }
-        word |= bit;
-        p.uniq[n_uniq] = id;
-        p.row0[n_uniq] = rows;
-        ++n_uniq;
-        rows += len;
+    try {
+        if (p.found.size() < 2 * (size_t)n_pairs) p.found.resize(2 * (size_t)n_pairs);
+    } catch (...) {
+        return fail(ESPN_ERR_NOMEM, "host allocation failed");
     }
-    for (int64_t u = 0; u < n_uniq; ++u) p.seen[(size_t)p.uniq[u] >> 6] = 0;     // leave the bitmap clear
-    if (status != ESPN_OK) return status;                                         // nothing has been enqueued
+    const int finders = (int)std::min<int64_t>(std::min(p.pool.parts(), kPackThreads), std::max<int64_t>(1, n_pairs / 8192));
+    int64_t n_found[kPackThreads] = {}, first_bad[kPackThreads], first_large[kPackThreads];
+    p.pool.run(finders, [&](int x) {
+        const int64_t begin = n_pairs * x / finders, end = n_pairs * (x + 1) / finders;
+        int64_t *mine = p.found.data() + 2 * begin, n = 0;
+        first_bad[x] = first_large[x] = -1;
+        for (int64_t i = begin; i < end; ++i) {
+            const int64_t id = cand_host[i];
+            if (id < 0 || id >= table->n_docs) {
+                if (first_bad[x] < 0) first_bad[x] = i;
+                continue;
+            }
+            const uint64_t bit = 1ull << (id & 63);
+            if (__atomic_fetch_or(&p.seen[(size_t)id >> 6], bit, __ATOMIC_RELAXED) & bit) continue;
+            const int64_t len = off[id + 1] - off[id];
+            if ((size_t)len * row_bytes > kPackBytes && first_large[x] < 0) first_large[x] = i;
+            mine[2 * n] = id;
+            mine[2 * n + 1] = len;
+            ++n;
+        }
+        n_found[x] = n;
+    });
+    int64_t n_uniq = 0, rows = 0;
+    for (int x = 0; x < finders; ++x) n_uniq += n_found[x];
+    // leave the bitmap clear, whatever comes next
+    p.pool.run(finders, [&](int x) {
+        const int64_t *mine = p.found.data() + 2 * (n_pairs * x / finders);
+        for (int64_t u = 0; u < n_found[x]; ++u)
+            __atomic_store_n(&p.seen[(size_t)mine[2 * u] >> 6], (uint64_t)0, __ATOMIC_RELAXED);
+    });
+    // errors, the first in list order: nothing has been enqueued
+    for (int x = 0; x < finders; ++x)
+        if (first_bad[x] >= 0)
+            return fail(ESPN_ERR_ID_RANGE, "candidate %lld of the batch is %lld, outside [0, %lld)", (long long)first_bad[x],
+                        (long long)cand_host[first_bad[x]], (long long)table->n_docs);
+    for (int x = 0; x < finders; ++x)
+        if (first_large[x] >= 0) {
+            const int64_t id = cand_host[first_large[x]];
+            return fail(ESPN_ERR_UNSUPPORTED, "document %lld holds %zu bytes, more than a pack buffer", (long long)id,
+                        (size_t)(off[id + 1] - off[id]) * row_bytes);
+        }
+    if (n_uniq > table->capacity_docs)
+        return fail(ESPN_ERR_NOMEM, "the batch needs more than the %lld rows / %lld documents a staging slot holds",
+                    (long long)table->capacity_rows, (long long)table->capacity_docs);
+    {
+        int64_t at = 0;
+        for (int x = 0; x < finders; ++x) {
+            const int64_t *mine = p.found.data() + 2 * (n_pairs * x / finders);
+            for (int64_t u = 0; u < n_found[x]; ++u, ++at) {
+                p.uniq[at] = mine[2 * u];
+                p.row0[at] = mine[2 * u + 1];           // for now: the document's length
+                rows += mine[2 * u + 1];
+            }
+        }
+    }
+    if (rows > table->capacity_rows)
+        return fail(ESPN_ERR_NOMEM, "the batch needs more than the %lld rows / %lld documents a staging slot holds",
+                    (long long)table->capacity_rows, (long long)table->capacity_docs);
+
+    // Which of them another slot still holds since an earlier packed prefetch (Zipf lists: a third of a batch's
+    // distinct documents were in the batch before): those are copied inside HBM instead of being packed and sent.
+    // The lists are put in the order (packed ..., handed over ...), so that what is packed fills the slot's first rows
+    // back to back, and the slot row of every document follows from the lengths.
+    const uint64_t gen = table->prefetches + 1;
+    uint64_t slot_gen[espn::MAX_SLOTS] = {};
+    for (int x = 0; x < table->n_slots; ++x) slot_gen[x] = x == slot ? 0 : table->slot[x].filled_at;
+    const int parts = (int)std::min<int64_t>(std::min(p.pool.parts(), kPackThreads), std::max<int64_t>(1, n_uniq / 4096));
+    p.pool.run(parts, [&](int x) {
+        for (int64_t u = n_uniq * x / parts; u < n_uniq * (x + 1) / parts; ++u) {
+            const int64_t id = p.uniq[u], w = p.where[(size_t)id];
+            int64_t from = -1;
+            if (w >= 0) {
+                const uint64_t then = slot_gen[w >> espn::OTHER_SHIFT];
+                if (then != 0 && (uint32_t)then == p.where_gen[(size_t)id]) from = w;
+            }
+            p.from[u] = from;
+        }
+    });
+    int64_t n_packed = 0, handed_rows = 0;
+    {
+        int64_t *ids = p.scratch.data(), *lens = ids + table->capacity_docs, *froms = lens + table->capacity_docs;
+        int64_t n_handed = 0;
+        for (int64_t u = 0; u < n_uniq; ++u) {
+            if (p.from[u] < 0) {
+                p.uniq[n_packed] = p.uniq[u];
+                p.row0[n_packed] = p.row0[u];
+                ++n_packed;
+            } else {
+                ids[n_handed] = p.uniq[u];
+                lens[n_handed] = p.row0[u];
+                froms[n_handed] = p.from[u];
+                handed_rows += p.row0[u];
+                ++n_handed;
+            }
+        }
+        for (int64_t h = 0; h < n_handed; ++h) {
+            p.uniq[n_packed + h] = ids[h];
+            p.row0[n_packed + h] = lens[h];
+            p.from[n_packed + h] = froms[h];
+        }
+        int64_t at = 0;
+        for (int64_t u = 0; u < n_uniq; ++u) {
+            const int64_t len = p.row0[u];
+            p.row0[u] = at;
+            at += len;
+        }
+    }
+    // ... and this slot is where they all are from now on
+    p.pool.run(parts, [&](int x) {
+        for (int64_t u = n_uniq * x / parts; u < n_uniq * (x + 1) / parts; ++u) {
+            p.where[(size_t)p.uniq[u]] = ((int64_t)slot << espn::OTHER_SHIFT) | p.row0[u];
+            p.where_gen[(size_t)p.uniq[u]] = (uint32_t)gen;
+        }
+    });
 
     // same ordering as espn_prefetch: after the last re-rank that read the slot, and after the last
     // prefetch into every other slot (which may be reading this one)
@@ -1741,9 +1864,11 @@ ESPN_API int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, i
     const dim3 clear_grid((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024));
     hipLaunchKernelGGL(espn::staging_clear_kernel, clear_grid, dim3(256), 0, st, s.bits, n_words, s.counters);
     HIP_TRY(hipGetLastError());
-    status = enqueue_packed(table, p, s, n_uniq, rows, st);
+    int status = enqueue_packed(table, p, s, n_packed, n_uniq, rows, handed_rows, st);
     // (the clear kernel has run by then and the publish kernel has not been enqueued: the slot holds nothing,
-    // and a staged re-rank of this batch reports ESPN_ERR_SHAPE through espn_table_check)
+    // and a staged re-rank of this batch reports ESPN_ERR_SHAPE through espn_table_check; a new prefetch number
+    // keeps later prefetches from taking documents out of it)
+    if (status != ESPN_OK) s.filled_at = ++table->prefetches;
     const hipError_t e = hipEventRecord(s.ready, st);
     if (status == ESPN_OK && e != hipSuccess) status = fail(ESPN_ERR_HIP, "hipEventRecord failed: %s", hipGetErrorString(e));
     return status;

@@ -116,9 +116,40 @@ __global__ __launch_bounds__(256) void staging_mark_kernel(
     }
 }
 
-// uniq[i] is a distinct document of the batch and row0[i] the slot row its rows were copied to
+// The packing engine's share of the slot-to-slot hand-over.  The host knows which documents of the batch an
+// earlier packed prefetch left in another slot: documents uniq[first .. n) are copied from there (from[u] = slot
+// x << OTHER_SHIFT | first row in x), one wave per document, to row row0[u] of this slot.
+struct SlotRows {
+    const uint4 *rows[MAX_SLOTS];
+};
+__global__ __launch_bounds__(256) void staging_handover_kernel(
+    const SlotRows all, const int64_t *__restrict__ off, const int64_t *__restrict__ uniq,
+    const int64_t *__restrict__ row0, const int64_t *__restrict__ from, int64_t first, int64_t n,
+    uint4 *__restrict__ slot, int chunks_per_row)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = (int64_t)gridDim.x * 4;
+    for (int64_t u = first + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); u < n; u += n_waves) {
+        const int64_t id = uniq[u], f = from[u];
+        const int64_t n_chunks = (off[id + 1] - off[id]) * chunks_per_row;
+        const uint4 *src = all.rows[f >> OTHER_SHIFT] + (size_t)(f & (((int64_t)1 << OTHER_SHIFT) - 1)) * chunks_per_row;
+        uint4 *dst = slot + (size_t)row0[u] * chunks_per_row;
+        int64_t x = lane;
+        for (; x + 7 * 64 < n_chunks; x += 8 * 64) {
+            uint4 v[8];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) v[y] = src[x + 64 * y];
+#pragma unroll
+            for (int y = 0; y < 8; ++y) dst[x + 64 * y] = v[y];
+        }
+        for (; x < n_chunks; x += 64) dst[x] = src[x];
+    }
+}
+
+// uniq[i] is a distinct document of the batch and row0[i] the slot row its rows were copied to; `handed` of the
+// `rows` rows came from other slots
 __global__ void staging_publish_kernel(const int64_t *__restrict__ uniq, const int64_t *__restrict__ row0, int64_t n,
-                                       unsigned long long rows, unsigned *__restrict__ bits,
+                                       unsigned long long rows, unsigned long long handed, unsigned *__restrict__ bits,
                                        int64_t *__restrict__ row_map, unsigned long long *__restrict__ counters)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -130,7 +161,7 @@ __global__ void staging_publish_kernel(const int64_t *__restrict__ uniq, const i
     if (i == 0) {
         counters[0] = (unsigned long long)n;
         counters[1] = rows;
-        counters[2] = 0ull;         // nothing is taken from other slots
+        counters[2] = handed;
         counters[3] = (unsigned long long)n;
     }
 }

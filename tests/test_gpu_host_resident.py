@@ -303,6 +303,93 @@ def test_the_packing_engine_fills_a_slot_like_the_gather_engine(key, changes):
     table.free()
 
 
+@pytest.mark.parametrize("n_slots,codec", [(2, "f16"), (3, "f16"), (4, "e4m3")])
+def test_the_packing_engine_takes_from_other_slots_what_they_hold(n_slots, codec):
+    """The host remembers where its packed prefetches put every document: what another slot of the ring still holds
+    is copied from there, only the rest is packed and sent.  Double-buffered on two streams, every batch against the
+    oracle and bit for bit against a slot that the gather engine filled."""
+    w = synth.scaled(synth.WORKLOADS["c5"], n_docs=20_000, B=16, K=300)
+    say("packing engine, hand-over in a ring of %d (%s)" % (n_slots, codec))
+    emb, off = host_table(w)
+    if codec == "e4m3":
+        codes, scale = synth.compress_e4m3(emb, off)
+        pinned = torch.empty(codes.shape, dtype=torch.uint8, pin_memory=True)
+        pinned.copy_(codes)
+        table = espn.espn_table_load_e4m3(pinned, scale, off)
+        reference = lambda q, cand: oracle.scores_e4m3(codes.numpy(), scale, off, q, cand)
+    else:
+        table = espn.espn_table_load(emb, off)
+        reference = lambda q, cand: oracle.scores(emb.numpy(), off, q, cand)
+    espn.espn_staging_create_ring(table, n_slots, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    n_batches = 7
+    cands = [synth.candidates(w, batch=n) for n in range(n_batches)]
+    cands_h = [torch.from_numpy(c) for c in cands]
+    cands_d = [c.to(DEV) for c in cands_h]
+    qs = [synth.queries(w, batch=n) for n in range(n_batches)]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    outs = []
+    espn.espn_prefetch_packed(table, cands_h[0], 0, side)
+    for n in range(n_batches):
+        if n + 1 < n_batches:
+            espn.espn_prefetch_packed(table, cands_h[n + 1], (n + 1) % n_slots, side)
+        outs.append(espn.espn_rerank_staged(table, n % n_slots, qs[n].to(DEV), cands_d[n], w.k, stream=main))
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    for n in range(n_batches):
+        ids, top, ws = outs[n]
+        o_all = reference(qs[n].numpy(), cands[n])
+        assert_scores_close(scores_of(ws, w.B, w.K), o_all, w.Q, "batch %d" % n)
+        for b in range(w.B):
+            assert_topk_matches(ids[b].cpu().numpy(), top[b].cpu().numpy(), o_all[b], cands[n][b], w.k, w.Q)
+    # most of the last batch was taken from the other slots
+    n = n_batches - 1
+    c = espn.espn_staging_counters(table, n % n_slots)
+    uniq = np.unique(cands[n])
+    assert c["distinct_docs"] == uniq.size
+    assert 0 < c["pcie_bytes"] < int((off[uniq + 1] - off[uniq]).sum()) * w.dim * (1 if codec == "e4m3" else 2)
+    # the same batches from a slot filled by the gather engine: the same bits
+    for n in (n_batches - 1, n_batches - 2):
+        spare = (n_batches + 1) % n_slots
+        espn.espn_prefetch(table, cands_d[n], spare)
+        g_ids, g_top, g_ws = espn.espn_rerank_staged(table, spare, qs[n].to(DEV), cands_d[n], w.k)
+        assert torch.equal(g_ids, outs[n][0]) and torch.equal(g_top.view(torch.int32), outs[n][1].view(torch.int32))
+        assert np.array_equal(scores_of(g_ws, w.B, w.K).view(np.int32), scores_of(outs[n][2], w.B, w.K).view(np.int32))
+    espn.espn_table_check(table)
+    table.free()
+
+
+def test_the_packing_engine_counts_what_it_sends():
+    w = synth.scaled(synth.WORKLOADS["c5"], n_docs=20_000, B=16, K=300)
+    say("packing engine: bytes sent with and without hand-over")
+    emb, off = host_table(w)
+    table = espn.espn_table_load(emb, off)
+    n_slots = 3
+    espn.espn_staging_create_ring(table, n_slots, capacity_rows=int(off[-1]), capacity_docs=w.n_docs)
+    cands = [synth.candidates(w, batch=n) for n in range(6)]
+    rows_of = lambda ids: int((off[ids + 1] - off[ids]).sum())
+    for n in range(5):
+        espn.espn_prefetch_packed(table, torch.from_numpy(cands[n]), n % n_slots)
+        c = espn.espn_staging_counters(table, n % n_slots)
+        uniq = np.unique(cands[n])
+        held = np.unique(np.concatenate([cands[m].ravel() for m in range(max(0, n - n_slots + 1), n)])) if n else np.empty(0, np.int64)
+        fresh = np.setdiff1d(uniq, held)
+        assert c["distinct_docs"] == uniq.size and c["rows"] == rows_of(uniq), n
+        assert c["pcie_bytes"] == rows_of(fresh) * w.dim * 2, n
+        if n >= 1:
+            assert fresh.size < uniq.size
+    # the gather engine refills slot 1 (batches 1 and 4 went there): the host's notes about it no longer hold
+    espn.espn_prefetch(table, torch.from_numpy(cands[5]).to(DEV), 1)
+    espn.espn_prefetch_packed(table, torch.from_numpy(cands[5]), 2)
+    c = espn.espn_staging_counters(table, 2)
+    uniq = np.unique(cands[5])
+    # slot 0 still holds batch 3; slot 1 is not trusted, and the host notes only the newest holder of a document
+    fresh = np.setdiff1d(uniq, np.setdiff1d(np.unique(cands[3]), np.unique(cands[4])))
+    assert c["pcie_bytes"] == rows_of(fresh) * w.dim * 2
+    torch.cuda.synchronize()
+    espn.espn_table_check(table)
+    table.free()
+
+
 def test_the_packing_engine_reports_its_errors_before_enqueuing_anything():
     w = synth.scaled(synth.WORKLOADS["c1"], n_docs=500, B=4, K=40)
     say("packing engine: errors")
@@ -400,10 +487,14 @@ def test_a_table_in_ordinary_host_memory_is_served_by_the_packing_engine():
         p_ids, p_top, p_ws = espn.espn_rerank_staged(pinned, 0, qs_d[n], cands_d[n], w.k)
         assert torch.equal(p_ids, ids) and torch.equal(p_top.view(torch.int32), top.view(torch.int32))
         assert np.array_equal(scores_of(p_ws, w.B, w.K).view(np.int32), scores_of(ws, w.B, w.K).view(np.int32))
+    # what the batch before left in the other slot is copied from there, the rest crosses PCIe
     c = espn.espn_staging_counters(table, (n_batches - 1) % 2)
     uniq = np.unique(cands[-1])
     rows = int((off[uniq + 1] - off[uniq]).sum())
-    assert c["distinct_docs"] == uniq.size and c["rows"] == rows and c["pcie_bytes"] == rows * w.dim * 2
+    fresh = np.setdiff1d(uniq, np.unique(cands[-2]))
+    assert 0 < fresh.size < uniq.size
+    sent = int((off[fresh + 1] - off[fresh]).sum())
+    assert c["distinct_docs"] == uniq.size and c["rows"] == rows and c["pcie_bytes"] == sent * w.dim * 2
     espn.espn_table_check(pinned)
     pinned.free()
     table.free()
