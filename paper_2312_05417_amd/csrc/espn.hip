@@ -1802,7 +1802,13 @@ ESPN_API int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, i
     // distinct documents were in the batch before): those are copied inside HBM instead of being packed and sent.
     // The lists are put in the order (packed ..., handed over ...), so that what is packed fills the slot's first rows
     // back to back, and the slot row of every document follows from the lengths.
-    const uint64_t gen = table->prefetches + 1;
+    // Same ordering as espn_prefetch: after the last re-rank that read the slot, and after the last prefetch into
+    // every other slot (which may be reading this one).  (Enqueued before the host's books are touched: from here on
+    // a failure gives the slot a new prefetch number, so that nothing is ever taken from it on the strength of them.)
+    HIP_TRY(hipStreamWaitEvent(st, s.consumed, 0));
+    for (int i = 0; i < table->n_slots; ++i)
+        if (i != slot) HIP_TRY(hipStreamWaitEvent(st, table->slot[i].ready, 0));
+    const uint64_t gen = s.filled_at = ++table->prefetches;
     uint64_t slot_gen[espn::MAX_SLOTS] = {};
     for (int x = 0; x < table->n_slots; ++x) slot_gen[x] = x == slot ? 0 : table->slot[x].filled_at;
     const int parts = (int)std::min<int64_t>(std::min(p.pool.parts(), kPackThreads), std::max<int64_t>(1, n_uniq / 4096));
@@ -1854,17 +1860,12 @@ ESPN_API int espn_prefetch_packed(espn_table *table, const int64_t *cand_host, i
         }
     });
 
-    // same ordering as espn_prefetch: after the last re-rank that read the slot, and after the last
-    // prefetch into every other slot (which may be reading this one)
-    HIP_TRY(hipStreamWaitEvent(st, s.consumed, 0));
-    for (int i = 0; i < table->n_slots; ++i)
-        if (i != slot) HIP_TRY(hipStreamWaitEvent(st, table->slot[i].ready, 0));
-    s.filled_at = ++table->prefetches;
     const int64_t n_words = (table->n_docs + 31) / 32 + 1;
     const dim3 clear_grid((unsigned)std::min<int64_t>((n_words + 255) / 256, 1024));
     hipLaunchKernelGGL(espn::staging_clear_kernel, clear_grid, dim3(256), 0, st, s.bits, n_words, s.counters);
-    HIP_TRY(hipGetLastError());
-    int status = enqueue_packed(table, p, s, n_packed, n_uniq, rows, handed_rows, st);
+    const hipError_t cleared = hipGetLastError();
+    int status = cleared == hipSuccess ? enqueue_packed(table, p, s, n_packed, n_uniq, rows, handed_rows, st)
+                                       : fail(ESPN_ERR_HIP, "launching the clear kernel failed: %s", hipGetErrorString(cleared));
     // (the clear kernel has run by then and the publish kernel has not been enqueued: the slot holds nothing,
     // and a staged re-rank of this batch reports ESPN_ERR_SHAPE through espn_table_check; a new prefetch number
     // keeps later prefetches from taking documents out of it)
