@@ -195,7 +195,11 @@ __device__ __forceinline__ float row16_sum(float v)
 //            line, so the loads have to be ordinary ones (non-temporal: 1.8 times slower).  They
 //            leave the rows in the caches, which is what a batch wants whose queries share
 //            documents (2048 queries with Zipf-distributed lists: 0.98 of the HBM peak this way,
-//            0.85 with non-temporal loads).
+//            0.85 with non-temporal loads).  This instantiation holds both ways and chooses per
+//            document (DocCursor::cached, wave-uniform): with a map of the popular documents
+//            (DocSource::popular) only those go through the caches and the others are streamed
+//            past them the LINEAR way, which keeps the popular ones there (the same lists: 4.66 ->
+//            4.4 ms per batch; 3.8 ms with the lists taken in id order, Batch::order).
 //
 // Work split.  A workgroup of WAVES waves owns a SLICE of one query's candidate list (up to
 // MAX_SLICE consecutive candidates).  All its threads first look the slice's documents up
@@ -370,7 +374,8 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     // A one-dimensional grid of B * slices workgroups (slices = workgroups per query).  Workgroups are
     // handed to the eight XCDs (each with an L2 of its own) in turn, by linear index.  With a multiple of
     // eight queries, the slices of a query are given linear indices that are equal modulo 8, so that they
-    // run on one XCD and share its copy of the query matrix.
+    // run on one XCD and share its copy of the query matrix.  An XCD takes its queries one after the other, all
+    // slices of each; with lists in id order it takes the slices one after the other, each for all its queries.
     const unsigned slices = (unsigned)((K + slice - 1) / slice);
     const unsigned n_queries = gridDim.x / slices;
     int g = (int)(blockIdx.x / slices), slice_index = (int)(blockIdx.x % slices);      // g: query of the launch
