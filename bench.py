@@ -276,8 +276,8 @@ class HbmCase:
                 score_then_topk(i)
             self.two_launch_ms = self._events(score_then_topk, steps)
         # a measuring stick: a plain contiguous read (nothing depends on what is read) of as many bytes as one
-        # launch of the scoring kernel reads, over successive windows of the table
-        window = min(int(self.launch_bytes) // 4096 * 4096, self.emb.numel() * self.elem_bytes // 4096 * 4096)
+        # launch of the dominant scoring kernel reads, over successive windows of the table
+        window = min(int(self.qplan["fuse"] * self.launch_bytes) // 4096 * 4096, self.emb.numel() * self.elem_bytes // 4096 * 4096)
         flat = self.emb.view(torch.uint8).view(-1)
         n_windows = max(1, min(64, flat.numel() // window))
         sink = torch.zeros(1, dtype=torch.int64, device=self.dev)
