@@ -211,8 +211,8 @@ __device__ __forceinline__ float row16_sum(float v)
 // keeps every wave busy until the slice is exhausted however uneven the documents are.  The tiles of the documents a wave takes form one
 // sequence that is software-pipelined P deep through registers: the load for tile u+P is issued
 // right after tile u is consumed, across document boundaries.  Loads are unconditional (an
-// exhausted cursor re-reads its last tile) so that the number of loads in flight is static and the
-// waits the compiler inserts are exact.
+// exhausted cursor re-reads a row of its last tile) so that the number of loads in flight is static
+// and the waits the compiler inserts are exact.
 //
 // A partial last tile: rows beyond the document's end are replaced by its last row (D >= 64: the
 // load address is clamped; D = 32: the bpermute source is clamped).  A duplicated row cannot change
@@ -251,11 +251,12 @@ typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 
 // Registers one lane holds of one tile: EB = bytes per component (2: binary16, 1: E4M3).  A tile is 16
-// rows, one MFMA's worth; 32-byte rows (32 E4M3 codes) come 32 to a tile, so that a tile is a full KiB and
-// one 16-byte load per lane there too.
+// rows, one MFMA's worth; 32-byte rows (32 E4M3 codes) come 64 to a tile, two 16-byte loads per lane: a document
+// of forty such rows is then one tile and not two (against tiles of 32 rows: 282-284 instead of 293 us per
+// launch of 16 batches of 64 queries, 23.4-23.9 instead of 25.0 us per single batch).
 template <int D, int EB>
 struct TileBuf {
-    static constexpr int ROWS = (D == 32 && EB == 1) ? 32 : 16;
+    static constexpr int ROWS = (D == 32 && EB == 1) ? 64 : 16;
     static constexpr int NW = ROWS * D * EB / 256;  // dwords
     unsigned w[NW];
 };
@@ -265,11 +266,16 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
                                                 const DocCursor &cur, int lane)
 {
     constexpr int ROW = D * EB;                    // bytes per row
+    // A cursor that has run out of documents keeps loading, so that the number of loads in flight stays static:
+    // one row of its last tile, not the whole tile again (P times per wave at the end of every slice; 2048 queries
+    // with Zipf lists 3.80 -> 3.71 ms, 256 queries with uniform lists 1344 -> 1335 us per two batches, 64-byte rows
+    // no difference; 32-byte rows lose 3 % by it and keep re-reading the tile).
+    const int t = (cur.done && !(D == 32 && EB == 1)) ? cur.tile + 1 : cur.t;
     if (D > 32 && (LINEAR || !cur.cached)) {
         // lane-linear: the tile is 16 * ROW contiguous bytes; instruction x takes its x-th KiB, lane l the
         // l-th 16-byte piece of that.  Every byte is asked for exactly once, whole cache lines by one
         // instruction each: non-temporal loads.  Past the document's end: the last valid piece.
-        const int npiece = min(16, cur.t - cur.tile) * (ROW / 16);
+        const int npiece = min(16, t - cur.tile) * (ROW / 16);
         const uint4v *p = reinterpret_cast<const uint4v *>(emb + ((size_t)cur.row0 + cur.tile) * ROW);
 #pragma unroll
         for (int x = 0; x < TileBuf<D, EB>::NW / 4; ++x) {
@@ -277,22 +283,25 @@ __device__ __forceinline__ void issue_tile_load(TileBuf<D, EB> &buf, const uint8
             buf.w[4 * x] = v.x; buf.w[4 * x + 1] = v.y; buf.w[4 * x + 2] = v.z; buf.w[4 * x + 3] = v.w;
         }
     } else if constexpr (D == 32) {
-        // lane-linear: the tile is 1 KiB (16 rows of 64 bytes, or 32 rows of 32 bytes), lane l loads its l-th
-        // 16 bytes; past the document's end: the last valid piece.  Every byte of the tile is asked for
-        // exactly once, by this one instruction.  LINEAR: a non-temporal load (no claim on cache space the
+        // lane-linear: the tile is 1 KiB (16 rows of 64 bytes) or 2 KiB (64 rows of 32 bytes), lane l loads its
+        // l-th 16 bytes of every KiB; past the document's end: the last valid piece.  Every byte of the tile is
+        // asked for exactly once, whole lines by one instruction each.  LINEAR: a non-temporal load (no claim on cache space the
         // look-ups could use: 1.5 % faster on a 32 us launch of binary16 rows, 1.9 % with 1024 queries a third
         // of whose documents repeat); otherwise an ordinary load, which leaves the rows in the caches for the
         // other queries of the batch that list the document (Zipf lists: 25 instead of 34 us).
-        const int npiece = min(TileBuf<D, EB>::ROWS, cur.t - cur.tile) * (ROW / 16);
+        const int npiece = min(TileBuf<D, EB>::ROWS, t - cur.tile) * (ROW / 16);
         const uint4v *p = reinterpret_cast<const uint4v *>(emb + ((size_t)cur.row0 + cur.tile) * ROW);
-        uint4v v;
-        if (LINEAR || !cur.cached) v = __builtin_nontemporal_load(p + min(lane, npiece - 1));
-        else v = p[min(lane, npiece - 1)];
-        buf.w[0] = v.x; buf.w[1] = v.y; buf.w[2] = v.z; buf.w[3] = v.w;
+#pragma unroll
+        for (int x = 0; x < TileBuf<D, EB>::NW / 4; ++x) {
+            uint4v v;
+            if (LINEAR || !cur.cached) v = __builtin_nontemporal_load(p + min(64 * x + lane, npiece - 1));
+            else v = p[min(64 * x + lane, npiece - 1)];
+            buf.w[4 * x] = v.x; buf.w[4 * x + 1] = v.y; buf.w[4 * x + 2] = v.z; buf.w[4 * x + 3] = v.w;
+        }
     } else {
         // lane (r, c) loads the c-th quarter of tile row r: D/2 contiguous bytes (binary16) or D/4 (E4M3)
         const int r = lane & 15, c = lane >> 4;
-        const int row = min(cur.tile + r, cur.t - 1);
+        const int row = min(cur.tile + r, t - 1);
         const uint4 *p = reinterpret_cast<const uint4 *>(emb + ((size_t)cur.row0 + row) * ROW + c * (ROW / 4));
 #pragma unroll
         for (int x = 0; x < TileBuf<D, EB>::NW / 4; ++x) {
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     // rows are one piece apart from a multiple of the bank period, so that the 16 rows a read touches
     // fall on different banks
     constexpr int ROW_PIECES = D * EB / 16;
-    __shared__ uint4 s_tile[D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : (D == 32 && EB == 1) ? WAVES * 64 : 1];
+    __shared__ uint4 s_tile[D > 32 ? WAVES * 16 * (ROW_PIECES + 1) : (D == 32 && EB == 1) ? WAVES * 2 * TileBuf<D, EB>::ROWS : 1];
 
     const uint8_t *__restrict__ emb = static_cast<const uint8_t *>(src.emb);
     const int Q = bt.Q, K = bt.K;
@@ -434,8 +443,8 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
     const bool own_first = ld.t > 0;
     TileBuf<D, EB> buf[P];
     if (own_first) {
-        issue_tile_load<D, EB, LINEAR>(buf[0], emb, ld, lane);
         ld.done = false;
+        issue_tile_load<D, EB, LINEAR>(buf[0], emb, ld, lane);
     }
 
     // descriptors of the slice's documents; a document with nothing to read has its score here
@@ -567,26 +576,32 @@ __global__ __launch_bounds__(WAVES * 64) void maxsim_slice_kernel(
                     };
                     half8 a[KS];
                     if constexpr (D == 32 && EB == 1) {
-                        // 32 rows of 32 bytes as loaded: lane l holds bytes [16 l, 16 l + 16) of the tile.  Through
-                        // the wave's own KiB of LDS, lane (r, c) takes bytes [8 c, 8 c + 8) of row min(r, rows-1)
-                        // of each half of the tile (the second half only if the document reaches into it)
-                        uint4 *scr = s_tile + wave * 64;
-                        scr[lane] = uint4{buf[p].w[0], buf[p].w[1], buf[p].w[2], buf[p].w[3]};
+                        // 64 rows of 32 bytes as loaded: lane l holds bytes [16 l, 16 l + 16) of each KiB of the tile.
+                        // Through the wave's own 2 KiB of LDS, lane (r, c) takes bytes [8 c, 8 c + 8) of row
+                        // min(16 x + r, rows-1) of each quarter x of the tile (a quarter is contracted only if the
+                        // document reaches into it)
+                        uint4 *scr = s_tile + wave * 2 * TR;
+#pragma unroll
+                        for (int x = 0; x < TR / 32; ++x)
+                            scr[64 * x + lane] = uint4{buf[p].w[4 * x], buf[p].w[4 * x + 1], buf[p].w[4 * x + 2], buf[p].w[4 * x + 3]};
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         const int rows = min(TR, cs.t - cs.tile);
                         const int first = cs.tile == 0 ? cs.lead : 0;          // ALIGN: rows before the document are not its own
                         const uint2 *pieces = reinterpret_cast<const uint2 *>(scr);
-                        const uint2 lo = pieces[4 * max(min(r, rows - 1), first) + c];
-                        const uint2 hi = pieces[4 * min(16 + r, rows - 1) + c];
+                        uint2 part[TR / 16];
+                        part[0] = pieces[4 * max(min(r, rows - 1), first) + c];
+#pragma unroll
+                        for (int x = 1; x < TR / 16; ++x) part[x] = pieces[4 * min(16 * x + r, rows - 1) + c];
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                         __builtin_amdgcn_wave_barrier();
-                        const unsigned w_lo[2] = {lo.x, lo.y}, w_hi[2] = {hi.x, hi.y};
-                        a[0] = fragment_of<EB>(w_lo);
-                        contract(a);
-                        if (rows > 16) {                     // wave-uniform
-                            a[0] = fragment_of<EB>(w_hi);
-                            contract(a);
+#pragma unroll
+                        for (int x = 0; x < TR / 16; ++x) {
+                            if (x == 0 || rows > 16 * x) {       // wave-uniform
+                                const unsigned w_x[2] = {part[x].x, part[x].y};
+                                a[0] = fragment_of<EB>(w_x);
+                                contract(a);
+                            }
                         }
                     } else {
                         if constexpr (D == 32) {
